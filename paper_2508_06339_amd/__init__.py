@@ -1,0 +1,10 @@
+"""svb: singular values on one MI355X by two-stage reduction to bidiagonal form.
+
+Thin Python binding over the C-ABI library libsvb.so (include/svb.h).  The
+binding only marshals arguments; every step runs in the library.
+"""
+from .binding import (  # noqa: F401
+    SVB_F64, SVB_F32, SVB_F16, SVB_BF16, SVB_OK, SvbError, library_path, load_library,
+    svb_workspace_bytes, svb_svdvals, svb_ge2gb, svb_gb2bd, svb_bdsvals, svb_last_timings,
+    svb_status_string, svdvals, dtype_code,
+)

@@ -1,0 +1,149 @@
+"""ctypes binding of libsvb.so.  Same names as the C entry points (include/svb.h).
+
+Device buffers are torch tensors (PyTorch supplies device memory and streams
+only); host buffers are numpy arrays.  There is no fallback: if the library
+is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+SVB_F64, SVB_F32, SVB_F16, SVB_BF16 = 0, 1, 2, 3
+SVB_OK = 0
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libsvb.so")
+_lib = None
+
+_i64 = ctypes.c_int64
+_vp = ctypes.c_void_p
+_szp = ctypes.POINTER(ctypes.c_size_t)
+_dp = ctypes.POINTER(ctypes.c_double)
+
+
+class SvbError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = int(status)
+        super().__init__(f"{where}: {svb_status_string(status)} (status {status})")
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libsvb.so (built in-tree by paper_2508_06339_amd.build); raises if absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise FileNotFoundError(
+            f"{_LIB_PATH} not found: build it with `python -m paper_2508_06339_amd.build` "
+            "(there is no CPU fallback)")
+    lib = ctypes.CDLL(_LIB_PATH)
+    lib.svb_workspace_bytes.argtypes = [ctypes.c_int, _i64, _i64, ctypes.c_int, _szp, _szp]
+    lib.svb_workspace_bytes.restype = ctypes.c_int
+    lib.svb_svdvals.argtypes = [ctypes.c_int, _i64, _i64, _vp, _i64, _vp, ctypes.c_int, _vp,
+                                ctypes.c_size_t, _vp]
+    lib.svb_svdvals.restype = ctypes.c_int
+    lib.svb_ge2gb.argtypes = [ctypes.c_int, _i64, _i64, _vp, _i64, ctypes.c_int, _vp, _i64, _vp,
+                              ctypes.c_size_t, _vp]
+    lib.svb_ge2gb.restype = ctypes.c_int
+    lib.svb_gb2bd.argtypes = [ctypes.c_int, _i64, ctypes.c_int, _vp, _i64, _vp, _vp, _vp,
+                              ctypes.c_size_t, _vp]
+    lib.svb_gb2bd.restype = ctypes.c_int
+    lib.svb_bdsvals.argtypes = [_i64, _dp, _dp, _dp]
+    lib.svb_bdsvals.restype = ctypes.c_int
+    lib.svb_last_timings.argtypes = [_dp, _dp, _dp]
+    lib.svb_last_timings.restype = ctypes.c_int
+    lib.svb_status_string.argtypes = [ctypes.c_int]
+    lib.svb_status_string.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def svb_status_string(status: int) -> str:
+    return load_library().svb_status_string(int(status)).decode()
+
+
+def dtype_code(torch_dtype) -> int:
+    import torch
+    return {torch.float64: SVB_F64, torch.float32: SVB_F32, torch.float16: SVB_F16,
+            torch.bfloat16: SVB_BF16}[torch_dtype]
+
+
+def _ptr(t):
+    return _vp(0) if t is None else _vp(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return _vp(torch.cuda.current_stream().cuda_stream)
+    return _vp(int(stream))
+
+
+def svb_workspace_bytes(dt: int, m: int, n: int, nb: int):
+    """Returns (status, dev_bytes, host_bytes)."""
+    dev = ctypes.c_size_t(0)
+    host = ctypes.c_size_t(0)
+    rc = load_library().svb_workspace_bytes(dt, m, n, nb, ctypes.byref(dev), ctypes.byref(host))
+    return rc, dev.value, host.value
+
+
+def svb_svdvals(dt, m, n, A_dev, lda, S_out_host: np.ndarray, nb, work_dev, work_bytes, stream=None) -> int:
+    return load_library().svb_svdvals(dt, m, n, _ptr(A_dev), lda, _vp(S_out_host.ctypes.data), nb,
+                                      _ptr(work_dev), work_bytes, _stream(stream))
+
+
+def svb_ge2gb(dt, m, n, A_dev, lda, nb, band_dev, ldab, work_dev, work_bytes, stream=None) -> int:
+    return load_library().svb_ge2gb(dt, m, n, _ptr(A_dev), lda, nb, _ptr(band_dev), ldab,
+                                    _ptr(work_dev), work_bytes, _stream(stream))
+
+
+def svb_gb2bd(band_dt, n, nb, band_dev, ldab, d_dev, e_dev, work_dev, work_bytes, stream=None) -> int:
+    return load_library().svb_gb2bd(band_dt, n, nb, _ptr(band_dev), ldab, _ptr(d_dev), _ptr(e_dev),
+                                    _ptr(work_dev), work_bytes, _stream(stream))
+
+
+def svb_bdsvals(n: int, d: np.ndarray, e: np.ndarray, sigma: np.ndarray) -> int:
+    def p(a):
+        return a.ctypes.data_as(_dp) if a is not None and a.size else ctypes.cast(None, _dp)
+    return load_library().svb_bdsvals(n, p(d), p(e), p(sigma))
+
+
+def svb_last_timings():
+    t = [ctypes.c_double(0.0) for _ in range(3)]
+    load_library().svb_last_timings(*[ctypes.byref(x) for x in t])
+    return tuple(x.value for x in t)
+
+
+def svdvals(A, nb: int = 64, overwrite: bool = False, work=None):
+    """Singular values (descending, numpy) of a square torch tensor on the GPU.
+
+    The tensor's memory is read as a column-major n x n matrix with lda = n; a
+    row-major tensor is therefore seen transposed, which has the same singular
+    values.  Marshals arguments for svb_svdvals; allocates the workspace with
+    torch unless one is passed in.
+    """
+    import torch
+    if A.dim() != 2 or A.shape[0] != A.shape[1] or not A.is_cuda:
+        raise ValueError("expected a square 2-D CUDA tensor")
+    if not (A.is_contiguous() or A.t().is_contiguous()):
+        raise ValueError("expected a dense row- or column-major tensor")
+    n = A.shape[0]
+    dt = dtype_code(A.dtype)
+    buf = A if overwrite else A.clone(memory_format=torch.preserve_format)
+    rc, dev_bytes, _ = svb_workspace_bytes(dt, n, n, nb)
+    if rc != SVB_OK:
+        raise SvbError(rc, "svb_workspace_bytes")
+    if work is None:
+        work = torch.empty(dev_bytes, dtype=torch.uint8, device=A.device)
+    out = np.empty(n, dtype=np.float64 if dt == SVB_F64 else np.float32)
+    rc = svb_svdvals(dt, n, n, buf, n, out, nb, work, work.numel())
+    if rc != SVB_OK:
+        raise SvbError(rc, "svb_svdvals")
+    return out

@@ -1,0 +1,261 @@
+// Stage 1, panel factorisation (paper Section 3.1 Algorithm 1 lines 2/4 and
+// Section 3.2 "Panel Factorization", Algorithm 3).
+//
+// A panel (the block column below a diagonal tile in a QR sweep, the block row
+// right of it in an LQ sweep) is copied, transposed for LQ, into a contiguous
+// work panel.  Its nb-row tiles ("chunks") are grouped into domains of g
+// chunks; every domain is factored by one workgroup with Householder
+// reflectors (GEQRT extended to several tiles), the R factors of the domains
+// are stacked into the next level's panel and factored the same way (the
+// role of TSQRT: annihilating tiles against an already triangular one), until
+// one R is left.  Each domain also produces the compact-WY pair (V, Y = V T)
+// that the trailing update applies with matrix products.
+#include "svb_internal.h"
+
+namespace svb {
+
+template <typename C> __device__ __forceinline__ C wave_sum(C v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+    return v;
+}
+
+// ---------------------------------------------------------------- gather
+// QR sweep: P[i, j] = A[row0 + i, col0 + j];  LQ sweep: P[i, j] = A[row0 + j, col0 + i]
+// for i < len, j < nb.  Block (32, 8) moves a 32 x 32 tile through LDS so that
+// both the read and the write run along contiguous memory.
+template <typename T, typename C>
+__global__ __launch_bounds__(256) void panel_gather_kernel(const T* __restrict__ A, int64_t lda,
+                                                           int64_t row0, int64_t col0, int lq,
+                                                           int64_t len, int nb,
+                                                           C* __restrict__ P, int64_t ldp)
+{
+    __shared__ C tile[32][33];
+    const int64_t i0 = (int64_t)blockIdx.x * 32;
+    const int j0 = blockIdx.y * 32;
+    const int tx = threadIdx.x, ty = threadIdx.y;
+    if (!lq) {
+        for (int jj = ty; jj < 32; jj += 8) {
+            int64_t i = i0 + tx;
+            if (i < len) P[i + (int64_t)(j0 + jj) * ldp] = ld_as<C, T>(&A[(row0 + i) + (col0 + j0 + jj) * lda]);
+        }
+    } else {
+        // read: tx runs along j (rows of A, contiguous), ty along i (columns of A)
+        for (int ii = ty; ii < 32; ii += 8) {
+            int64_t i = i0 + ii;
+            if (i < len) tile[ii][tx] = ld_as<C, T>(&A[(row0 + j0 + tx) + (col0 + i) * lda]);
+        }
+        __syncthreads();
+        for (int jj = ty; jj < 32; jj += 8) {
+            int64_t i = i0 + tx;
+            if (i < len) P[i + (int64_t)(j0 + jj) * ldp] = tile[tx][jj];
+        }
+    }
+}
+
+template <typename T, typename C>
+void launch_panel_gather(const T* A, int64_t lda, int64_t row0, int64_t col0, bool lq,
+                         int64_t len, int nb, C* P, int64_t ldp, hipStream_t s)
+{
+    dim3 grid((unsigned)((len + 31) / 32), (unsigned)(nb / 32));
+    dim3 block(32, 8);
+    hipLaunchKernelGGL((panel_gather_kernel<T, C>), grid, block, 0, s, A, lda, row0, col0,
+                       lq ? 1 : 0, len, nb, P, ldp);
+}
+
+// ---------------------------------------------------------------- domain QR
+// One workgroup factors one domain (h = nch*NB rows, NB columns) in place in
+// the work panel.  Per column k (Algorithm 3's loop): the tail norm, the
+// reflector scalars, then every other column is visited once by one wave: a
+// column right of k gets the rank-one update, a column left of k (already a
+// reflector) yields the inner product needed for the next column of T.
+// Reflector convention: H = I - tau v v^T, v_k = 1, beta = -sign(alpha)*norm,
+// tau = (beta - alpha)/beta (equal to Algorithm 3's 2x^2/(x^2+|tail|^2)); a
+// zero tail gives tau = 0 instead of the paper's 10*eps rule.
+template <typename C, int NB, int NT>
+__global__ __launch_bounds__(NT) void panel_qr_kernel(C* __restrict__ P, int64_t ldp,
+                                                      C* __restrict__ Y, C* __restrict__ Tws,
+                                                      int chunks, int g,
+                                                      C* __restrict__ Pnext, int64_t ldnext)
+{
+    constexpr int NW = NT / kWave;
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    C* vs = reinterpret_cast<C*>(smem_raw);  // h entries
+    __shared__ C zs[NB];
+    __shared__ C red[NW];
+
+    const int d = blockIdx.x;
+    const int nch = min(g, chunks - d * g);
+    const int h = nch * NB;
+    C* Pd = P + (int64_t)d * g * NB;
+    C* Yd = Y + (int64_t)d * g * NB;
+    C* Td = Tws + (int64_t)d * NB * NB;
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = tid / kWave;
+
+    for (int k = 0; k < NB; ++k) {
+        C* colk = Pd + (int64_t)k * ldp;
+        // 1. squared norm of the tail, and the pivot
+        C ss = 0;
+        for (int i = k + 1 + tid; i < h; i += NT) {
+            C x = colk[i];
+            ss += x * x;
+        }
+        const C alpha = colk[k];
+        ss = wave_sum(ss);
+        if (lane == 0) red[wave] = ss;
+        __syncthreads();
+        ss = 0;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) ss += red[w];
+        C tau, beta, inv;
+        if (ss == (C)0) {
+            tau = 0;
+            beta = alpha;
+            inv = 0;
+        } else {
+            C nrm = sqrt(alpha * alpha + ss);
+            beta = alpha >= (C)0 ? -nrm : nrm;
+            tau = (beta - alpha) / beta;
+            inv = (C)1 / (alpha - beta);
+        }
+        // 2. v = (0.., 1, tail/(alpha-beta)) to LDS and in place
+        for (int i = tid; i < h; i += NT) {
+            C v = (i < k) ? (C)0 : ((i == k) ? (C)1 : colk[i] * inv);
+            vs[i] = v;
+            if (i > k) colk[i] = v;
+        }
+        if (tid == 0) colk[k] = beta;
+        __syncthreads();
+        // 3. one wave per column
+        const int i0 = (k / kWave) * kWave;
+        for (int j = wave; j < NB; j += NW) {
+            if (j == k) continue;
+            C* colj = Pd + (int64_t)j * ldp;
+            C dot = 0;
+            for (int i = i0 + lane; i < h; i += kWave) dot += vs[i] * colj[i];
+            dot = wave_sum(dot);
+            if (j < k) {
+                if (lane == 0) zs[j] = dot;
+            } else {
+                const C f = tau * dot;
+                for (int i = i0 + lane; i < h; i += kWave) {
+                    C v = vs[i];
+                    if (v != (C)0) colj[i] -= f * v;
+                }
+            }
+        }
+        __syncthreads();
+        // 4. column k of T: T[0:k,k] = -tau * T[0:k,0:k] * (V[:,0:k]^T v_k), T[k,k] = tau
+        if (tid < k) {
+            C acc = 0;
+            for (int j = tid; j < k; ++j) acc += Td[tid + j * NB] * zs[j];
+            Td[tid + k * NB] = -tau * acc;
+        } else if (tid == k) {
+            Td[k + k * NB] = tau;
+        }
+    }
+    __syncthreads();
+    // R (upper triangle of the top tile) becomes chunk d of the next level's panel
+    for (int idx = tid; idx < NB * NB; idx += NT) {
+        const int i = idx % NB, j = idx / NB;
+        Pnext[((int64_t)d * NB + i) + (int64_t)j * ldnext] = (i <= j) ? Pd[i + (int64_t)j * ldp] : (C)0;
+    }
+    __syncthreads();
+    // make V explicit: unit diagonal, zeros above it
+    for (int idx = tid; idx < NB * NB; idx += NT) {
+        const int i = idx % NB, j = idx / NB;
+        if (i < j) Pd[i + (int64_t)j * ldp] = 0;
+        else if (i == j) Pd[i + (int64_t)j * ldp] = 1;
+    }
+    __syncthreads();
+    // Y = V T (T upper triangular)
+    for (int i = tid; i < h; i += NT) {
+        for (int k = 0; k < NB; ++k) {
+            C acc = 0;
+            for (int j = 0; j <= k; ++j) acc += Pd[i + (int64_t)j * ldp] * Td[j + k * NB];
+            Yd[i + (int64_t)k * ldp] = acc;
+        }
+    }
+}
+
+template <typename C>
+void launch_panel_qr(int nb, C* P, int64_t ldp, C* Y, C* Tws, int chunks, int g,
+                     C* Pnext, int64_t ldnext, int* /*err*/, hipStream_t s)
+{
+    const int domains = (chunks + g - 1) / g;
+    const size_t smem = (size_t)g * nb * sizeof(C);
+    constexpr int NT = 512;
+    switch (nb) {
+    case 32:
+        hipLaunchKernelGGL((panel_qr_kernel<C, 32, NT>), dim3(domains), dim3(NT), smem, s, P, ldp, Y, Tws, chunks, g, Pnext, ldnext);
+        break;
+    case 64:
+        hipLaunchKernelGGL((panel_qr_kernel<C, 64, NT>), dim3(domains), dim3(NT), smem, s, P, ldp, Y, Tws, chunks, g, Pnext, ldnext);
+        break;
+    default:
+        hipLaunchKernelGGL((panel_qr_kernel<C, 128, NT>), dim3(domains), dim3(NT), smem, s, P, ldp, Y, Tws, chunks, g, Pnext, ldnext);
+        break;
+    }
+}
+
+// ---------------------------------------------------------------- R -> band
+// The last level's R is final: a QR sweep's R is the upper triangle of the
+// diagonal tile, an LQ sweep's R^T the lower triangle of the tile right of it
+// (Figure 1).  Together these triangles are exactly the band that stage 2
+// receives, so they are written straight into the packed band.
+template <typename C>
+__global__ __launch_bounds__(256) void scatter_r_kernel(const C* __restrict__ R, int64_t ldr, int nb,
+                                                        C* __restrict__ band, int64_t ldab,
+                                                        int64_t row0, int64_t col0, int lq)
+{
+    for (int idx = blockIdx.x * blockDim.x + threadIdx.x; idx < nb * nb; idx += gridDim.x * blockDim.x) {
+        const int i = idx % nb, j = idx / nb;
+        if (i > j) continue;
+        const C r = R[i + (int64_t)j * ldr];
+        const int64_t gi = lq ? row0 + j : row0 + i;
+        const int64_t gj = lq ? col0 + i : col0 + j;
+        band[(gi - gj + 2 * nb - 1) + gj * ldab] = r;
+    }
+}
+
+template <typename C>
+void launch_scatter_r(const C* R, int64_t ldr, int nb, C* band, int64_t ldab,
+                      int64_t row0, int64_t col0, bool lq, hipStream_t s)
+{
+    hipLaunchKernelGGL((scatter_r_kernel<C>), dim3((nb * nb + 255) / 256), dim3(256), 0, s, R, ldr,
+                       nb, band, ldab, row0, col0, lq ? 1 : 0);
+}
+
+template <typename C>
+__global__ __launch_bounds__(256) void band_clear_kernel(C* __restrict__ band, int64_t total)
+{
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+         i += (int64_t)gridDim.x * blockDim.x)
+        band[i] = 0;
+}
+
+template <typename C>
+void launch_band_clear(C* band, int64_t ldab, int64_t n, hipStream_t s)
+{
+    const int64_t total = ldab * n;
+    int blocks = (int)((total + 255) / 256);
+    if (blocks > 4096) blocks = 4096;
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL((band_clear_kernel<C>), dim3(blocks), dim3(256), 0, s, band, total);
+}
+
+// explicit instantiations
+template void launch_panel_gather<double, double>(const double*, int64_t, int64_t, int64_t, bool, int64_t, int, double*, int64_t, hipStream_t);
+template void launch_panel_gather<float, float>(const float*, int64_t, int64_t, int64_t, bool, int64_t, int, float*, int64_t, hipStream_t);
+template void launch_panel_gather<__half, float>(const __half*, int64_t, int64_t, int64_t, bool, int64_t, int, float*, int64_t, hipStream_t);
+template void launch_panel_qr<double>(int, double*, int64_t, double*, double*, int, int, double*, int64_t, int*, hipStream_t);
+template void launch_panel_qr<float>(int, float*, int64_t, float*, float*, int, int, float*, int64_t, int*, hipStream_t);
+template void launch_scatter_r<double>(const double*, int64_t, int, double*, int64_t, int64_t, int64_t, bool, hipStream_t);
+template void launch_scatter_r<float>(const float*, int64_t, int, float*, int64_t, int64_t, int64_t, bool, hipStream_t);
+template void launch_band_clear<double>(double*, int64_t, int64_t, hipStream_t);
+template void launch_band_clear<float>(float*, int64_t, int64_t, hipStream_t);
+
+}  // namespace svb

@@ -1,0 +1,161 @@
+// Stage 1, trailing-matrix update (paper Section 3.1 Algorithm 1 lines 3/6,
+// Section 3.2 "Trailing Submatrix Update", Algorithms 4 and 5).
+//
+// The paper applies the reflectors of a tile one at a time with scalar FMAs
+// (Algorithm 5).  Here the reflectors of a whole domain are applied at once in
+// compact-WY form: with Y = V T,
+//     QR sweep:  C <- Q^T C = C - V (Y^T C)      (reflectors from the left)
+//     LQ sweep:  C <- C Q   = C - (C Y) V^T      (reflectors from the right)
+// i.e. two matrix products per domain: W = Y^T C (kernel K1), C -= V W
+// (kernel K2).  Trailing-matrix element (p, q) lives at base + p*sp + q*sq;
+// p runs along the panel direction, q along the free direction, so the LQ
+// sweep is the QR sweep with (sp, sq) = (lda, 1) instead of (1, lda).
+//
+// A level's chunk ch covers panel rows ch*stride .. ch*stride + NB - 1
+// (stride = NB at level 0, NB*g^L above: the rows that hold the R factors of
+// the level below), and rows ch*NB .. of the level's V / Y panels.
+#include "svb_internal.h"
+
+namespace svb {
+
+// ------------------------------------------------------------------------
+// Reference implementation with plain FMAs (selected with impl = 0; kept as
+// the cross-check for the MFMA kernels).
+// ------------------------------------------------------------------------
+template <typename T, typename C, int NB, bool LQ>
+__global__ __launch_bounds__(256) void k1_simple(const T* __restrict__ Cb, int64_t sp, int64_t sq,
+                                                 int64_t qlen, const C* __restrict__ Y, int64_t ldp,
+                                                 int chunks, int g, int64_t stride, C* __restrict__ W)
+{
+    constexpr int TQ = 64, TK = 32, PER = NB / 4;
+    __shared__ C Ys[TK][NB + 1];
+    __shared__ C Cs[TK][TQ + 1];
+    const int d = blockIdx.y;
+    const int64_t q0 = (int64_t)blockIdx.x * TQ;
+    const int nch = min(g, chunks - d * g);
+    const int t = threadIdx.x;
+    const int q = t % TQ, grp = t / TQ;
+    C acc[PER];
+#pragma unroll
+    for (int u = 0; u < PER; ++u) acc[u] = 0;
+    for (int ch = 0; ch < nch; ++ch) {
+        const int64_t chg = (int64_t)d * g + ch;
+        for (int a0 = 0; a0 < NB; a0 += TK) {
+            for (int idx = t; idx < TK * NB; idx += 256) {
+                const int a = idx % TK, kk = idx / TK;
+                Ys[a][kk] = Y[(chg * NB + a0 + a) + (int64_t)kk * ldp];
+            }
+            for (int idx = t; idx < TK * TQ; idx += 256) {
+                int a, qq;
+                if (LQ) { qq = idx % TQ; a = idx / TQ; } else { a = idx % TK; qq = idx / TK; }
+                const int64_t p = chg * stride + a0 + a;
+                C v = 0;
+                if (q0 + qq < qlen) v = ld_as<C, T>(&Cb[p * sp + (q0 + qq) * sq]);
+                Cs[a][qq] = v;
+            }
+            __syncthreads();
+#pragma unroll 4
+            for (int a = 0; a < TK; ++a) {
+                const C c = Cs[a][q];
+#pragma unroll
+                for (int u = 0; u < PER; ++u) acc[u] += Ys[a][grp * PER + u] * c;
+            }
+            __syncthreads();
+        }
+    }
+    if (q0 + q < qlen) {
+        C* Wd = W + (int64_t)d * NB * qlen;
+#pragma unroll
+        for (int u = 0; u < PER; ++u) Wd[(grp * PER + u) + (q0 + q) * NB] = acc[u];
+    }
+}
+
+template <typename T, typename C, int NB, bool LQ>
+__global__ __launch_bounds__(256) void k2_simple(T* __restrict__ Cb, int64_t sp, int64_t sq,
+                                                 int64_t qlen, const C* __restrict__ V, int64_t ldp,
+                                                 int g, int64_t stride, const C* __restrict__ W)
+{
+    constexpr int TQ = 32, TK = 16, PER = NB / 8;
+    __shared__ C Vs[TK][NB + 1];
+    __shared__ C Ws[TK][TQ + 1];
+    __shared__ C Os[NB][TQ + 1];
+    const int64_t chg = blockIdx.y;
+    const int d = (int)(chg / g);
+    const int64_t q0 = (int64_t)blockIdx.x * TQ;
+    const int t = threadIdx.x;
+    const int q = t % TQ, grp = t / TQ;
+    const C* Wd = W + (int64_t)d * NB * qlen;
+    C acc[PER];
+#pragma unroll
+    for (int u = 0; u < PER; ++u) acc[u] = 0;
+    for (int k0 = 0; k0 < NB; k0 += TK) {
+        for (int idx = t; idx < TK * NB; idx += 256) {
+            const int a = idx % NB, kk = idx / NB;
+            Vs[kk][a] = V[(chg * NB + a) + (int64_t)(k0 + kk) * ldp];
+        }
+        for (int idx = t; idx < TK * TQ; idx += 256) {
+            const int kk = idx % TK, qq = idx / TK;
+            Ws[kk][qq] = (q0 + qq < qlen) ? Wd[(k0 + kk) + (q0 + qq) * NB] : (C)0;
+        }
+        __syncthreads();
+#pragma unroll 4
+        for (int kk = 0; kk < TK; ++kk) {
+            const C w = Ws[kk][q];
+#pragma unroll
+            for (int u = 0; u < PER; ++u) acc[u] += Vs[kk][grp * PER + u] * w;
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int u = 0; u < PER; ++u) Os[grp * PER + u][q] = acc[u];
+    __syncthreads();
+    for (int idx = t; idx < NB * TQ; idx += 256) {
+        int a, qq;
+        if (LQ) { qq = idx % TQ; a = idx / TQ; } else { a = idx % NB; qq = idx / NB; }
+        if (q0 + qq < qlen) {
+            T* ptr = &Cb[(chg * stride + a) * sp + (q0 + qq) * sq];
+            st_as<T, C>(ptr, ld_as<C, T>(ptr) - Os[a][qq]);
+        }
+    }
+}
+
+template <typename T, typename C, int NB, bool LQ>
+static void update_simple(T* Cb, int64_t lda, int64_t qlen, const C* V, const C* Y, int64_t ldp,
+                          int chunks, int g, int64_t stride, C* W, hipStream_t s)
+{
+    const int64_t sp = LQ ? lda : 1, sq = LQ ? 1 : lda;
+    const int domains = (chunks + g - 1) / g;
+    dim3 g1((unsigned)((qlen + 63) / 64), (unsigned)domains);
+    hipLaunchKernelGGL((k1_simple<T, C, NB, LQ>), g1, dim3(256), 0, s, Cb, sp, sq, qlen, Y, ldp,
+                       chunks, g, stride, W);
+    dim3 g2((unsigned)((qlen + 31) / 32), (unsigned)chunks);
+    hipLaunchKernelGGL((k2_simple<T, C, NB, LQ>), g2, dim3(256), 0, s, Cb, sp, sq, qlen, V, ldp, g,
+                       stride, W);
+}
+
+template <typename T, typename C, int NB>
+static void update_nb(bool lq, T* Cb, int64_t lda, int64_t qlen, const C* V, const C* Y,
+                      int64_t ldp, int chunks, int g, int64_t stride, C* W, int impl, hipStream_t s)
+{
+    (void)impl;
+    if (lq) update_simple<T, C, NB, true>(Cb, lda, qlen, V, Y, ldp, chunks, g, stride, W, s);
+    else update_simple<T, C, NB, false>(Cb, lda, qlen, V, Y, ldp, chunks, g, stride, W, s);
+}
+
+template <typename T, typename C>
+void launch_update(int nb, bool lq, T* Cbase, int64_t lda, int64_t qlen, const C* V, const C* Y,
+                   int64_t ldp, int chunks, int g, int64_t stride, C* W, int impl, hipStream_t s)
+{
+    if (qlen <= 0) return;
+    switch (nb) {
+    case 32: update_nb<T, C, 32>(lq, Cbase, lda, qlen, V, Y, ldp, chunks, g, stride, W, impl, s); break;
+    case 64: update_nb<T, C, 64>(lq, Cbase, lda, qlen, V, Y, ldp, chunks, g, stride, W, impl, s); break;
+    default: update_nb<T, C, 128>(lq, Cbase, lda, qlen, V, Y, ldp, chunks, g, stride, W, impl, s); break;
+    }
+}
+
+template void launch_update<double, double>(int, bool, double*, int64_t, int64_t, const double*, const double*, int64_t, int, int, int64_t, double*, int, hipStream_t);
+template void launch_update<float, float>(int, bool, float*, int64_t, int64_t, const float*, const float*, int64_t, int, int, int64_t, float*, int, hipStream_t);
+template void launch_update<__half, float>(int, bool, __half*, int64_t, int64_t, const float*, const float*, int64_t, int, int, int64_t, float*, int, hipStream_t);
+
+}  // namespace svb

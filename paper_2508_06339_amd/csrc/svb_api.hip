@@ -1,0 +1,304 @@
+// C-ABI entry points and the host-side stage driver.
+#include <chrono>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <vector>
+
+#include "svb_internal.h"
+
+namespace svb {
+
+int env_int(const char* name, int dflt)
+{
+    const char* v = std::getenv(name);
+    return (v && *v) ? std::atoi(v) : dflt;
+}
+
+namespace {
+
+inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+size_t compute_size(svb_dtype dt) { return dt == SVB_F64 ? 8 : 4; }
+size_t storage_size(svb_dtype dt) { return dt == SVB_F64 ? 8 : (dt == SVB_F32 ? 4 : 2); }
+
+int check_shape(svb_dtype dt, int64_t m, int64_t n, int nb)
+{
+    if (m < 0 || n < 0) return SVB_ERR_ARG;
+    if (dt != SVB_F64 && dt != SVB_F32 && dt != SVB_F16) return SVB_ERR_UNSUPPORTED;
+    if (nb != 32 && nb != 64 && nb != 128) return SVB_ERR_UNSUPPORTED;
+    if (m != n || n <= 0 || n % nb != 0) return SVB_ERR_UNSUPPORTED;
+    return SVB_OK;
+}
+
+// chunks-per-domain of the panel tree
+int domain_chunks(int nb)
+{
+    int g = env_int("SVB_DOMAIN_CHUNKS", 0);
+    if (g >= 2 && g <= 64) return g;
+    return nb == 128 ? 8 : (nb == 64 ? 8 : 8);
+}
+constexpr int kMinDomainChunks = 2;  // workspace is sized for any g >= this
+
+// Workspace layout (element counts in the compute type).
+struct Carve {
+    size_t panel_elems;  // V panels of all levels
+    size_t w_elems;      // W of the largest level
+    size_t t_elems;      // T factors of one level
+    size_t band_elems, de_elems;
+    size_t off_V, off_Y, off_W, off_T, off_band, off_d, off_e, off_err, total;
+};
+
+Carve carve(svb_dtype dt, int64_t n, int nb)
+{
+    Carve c{};
+    const size_t cs = compute_size(dt);
+    // levels shrink by >= kMinDomainChunks: sum of panel rows <= 2n (+ one chunk per level)
+    c.panel_elems = (size_t)(2 * n + (int64_t)(kMaxLevels + 2) * nb) * nb;
+    c.w_elems = (size_t)n * (size_t)n / kMinDomainChunks + (size_t)n * nb;
+    c.t_elems = (size_t)(n / nb + 1) * nb * nb;
+    c.band_elems = (size_t)(3 * nb) * (size_t)n;
+    c.de_elems = (size_t)n;
+    size_t off = 0;
+    c.off_V = off; off += align_up(c.panel_elems * cs);
+    c.off_Y = off; off += align_up(c.panel_elems * cs);
+    c.off_W = off; off += align_up(c.w_elems * cs);
+    c.off_T = off; off += align_up(c.t_elems * cs);
+    c.off_band = off; off += align_up(c.band_elems * cs);
+    c.off_d = off; off += align_up(c.de_elems * cs);
+    c.off_e = off; off += align_up(c.de_elems * cs);
+    c.off_err = off; off += 256;
+    off += chase_workspace_bytes(n, nb);
+    c.total = off;
+    return c;
+}
+
+int build_levels(int64_t len, int nb, int g, Level* lv)
+{
+    int nl = 0;
+    int chunks = (int)(len / nb);
+    int64_t stride = nb, poff = 0;
+    for (;;) {
+        Level& L = lv[nl];
+        L.chunks = chunks;
+        L.domains = (chunks + g - 1) / g;
+        L.stride = stride;
+        L.poff = poff;
+        L.ldp = (int64_t)chunks * nb;
+        L.woff = 0;
+        poff += L.ldp * nb;
+        ++nl;
+        if (L.domains == 1 || nl == kMaxLevels) break;
+        chunks = L.domains;
+        stride *= g;
+    }
+    return nl;
+}
+
+struct Timings { double s1 = 0, s2 = 0, s3 = 0; } g_last;
+
+template <typename T, typename C>
+int ge2gb_impl(int64_t n, T* A, int64_t lda, int nb, C* band, int64_t ldab, unsigned char* work,
+               const Carve& cv, hipStream_t s)
+{
+    C* Vb = reinterpret_cast<C*>(work + cv.off_V);
+    C* Yb = reinterpret_cast<C*>(work + cv.off_Y);
+    C* Wb = reinterpret_cast<C*>(work + cv.off_W);
+    C* Tb = reinterpret_cast<C*>(work + cv.off_T);
+    int* err = reinterpret_cast<int*>(work + cv.off_err);
+    const int g = domain_chunks(nb);
+    const int impl = env_int("SVB_UPDATE_IMPL", 1);
+    const int64_t N = n / nb;
+    Level lv[kMaxLevels];
+
+    launch_band_clear<C>(band, ldab, n, s);
+    for (int64_t k = 0; k < N; ++k) {
+        for (int half = 0; half < 2; ++half) {
+            const bool lq = half == 1;
+            if (lq && k == N - 1) break;
+            // panel: QR -> rows k*nb.., columns k*nb..; LQ -> rows k*nb.., columns (k+1)*nb..
+            const int64_t row0 = k * nb;
+            const int64_t col0 = lq ? (k + 1) * nb : k * nb;
+            const int64_t len = lq ? n - (k + 1) * nb : n - k * nb;
+            const int nl = build_levels(len, nb, g, lv);
+            launch_panel_gather<T, C>(A, lda, row0, col0, lq, len, nb, Vb + lv[0].poff, lv[0].ldp, s);
+            for (int L = 0; L < nl; ++L) {
+                // the R factors of level L are stacked into level L+1's panel; the last
+                // level's single R lands right behind it
+                const int64_t next_off = lv[L].poff + lv[L].ldp * nb;
+                const int64_t ldnext = (int64_t)lv[L].domains * nb;
+                launch_panel_qr<C>(nb, Vb + lv[L].poff, lv[L].ldp, Yb + lv[L].poff, Tb, lv[L].chunks, g,
+                                   Vb + next_off, ldnext, err, s);
+                if (L == nl - 1)
+                    launch_scatter_r<C>(Vb + next_off, ldnext, nb, band, ldab, row0, col0, lq, s);
+            }
+            // trailing matrix: QR -> rows k*nb.., columns (k+1)*nb..;  LQ -> rows (k+1)*nb.., columns (k+1)*nb..
+            const int64_t qlen = n - (k + 1) * nb;
+            if (qlen > 0) {
+                T* Cb = lq ? A + (k + 1) * nb + (k + 1) * nb * lda : A + k * nb + (k + 1) * nb * lda;
+                for (int L = 0; L < nl; ++L)
+                    launch_update<T, C>(nb, lq, Cb, lda, qlen, Vb + lv[L].poff, Yb + lv[L].poff, lv[L].ldp,
+                                        lv[L].chunks, g, lv[L].stride, Wb, impl, s);
+            }
+        }
+    }
+    return hipGetLastError() == hipSuccess ? SVB_OK : SVB_ERR_DEVICE;
+}
+
+int ge2gb_dispatch(svb_dtype dt, int64_t n, void* A, int64_t lda, int nb, void* band, int64_t ldab,
+                   void* work, const Carve& cv, hipStream_t s)
+{
+    unsigned char* w = static_cast<unsigned char*>(work);
+    switch (dt) {
+    case SVB_F64: return ge2gb_impl<double, double>(n, (double*)A, lda, nb, (double*)band, ldab, w, cv, s);
+    case SVB_F32: return ge2gb_impl<float, float>(n, (float*)A, lda, nb, (float*)band, ldab, w, cv, s);
+    case SVB_F16: return ge2gb_impl<__half, float>(n, (__half*)A, lda, nb, (float*)band, ldab, w, cv, s);
+    default: return SVB_ERR_UNSUPPORTED;
+    }
+}
+
+}  // namespace
+}  // namespace svb
+
+using namespace svb;
+
+extern "C" {
+
+int svb_workspace_bytes(svb_dtype dt, int64_t m, int64_t n, int nb, size_t* dev_bytes, size_t* host_bytes)
+{
+    const int rc = check_shape(dt, m, n, nb);
+    if (rc != SVB_OK) return rc;
+    const Carve cv = carve(dt, n, nb);
+    if (dev_bytes) *dev_bytes = cv.total;
+    if (host_bytes) *host_bytes = 0;
+    return SVB_OK;
+}
+
+int svb_ge2gb(svb_dtype dt, int64_t m, int64_t n, void* A_dev, int64_t lda, int nb, void* band_dev,
+              int64_t ldab, void* work_dev, size_t work_bytes, void* stream)
+{
+    const int rc = check_shape(dt, m, n, nb);
+    if (rc != SVB_OK) return rc;
+    if (!A_dev || !band_dev || !work_dev || lda < m || ldab < 3 * (int64_t)nb) return SVB_ERR_ARG;
+    const Carve cv = carve(dt, n, nb);
+    if (work_bytes < cv.total) return SVB_ERR_WORKSPACE;
+    return ge2gb_dispatch(dt, n, A_dev, lda, nb, band_dev, ldab, work_dev, cv, (hipStream_t)stream);
+}
+
+int svb_gb2bd(svb_dtype band_dt, int64_t n, int nb, void* band_dev, int64_t ldab, void* d_dev,
+              void* e_dev, void* work_dev, size_t work_bytes, void* stream)
+{
+    if (n < 0) return SVB_ERR_ARG;
+    if (band_dt != SVB_F64 && band_dt != SVB_F32) return SVB_ERR_UNSUPPORTED;
+    if (nb != 32 && nb != 64 && nb != 128) return SVB_ERR_UNSUPPORTED;
+    if (n == 0) return SVB_OK;
+    if (!band_dev || !d_dev || !e_dev || ldab < 3 * (int64_t)nb) return SVB_ERR_ARG;
+    if (work_bytes < chase_workspace_bytes(n, nb)) return SVB_ERR_WORKSPACE;
+    if (chase_workspace_bytes(n, nb) > 0 && !work_dev) return SVB_ERR_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    if (band_dt == SVB_F64)
+        return run_chase<double>(n, nb, (double*)band_dev, ldab, (double*)d_dev, (double*)e_dev, work_dev, work_bytes, s);
+    return run_chase<float>(n, nb, (float*)band_dev, ldab, (float*)d_dev, (float*)e_dev, work_dev, work_bytes, s);
+}
+
+int svb_bdsvals(int64_t n, const double* d, const double* e, double* sigma)
+{
+    return host_bdsvals(n, d, e, sigma);
+}
+
+int svb_svdvals(svb_dtype dt, int64_t m, int64_t n, void* A_dev, int64_t lda, void* S_out_host, int nb,
+                void* work_dev, size_t work_bytes, void* stream)
+{
+    int rc = check_shape(dt, m, n, nb);
+    if (rc != SVB_OK) return rc;
+    if (!A_dev || !S_out_host || !work_dev || lda < m) return SVB_ERR_ARG;
+    const Carve cv = carve(dt, n, nb);
+    if (work_bytes < cv.total) return SVB_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    unsigned char* w = static_cast<unsigned char*>(work_dev);
+    void* band = w + cv.off_band;
+    void* dd = w + cv.off_d;
+    void* de = w + cv.off_e;
+    const int64_t ldab = 3 * (int64_t)nb;
+    const svb_dtype bdt = dt == SVB_F64 ? SVB_F64 : SVB_F32;
+
+    hipEvent_t ev0, ev1, ev2;
+    if (hipEventCreate(&ev0) != hipSuccess || hipEventCreate(&ev1) != hipSuccess ||
+        hipEventCreate(&ev2) != hipSuccess)
+        return SVB_ERR_DEVICE;
+    (void)hipEventRecord(ev0, s);
+    rc = ge2gb_dispatch(dt, n, A_dev, lda, nb, band, ldab, work_dev, cv, s);
+    (void)hipEventRecord(ev1, s);
+    if (rc == SVB_OK) {
+        void* cw = w + cv.off_err + 256;
+        rc = svb_gb2bd(bdt, n, nb, band, ldab, dd, de, cw, chase_workspace_bytes(n, nb), s);
+    }
+    (void)hipEventRecord(ev2, s);
+    std::vector<double> hd((size_t)n), he((size_t)n), hs((size_t)n);
+    if (rc == SVB_OK) {
+        const size_t cs = compute_size(dt);
+        std::vector<unsigned char> raw(2 * (size_t)n * cs);
+        if (hipMemcpyAsync(raw.data(), dd, (size_t)n * cs, hipMemcpyDeviceToHost, s) != hipSuccess ||
+            hipMemcpyAsync(raw.data() + (size_t)n * cs, de, (size_t)n * cs, hipMemcpyDeviceToHost, s) != hipSuccess ||
+            hipStreamSynchronize(s) != hipSuccess) {
+            rc = SVB_ERR_DEVICE;
+        } else if (dt == SVB_F64) {
+            std::memcpy(hd.data(), raw.data(), (size_t)n * 8);
+            std::memcpy(he.data(), raw.data() + (size_t)n * 8, (size_t)n * 8);
+        } else {
+            const float* fd = reinterpret_cast<const float*>(raw.data());
+            for (int64_t i = 0; i < n; ++i) {
+                hd[(size_t)i] = fd[i];
+                he[(size_t)i] = fd[n + i];
+            }
+        }
+    } else {
+        (void)hipStreamSynchronize(s);
+    }
+    float ms1 = 0, ms2 = 0;
+    (void)hipEventElapsedTime(&ms1, ev0, ev1);
+    (void)hipEventElapsedTime(&ms2, ev1, ev2);
+    (void)hipEventDestroy(ev0);
+    (void)hipEventDestroy(ev1);
+    (void)hipEventDestroy(ev2);
+    if (rc == SVB_OK && hipGetLastError() != hipSuccess) rc = SVB_ERR_DEVICE;
+    double t3 = 0;
+    if (rc == SVB_OK) {
+        const auto t0 = std::chrono::steady_clock::now();
+        rc = host_bdsvals(n, hd.data(), he.data(), hs.data());
+        t3 = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
+        if (rc == SVB_OK) {
+            if (dt == SVB_F64) std::memcpy(S_out_host, hs.data(), (size_t)n * 8);
+            else
+                for (int64_t i = 0; i < n; ++i) static_cast<float*>(S_out_host)[i] = (float)hs[(size_t)i];
+        }
+    }
+    g_last.s1 = ms1 * 1e-3;
+    g_last.s2 = ms2 * 1e-3;
+    g_last.s3 = t3;
+    return rc;
+}
+
+int svb_last_timings(double* t_stage1, double* t_stage2, double* t_stage3)
+{
+    if (t_stage1) *t_stage1 = g_last.s1;
+    if (t_stage2) *t_stage2 = g_last.s2;
+    if (t_stage3) *t_stage3 = g_last.s3;
+    return SVB_OK;
+}
+
+const char* svb_status_string(int status)
+{
+    switch (status) {
+    case SVB_OK: return "ok";
+    case SVB_ERR_ARG: return "invalid argument";
+    case SVB_ERR_UNSUPPORTED: return "unsupported shape, tile size or dtype";
+    case SVB_ERR_WORKSPACE: return "workspace too small";
+    case SVB_ERR_DEVICE: return "HIP error";
+    case SVB_ERR_NOCONV: return "bidiagonal solver did not converge";
+    case SVB_ERR_NONFINITE: return "non-finite value in the bidiagonal";
+    default: return "unknown status";
+    }
+}
+
+}  // extern "C"

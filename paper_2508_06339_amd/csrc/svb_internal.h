@@ -1,0 +1,82 @@
+// Internal declarations shared by the HIP translation units of libsvb.
+// gfx950 only; wavefront size 64.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "../../include/svb.h"
+
+namespace svb {
+
+constexpr int kWave = 64;
+
+// Storage <-> compute conversions.  f16 is a storage type only: products and
+// sums are formed in f32 (the paper's treatment of half precision, Section 4.3).
+template <typename T> struct compute_of { using type = T; };
+template <> struct compute_of<__half> { using type = float; };
+
+template <typename C, typename T> __device__ __forceinline__ C ld_as(const T* p) { return (C)(*p); }
+template <> __device__ __forceinline__ float ld_as<float, __half>(const __half* p) { return __half2float(*p); }
+template <typename T, typename C> __device__ __forceinline__ void st_as(T* p, C v) { *p = (T)v; }
+template <> __device__ __forceinline__ void st_as<__half, float>(__half* p, float v) { *p = __float2half(v); }
+
+// Geometry of one half-sweep's panel tree (Section 3.1: GEQRT on the first
+// tile, then the tiles below are annihilated; here the tiles of a panel are
+// grouped into domains that are factored independently and merged level by
+// level, each level stacking the R factors of the level below).
+struct Level {
+    int chunks;        // number of nb-row chunks at this level
+    int domains;       // ceil(chunks / g)
+    int64_t stride;    // distance in panel rows between consecutive chunks: nb * g^level
+    int64_t poff;      // element offset of this level's panel inside the panel buffers
+    int64_t ldp;       // leading dimension of this level's panel = chunks * nb
+    int64_t woff;      // element offset of this level's W inside the W buffer
+};
+constexpr int kMaxLevels = 12;
+
+struct Orient {
+    // address of trailing-matrix element (p, q): base + p*sp + q*sq, where p runs along
+    // the panel direction (rows for a QR sweep, columns for an LQ sweep) and q
+    // along the free direction.
+    int64_t sp, sq;
+};
+
+// ---- stage 1, panel ---------------------------------------------------------
+template <typename T, typename C>
+void launch_panel_gather(const T* A, int64_t lda, int64_t row0, int64_t col0, bool lq,
+                         int64_t len, int nb, C* P, int64_t ldp, hipStream_t s);
+
+template <typename C>
+void launch_panel_qr(int nb, C* P, int64_t ldp, C* Y, C* Tws, int chunks, int g,
+                     C* Pnext, int64_t ldnext, int* err, hipStream_t s);
+
+template <typename C>
+void launch_scatter_r(const C* R, int64_t ldr, int nb, C* band, int64_t ldab,
+                      int64_t row0, int64_t col0, bool lq, hipStream_t s);
+
+template <typename C>
+void launch_band_clear(C* band, int64_t ldab, int64_t n, hipStream_t s);
+
+// ---- stage 1, trailing update ----------------------------------------------
+// W_d = Y_d^T C_d for every domain d of a level, then C_d -= V_d W_d
+// (QR orientation; the LQ orientation is the same with p/q swapped).
+template <typename T, typename C>
+void launch_update(int nb, bool lq, T* Cbase, int64_t lda, int64_t qlen,
+                   const C* V, const C* Y, int64_t ldp, int chunks, int g, int64_t stride,
+                   C* W, int impl, hipStream_t s);
+
+// ---- stage 2 -----------------------------------------------------------------
+template <typename C>
+int run_chase(int64_t n, int nb, C* band, int64_t ldab, C* d, C* e,
+              void* work, size_t work_bytes, hipStream_t s);
+size_t chase_workspace_bytes(int64_t n, int nb);
+
+// ---- stage 3 (host) -----------------------------------------------------------
+int host_bdsvals(int64_t n, const double* d, const double* e, double* sigma);
+
+int env_int(const char* name, int dflt);
+
+}  // namespace svb
