@@ -59,6 +59,12 @@ def load_library():
     lib.svb_bdsvals.restype = ctypes.c_int
     lib.svb_last_timings.argtypes = [_dp, _dp, _dp]
     lib.svb_last_timings.restype = ctypes.c_int
+    lib.svb_profile_enable.argtypes = [ctypes.c_int]
+    lib.svb_profile_enable.restype = ctypes.c_int
+    lib.svb_profile_collect.argtypes = []
+    lib.svb_profile_collect.restype = ctypes.c_int
+    lib.svb_profile_get.argtypes = [ctypes.c_int, _dp, ctypes.POINTER(_i64), _dp, _dp]
+    lib.svb_profile_get.restype = ctypes.c_int
     lib.svb_status_string.argtypes = [ctypes.c_int]
     lib.svb_status_string.restype = ctypes.c_char_p
     _lib = lib
@@ -119,6 +125,26 @@ def svb_last_timings():
     t = [ctypes.c_double(0.0) for _ in range(3)]
     load_library().svb_last_timings(*[ctypes.byref(x) for x in t])
     return tuple(x.value for x in t)
+
+
+SVB_PROF_PANEL, SVB_PROF_K1, SVB_PROF_K2, SVB_PROF_CHASE = 0, 1, 2, 3
+
+
+def svb_profile_enable(on: bool) -> int:
+    return load_library().svb_profile_enable(1 if on else 0)
+
+
+def svb_profile_collect() -> int:
+    return load_library().svb_profile_collect()
+
+
+def svb_profile_get(kind: int) -> dict:
+    sec, fl, by = ctypes.c_double(0), ctypes.c_double(0), ctypes.c_double(0)
+    cnt = _i64(0)
+    rc = load_library().svb_profile_get(kind, ctypes.byref(sec), ctypes.byref(cnt), ctypes.byref(fl), ctypes.byref(by))
+    if rc != SVB_OK:
+        raise SvbError(rc, "svb_profile_get")
+    return dict(seconds=sec.value, launches=cnt.value, flops=fl.value, bytes=by.value)
 
 
 def svdvals(A, nb: int = 64, overwrite: bool = False, work=None):

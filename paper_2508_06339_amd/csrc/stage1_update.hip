@@ -121,41 +121,51 @@ __global__ __launch_bounds__(256) void k2_simple(T* __restrict__ Cb, int64_t sp,
 
 template <typename T, typename C, int NB, bool LQ>
 static void update_simple(T* Cb, int64_t lda, int64_t qlen, const C* V, const C* Y, int64_t ldp,
-                          int chunks, int g, int64_t stride, C* W, hipStream_t s)
+                          int chunks, int g, int64_t stride, C* W, bool credited, hipStream_t s)
 {
+    // algorithmic work of one product: 2*rows*NB*cols flops; the matrix block is read once
+    // by K1 and read + written by K2.  Levels above 0 are overhead of the tree: not credited.
+    const double fl = credited ? 2.0 * chunks * NB * (double)NB * (double)qlen : 0.0;
+    const double by = credited ? (double)chunks * NB * (double)qlen * sizeof(T) : 0.0;
     const int64_t sp = LQ ? lda : 1, sq = LQ ? 1 : lda;
     const int domains = (chunks + g - 1) / g;
     dim3 g1((unsigned)((qlen + 63) / 64), (unsigned)domains);
+    prof_begin(SVB_PROF_K1, s, fl, by);
     hipLaunchKernelGGL((k1_simple<T, C, NB, LQ>), g1, dim3(256), 0, s, Cb, sp, sq, qlen, Y, ldp,
                        chunks, g, stride, W);
+    prof_end(s);
     dim3 g2((unsigned)((qlen + 31) / 32), (unsigned)chunks);
+    prof_begin(SVB_PROF_K2, s, fl, 2.0 * by);
     hipLaunchKernelGGL((k2_simple<T, C, NB, LQ>), g2, dim3(256), 0, s, Cb, sp, sq, qlen, V, ldp, g,
                        stride, W);
+    prof_end(s);
 }
 
 template <typename T, typename C, int NB>
 static void update_nb(bool lq, T* Cb, int64_t lda, int64_t qlen, const C* V, const C* Y,
-                      int64_t ldp, int chunks, int g, int64_t stride, C* W, int impl, hipStream_t s)
+                      int64_t ldp, int chunks, int g, int64_t stride, C* W, int impl, bool credited,
+                      hipStream_t s)
 {
     (void)impl;
-    if (lq) update_simple<T, C, NB, true>(Cb, lda, qlen, V, Y, ldp, chunks, g, stride, W, s);
-    else update_simple<T, C, NB, false>(Cb, lda, qlen, V, Y, ldp, chunks, g, stride, W, s);
+    if (lq) update_simple<T, C, NB, true>(Cb, lda, qlen, V, Y, ldp, chunks, g, stride, W, credited, s);
+    else update_simple<T, C, NB, false>(Cb, lda, qlen, V, Y, ldp, chunks, g, stride, W, credited, s);
 }
 
 template <typename T, typename C>
 void launch_update(int nb, bool lq, T* Cbase, int64_t lda, int64_t qlen, const C* V, const C* Y,
-                   int64_t ldp, int chunks, int g, int64_t stride, C* W, int impl, hipStream_t s)
+                   int64_t ldp, int chunks, int g, int64_t stride, C* W, int impl, bool credited,
+                   hipStream_t s)
 {
     if (qlen <= 0) return;
     switch (nb) {
-    case 32: update_nb<T, C, 32>(lq, Cbase, lda, qlen, V, Y, ldp, chunks, g, stride, W, impl, s); break;
-    case 64: update_nb<T, C, 64>(lq, Cbase, lda, qlen, V, Y, ldp, chunks, g, stride, W, impl, s); break;
-    default: update_nb<T, C, 128>(lq, Cbase, lda, qlen, V, Y, ldp, chunks, g, stride, W, impl, s); break;
+    case 32: update_nb<T, C, 32>(lq, Cbase, lda, qlen, V, Y, ldp, chunks, g, stride, W, impl, credited, s); break;
+    case 64: update_nb<T, C, 64>(lq, Cbase, lda, qlen, V, Y, ldp, chunks, g, stride, W, impl, credited, s); break;
+    default: update_nb<T, C, 128>(lq, Cbase, lda, qlen, V, Y, ldp, chunks, g, stride, W, impl, credited, s); break;
     }
 }
 
-template void launch_update<double, double>(int, bool, double*, int64_t, int64_t, const double*, const double*, int64_t, int, int, int64_t, double*, int, hipStream_t);
-template void launch_update<float, float>(int, bool, float*, int64_t, int64_t, const float*, const float*, int64_t, int, int, int64_t, float*, int, hipStream_t);
-template void launch_update<__half, float>(int, bool, __half*, int64_t, int64_t, const float*, const float*, int64_t, int, int, int64_t, float*, int, hipStream_t);
+template void launch_update<double, double>(int, bool, double*, int64_t, int64_t, const double*, const double*, int64_t, int, int, int64_t, double*, int, bool, hipStream_t);
+template void launch_update<float, float>(int, bool, float*, int64_t, int64_t, const float*, const float*, int64_t, int, int, int64_t, float*, int, bool, hipStream_t);
+template void launch_update<__half, float>(int, bool, __half*, int64_t, int64_t, const float*, const float*, int64_t, int, int, int64_t, float*, int, bool, hipStream_t);
 
 }  // namespace svb

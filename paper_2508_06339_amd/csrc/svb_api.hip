@@ -97,6 +97,55 @@ int build_levels(int64_t len, int nb, int g, Level* lv)
 
 struct Timings { double s1 = 0, s2 = 0, s3 = 0; } g_last;
 
+// Optional per-kernel timing with events on the launching stream.
+struct Profiler {
+    struct Rec { int kind; hipEvent_t a, b; double flops, bytes; };
+    bool on = false;
+    std::vector<hipEvent_t> pool;
+    std::vector<Rec> recs;
+    double sec[SVB_PROF_KINDS] = {0}, flops[SVB_PROF_KINDS] = {0}, bytes[SVB_PROF_KINDS] = {0};
+    int64_t count[SVB_PROF_KINDS] = {0};
+    hipEvent_t get()
+    {
+        if (!pool.empty()) { hipEvent_t e = pool.back(); pool.pop_back(); return e; }
+        hipEvent_t e = nullptr;
+        (void)hipEventCreate(&e);
+        return e;
+    }
+    void begin(int kind, hipStream_t s, double fl, double by)
+    {
+        if (!on) return;
+        Rec r{kind, get(), get(), fl, by};
+        (void)hipEventRecord(r.a, s);
+        recs.push_back(r);
+    }
+    void end(hipStream_t s)
+    {
+        if (!on) return;
+        (void)hipEventRecord(recs.back().b, s);
+    }
+    void collect()
+    {
+        for (auto& r : recs) {
+            float ms = 0;
+            if (hipEventSynchronize(r.b) == hipSuccess && hipEventElapsedTime(&ms, r.a, r.b) == hipSuccess) {
+                sec[r.kind] += ms * 1e-3;
+                flops[r.kind] += r.flops;
+                bytes[r.kind] += r.bytes;
+                count[r.kind] += 1;
+            }
+            pool.push_back(r.a);
+            pool.push_back(r.b);
+        }
+        recs.clear();
+    }
+    void reset()
+    {
+        collect();
+        for (int k = 0; k < SVB_PROF_KINDS; ++k) { sec[k] = flops[k] = bytes[k] = 0; count[k] = 0; }
+    }
+} g_prof;
+
 template <typename T, typename C>
 int ge2gb_impl(int64_t n, T* A, int64_t lda, int nb, C* band, int64_t ldab, unsigned char* work,
                const Carve& cv, hipStream_t s)
@@ -121,6 +170,7 @@ int ge2gb_impl(int64_t n, T* A, int64_t lda, int nb, C* band, int64_t ldab, unsi
             const int64_t col0 = lq ? (k + 1) * nb : k * nb;
             const int64_t len = lq ? n - (k + 1) * nb : n - k * nb;
             const int nl = build_levels(len, nb, g, lv);
+            g_prof.begin(SVB_PROF_PANEL, s, 2.0 * (double)len * nb * nb, 0.0);
             launch_panel_gather<T, C>(A, lda, row0, col0, lq, len, nb, Vb + lv[0].poff, lv[0].ldp, s);
             for (int L = 0; L < nl; ++L) {
                 // the R factors of level L are stacked into level L+1's panel; the last
@@ -132,13 +182,14 @@ int ge2gb_impl(int64_t n, T* A, int64_t lda, int nb, C* band, int64_t ldab, unsi
                 if (L == nl - 1)
                     launch_scatter_r<C>(Vb + next_off, ldnext, nb, band, ldab, row0, col0, lq, s);
             }
+            g_prof.end(s);
             // trailing matrix: QR -> rows k*nb.., columns (k+1)*nb..;  LQ -> rows (k+1)*nb.., columns (k+1)*nb..
             const int64_t qlen = n - (k + 1) * nb;
             if (qlen > 0) {
                 T* Cb = lq ? A + (k + 1) * nb + (k + 1) * nb * lda : A + k * nb + (k + 1) * nb * lda;
                 for (int L = 0; L < nl; ++L)
                     launch_update<T, C>(nb, lq, Cb, lda, qlen, Vb + lv[L].poff, Yb + lv[L].poff, lv[L].ldp,
-                                        lv[L].chunks, g, lv[L].stride, Wb, impl, s);
+                                        lv[L].chunks, g, lv[L].stride, Wb, impl, L == 0, s);
             }
         }
     }
@@ -158,6 +209,10 @@ int ge2gb_dispatch(svb_dtype dt, int64_t n, void* A, int64_t lda, int nb, void* 
 }
 
 }  // namespace
+
+void prof_begin(int kind, hipStream_t s, double flops, double bytes) { g_prof.begin(kind, s, flops, bytes); }
+void prof_end(hipStream_t s) { g_prof.end(s); }
+
 }  // namespace svb
 
 using namespace svb;
@@ -196,9 +251,15 @@ int svb_gb2bd(svb_dtype band_dt, int64_t n, int nb, void* band_dev, int64_t ldab
     if (work_bytes < chase_workspace_bytes(n, nb)) return SVB_ERR_WORKSPACE;
     if (chase_workspace_bytes(n, nb) > 0 && !work_dev) return SVB_ERR_ARG;
     hipStream_t s = (hipStream_t)stream;
+    const double cs = band_dt == SVB_F64 ? 8.0 : 4.0;
+    prof_begin(SVB_PROF_CHASE, s, 6.0 * (double)n * (double)n * nb, 3.0 * (double)n * (double)n * nb * cs);
+    int rc;
     if (band_dt == SVB_F64)
-        return run_chase<double>(n, nb, (double*)band_dev, ldab, (double*)d_dev, (double*)e_dev, work_dev, work_bytes, s);
-    return run_chase<float>(n, nb, (float*)band_dev, ldab, (float*)d_dev, (float*)e_dev, work_dev, work_bytes, s);
+        rc = run_chase<double>(n, nb, (double*)band_dev, ldab, (double*)d_dev, (double*)e_dev, work_dev, work_bytes, s);
+    else
+        rc = run_chase<float>(n, nb, (float*)band_dev, ldab, (float*)d_dev, (float*)e_dev, work_dev, work_bytes, s);
+    prof_end(s);
+    return rc;
 }
 
 int svb_bdsvals(int64_t n, const double* d, const double* e, double* sigma)
@@ -273,6 +334,7 @@ int svb_svdvals(svb_dtype dt, int64_t m, int64_t n, void* A_dev, int64_t lda, vo
                 for (int64_t i = 0; i < n; ++i) static_cast<float*>(S_out_host)[i] = (float)hs[(size_t)i];
         }
     }
+    if (g_prof.on) g_prof.collect();
     g_last.s1 = ms1 * 1e-3;
     g_last.s2 = ms2 * 1e-3;
     g_last.s3 = t3;
@@ -284,6 +346,29 @@ int svb_last_timings(double* t_stage1, double* t_stage2, double* t_stage3)
     if (t_stage1) *t_stage1 = g_last.s1;
     if (t_stage2) *t_stage2 = g_last.s2;
     if (t_stage3) *t_stage3 = g_last.s3;
+    return SVB_OK;
+}
+
+int svb_profile_enable(int on)
+{
+    g_prof.reset();
+    g_prof.on = on != 0;
+    return SVB_OK;
+}
+
+int svb_profile_collect(void)
+{
+    g_prof.collect();
+    return SVB_OK;
+}
+
+int svb_profile_get(int kind, double* seconds, int64_t* launches, double* flops, double* bytes)
+{
+    if (kind < 0 || kind >= SVB_PROF_KINDS) return SVB_ERR_ARG;
+    if (seconds) *seconds = g_prof.sec[kind];
+    if (launches) *launches = g_prof.count[kind];
+    if (flops) *flops = g_prof.flops[kind];
+    if (bytes) *bytes = g_prof.bytes[kind];
     return SVB_OK;
 }
 
