@@ -14,6 +14,8 @@
 // A level's chunk ch covers panel rows ch*stride .. ch*stride + NB - 1
 // (stride = NB at level 0, NB*g^L above: the rows that hold the R factors of
 // the level below), and rows ch*NB .. of the level's V / Y panels.
+#include <type_traits>
+
 #include "svb_internal.h"
 
 namespace svb {
@@ -141,14 +143,284 @@ static void update_simple(T* Cb, int64_t lda, int64_t qlen, const C* V, const C*
     prof_end(s);
 }
 
+// ------------------------------------------------------------------------
+// MFMA implementation.
+//
+// One workgroup of 4 waves computes a TM x TN tile D = A_op * B_op with
+// v_mfma_f32_32x32x2_f32 (f32 arithmetic) or v_mfma_f64_16x16x4_f64 (f64).
+// Both operands are staged through LDS in k-major order (Xs[k][mn], row
+// length odd), TK = 128 bytes of k per stage; the next stage's global loads
+// are issued into registers before the current stage's MFMAs.  Tile roles
+// are chosen so that the lanes of an accumulator register run along the
+// direction in which the trailing matrix is contiguous in memory:
+//   K1, both sweeps : D[q][kk] = sum_p C(p,q) Y(p,kk)     -> W[kk + q*NB]
+//   K2, QR sweep    : D[q][p]  = sum_kk W(kk,q) V(p,kk)   -> C(p,q) -= D
+//   K2, LQ sweep    : D[p][q]  = sum_kk V(p,kk) W(kk,q)   -> C(p,q) -= D
+// ------------------------------------------------------------------------
+template <typename C> struct Mfma;
+
+template <> struct Mfma<float> {
+    static constexpr int BM = 32, BN = 32, BK = 2, NACC = 16;
+    typedef float acc_t __attribute__((ext_vector_type(16)));
+    static __device__ __forceinline__ acc_t run(float a, float b, acc_t c)
+    {
+        return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
+    }
+    // operand element held by lane l: (mn, k) = (l % 32, l / 32)
+    static __device__ __forceinline__ int op_mn(int l) { return l & 31; }
+    static __device__ __forceinline__ int op_k(int l) { return l >> 5; }
+    // accumulator register i of lane l is D(row, col)
+    static __device__ __forceinline__ int row(int i, int l) { return 8 * (i >> 2) + 4 * (l >> 5) + (i & 3); }
+    static __device__ __forceinline__ int col(int l) { return l & 31; }
+};
+
+template <> struct Mfma<double> {
+    static constexpr int BM = 16, BN = 16, BK = 4, NACC = 4;
+    typedef double acc_t __attribute__((ext_vector_type(4)));
+    static __device__ __forceinline__ acc_t run(double a, double b, acc_t c)
+    {
+        return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ int op_mn(int l) { return l & 15; }
+    static __device__ __forceinline__ int op_k(int l) { return l >> 4; }
+    static __device__ __forceinline__ int row(int i, int l) { return 4 * i + (l >> 4); }
+    static __device__ __forceinline__ int col(int l) { return l & 15; }
+};
+
+// Pol supplies: TM, TN, WM, WN, A_KC, B_KC (operand contiguous along k?),
+// ktiles(), loadA(mn, kt, k), loadB(mn, kt, k), store(m, n, value).
+template <typename C, typename Pol>
+__device__ __forceinline__ void gemm_tile(const Pol& pol)
+{
+    using M = Mfma<C>;
+    constexpr int TM = Pol::TM, TN = Pol::TN, WM = Pol::WM, WN = Pol::WN;
+    constexpr int TK = 128 / (int)sizeof(C);
+    constexpr int LDA = TM + 1, LDB = TN + 1;
+    constexpr int WGN = TN / WN;
+    static_assert((TM / WM) * WGN == 4, "4 waves per workgroup");
+    constexpr int FM = WM / M::BM, FN = WN / M::BN;
+    constexpr int NA = TK * TM / 256, NBE = TK * TN / 256;
+    __shared__ C As[TK * LDA];
+    __shared__ C Bs[TK * LDB];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;
+    typename M::acc_t acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int r = 0; r < M::NACC; ++r) acc[i][j][r] = 0;
+
+    C ra[NA], rb[NBE];
+    auto fetch = [&](int kt) {
+#pragma unroll
+        for (int e = 0; e < NA; ++e) {
+            const int idx = tid + e * 256;
+            const int k = Pol::A_KC ? idx % TK : idx / TM;
+            const int mn = Pol::A_KC ? idx / TK : idx % TM;
+            ra[e] = pol.loadA(mn, kt, k);
+        }
+#pragma unroll
+        for (int e = 0; e < NBE; ++e) {
+            const int idx = tid + e * 256;
+            const int k = Pol::B_KC ? idx % TK : idx / TN;
+            const int mn = Pol::B_KC ? idx / TK : idx % TN;
+            rb[e] = pol.loadB(mn, kt, k);
+        }
+    };
+    auto stash = [&]() {
+#pragma unroll
+        for (int e = 0; e < NA; ++e) {
+            const int idx = tid + e * 256;
+            const int k = Pol::A_KC ? idx % TK : idx / TM;
+            const int mn = Pol::A_KC ? idx / TK : idx % TM;
+            As[k * LDA + mn] = ra[e];
+        }
+#pragma unroll
+        for (int e = 0; e < NBE; ++e) {
+            const int idx = tid + e * 256;
+            const int k = Pol::B_KC ? idx % TK : idx / TN;
+            const int mn = Pol::B_KC ? idx / TK : idx % TN;
+            Bs[k * LDB + mn] = rb[e];
+        }
+    };
+
+    const int nkt = pol.ktiles();
+    fetch(0);
+    for (int kt = 0; kt < nkt; ++kt) {
+        stash();
+        __syncthreads();
+        if (kt + 1 < nkt) fetch(kt + 1);
+        const int omn = M::op_mn(lane), ok = M::op_k(lane);
+#pragma unroll
+        for (int kk = 0; kk < TK; kk += M::BK) {
+            C a[FM], b[FN];
+#pragma unroll
+            for (int i = 0; i < FM; ++i) a[i] = As[(kk + ok) * LDA + wm0 + i * M::BM + omn];
+#pragma unroll
+            for (int j = 0; j < FN; ++j) b[j] = Bs[(kk + ok) * LDB + wn0 + j * M::BN + omn];
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int j = 0; j < FN; ++j) acc[i][j] = M::run(a[i], b[j], acc[i][j]);
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int r = 0; r < M::NACC; ++r)
+                pol.store(wm0 + i * M::BM + M::row(r, lane), wn0 + j * M::BN + M::col(lane), acc[i][j][r]);
+}
+
+template <int NB, bool TRANSPOSED> struct TileShape;  // TRANSPOSED: TM = NB, TN = 128
+template <> struct TileShape<128, false> { static constexpr int TM = 128, TN = 128, WM = 64, WN = 64; };
+template <> struct TileShape<64, false>  { static constexpr int TM = 128, TN = 64,  WM = 64, WN = 32; };
+template <> struct TileShape<32, false>  { static constexpr int TM = 128, TN = 32,  WM = 32, WN = 32; };
+template <> struct TileShape<128, true>  { static constexpr int TM = 128, TN = 128, WM = 64, WN = 64; };
+template <> struct TileShape<64, true>   { static constexpr int TM = 64,  TN = 128, WM = 32, WN = 64; };
+template <> struct TileShape<32, true>   { static constexpr int TM = 32,  TN = 128, WM = 32, WN = 32; };
+
+// K1: D[q][kk] = sum over the domain's rows p of C(p,q) * Y(p,kk)
+template <typename T, typename C, int NB, bool LQ>
+struct K1Pol : TileShape<NB, false> {
+    static constexpr bool A_KC = !LQ, B_KC = true;
+    static constexpr int TK = 128 / (int)sizeof(C);
+    static constexpr int KPC = NB / TK;  // k-tiles per chunk
+    const T* Cb; int64_t sp, sq, qlen, q0; const C* Y; int64_t ldp; int64_t ch0; int nch; int64_t stride; C* Wd;
+    __device__ __forceinline__ int ktiles() const { return nch * KPC; }
+    __device__ __forceinline__ C loadA(int mn, int kt, int k) const
+    {
+        const int64_t q = q0 + mn;
+        if (q >= qlen) return (C)0;
+        const int64_t p = (ch0 + kt / KPC) * stride + (kt % KPC) * TK + k;
+        return ld_as<C, T>(&Cb[p * sp + q * sq]);
+    }
+    __device__ __forceinline__ C loadB(int mn, int kt, int k) const
+    {
+        const int64_t row = (ch0 + kt / KPC) * NB + (kt % KPC) * TK + k;
+        return Y[row + (int64_t)mn * ldp];
+    }
+    __device__ __forceinline__ void store(int m, int n, C v) const
+    {
+        const int64_t q = q0 + m;
+        if (q < qlen) Wd[n + q * NB] = v;
+    }
+};
+
+template <typename T, typename C, int NB, bool LQ>
+__global__ __launch_bounds__(256) void k1_mfma(const T* __restrict__ Cb, int64_t sp, int64_t sq,
+                                               int64_t qlen, const C* __restrict__ Y, int64_t ldp,
+                                               int chunks, int g, int64_t stride, C* __restrict__ W)
+{
+    const int d = blockIdx.y;
+    K1Pol<T, C, NB, LQ> pol;
+    pol.Cb = Cb; pol.sp = sp; pol.sq = sq; pol.qlen = qlen; pol.q0 = (int64_t)blockIdx.x * 128;
+    pol.Y = Y; pol.ldp = ldp; pol.ch0 = (int64_t)d * g; pol.nch = min(g, chunks - d * g);
+    pol.stride = stride; pol.Wd = W + (int64_t)d * NB * qlen;
+    gemm_tile<C>(pol);
+}
+
+// K2, QR sweep: D[q][p] = sum_kk W(kk,q) V(p,kk);  C(p,q) -= D
+template <typename T, typename C, int NB>
+struct K2QrPol : TileShape<NB, false> {
+    static constexpr bool A_KC = true, B_KC = false;
+    static constexpr int TK = 128 / (int)sizeof(C);
+    T* Cb; int64_t sp, sq, qlen, q0; const C* V; int64_t ldp; int64_t ch; int64_t stride; const C* Wd;
+    __device__ __forceinline__ int ktiles() const { return NB / TK; }
+    __device__ __forceinline__ C loadA(int mn, int kt, int k) const
+    {
+        const int64_t q = q0 + mn;
+        return q < qlen ? Wd[(kt * TK + k) + q * NB] : (C)0;
+    }
+    __device__ __forceinline__ C loadB(int mn, int kt, int k) const
+    {
+        return V[(ch * NB + mn) + (int64_t)(kt * TK + k) * ldp];
+    }
+    __device__ __forceinline__ void store(int m, int n, C v) const
+    {
+        const int64_t q = q0 + m;
+        if (q < qlen) {
+            T* ptr = &Cb[(ch * stride + n) * sp + q * sq];
+            st_as<T, C>(ptr, ld_as<C, T>(ptr) - v);
+        }
+    }
+};
+
+// K2, LQ sweep: D[p][q] = sum_kk V(p,kk) W(kk,q);  C(p,q) -= D
+template <typename T, typename C, int NB>
+struct K2LqPol : TileShape<NB, true> {
+    static constexpr bool A_KC = false, B_KC = true;
+    static constexpr int TK = 128 / (int)sizeof(C);
+    T* Cb; int64_t sp, sq, qlen, q0; const C* V; int64_t ldp; int64_t ch; int64_t stride; const C* Wd;
+    __device__ __forceinline__ int ktiles() const { return NB / TK; }
+    __device__ __forceinline__ C loadA(int mn, int kt, int k) const
+    {
+        return V[(ch * NB + mn) + (int64_t)(kt * TK + k) * ldp];
+    }
+    __device__ __forceinline__ C loadB(int mn, int kt, int k) const
+    {
+        const int64_t q = q0 + mn;
+        return q < qlen ? Wd[(kt * TK + k) + q * NB] : (C)0;
+    }
+    __device__ __forceinline__ void store(int m, int n, C v) const
+    {
+        const int64_t q = q0 + n;
+        if (q < qlen) {
+            T* ptr = &Cb[(ch * stride + m) * sp + q * sq];
+            st_as<T, C>(ptr, ld_as<C, T>(ptr) - v);
+        }
+    }
+};
+
+template <typename T, typename C, int NB, bool LQ>
+__global__ __launch_bounds__(256) void k2_mfma(T* __restrict__ Cb, int64_t sp, int64_t sq, int64_t qlen,
+                                               const C* __restrict__ V, int64_t ldp, int g,
+                                               int64_t stride, const C* __restrict__ W)
+{
+    const int64_t ch = blockIdx.y;
+    typename std::conditional<LQ, K2LqPol<T, C, NB>, K2QrPol<T, C, NB>>::type pol;
+    pol.Cb = Cb; pol.sp = sp; pol.sq = sq; pol.qlen = qlen; pol.q0 = (int64_t)blockIdx.x * 128;
+    pol.V = V; pol.ldp = ldp; pol.ch = ch; pol.stride = stride;
+    pol.Wd = W + (ch / g) * (int64_t)NB * qlen;
+    gemm_tile<C>(pol);
+}
+
+template <typename T, typename C, int NB, bool LQ>
+static void update_mfma(T* Cb, int64_t lda, int64_t qlen, const C* V, const C* Y, int64_t ldp,
+                        int chunks, int g, int64_t stride, C* W, bool credited, hipStream_t s)
+{
+    const int64_t sp = LQ ? lda : 1, sq = LQ ? 1 : lda;
+    const int domains = (chunks + g - 1) / g;
+    const double fl = credited ? 2.0 * chunks * NB * (double)NB * (double)qlen : 0.0;
+    const double by = credited ? (double)chunks * NB * (double)qlen * sizeof(T) : 0.0;
+    const unsigned qt = (unsigned)((qlen + 127) / 128);
+    prof_begin(SVB_PROF_K1, s, fl, by);
+    hipLaunchKernelGGL((k1_mfma<T, C, NB, LQ>), dim3(qt, (unsigned)domains), dim3(256), 0, s, Cb, sp, sq,
+                       qlen, Y, ldp, chunks, g, stride, W);
+    prof_end(s);
+    prof_begin(SVB_PROF_K2, s, fl, 2.0 * by);
+    hipLaunchKernelGGL((k2_mfma<T, C, NB, LQ>), dim3(qt, (unsigned)chunks), dim3(256), 0, s, Cb, sp, sq,
+                       qlen, V, ldp, g, stride, W);
+    prof_end(s);
+}
+
 template <typename T, typename C, int NB>
 static void update_nb(bool lq, T* Cb, int64_t lda, int64_t qlen, const C* V, const C* Y,
                       int64_t ldp, int chunks, int g, int64_t stride, C* W, int impl, bool credited,
                       hipStream_t s)
 {
-    (void)impl;
-    if (lq) update_simple<T, C, NB, true>(Cb, lda, qlen, V, Y, ldp, chunks, g, stride, W, credited, s);
-    else update_simple<T, C, NB, false>(Cb, lda, qlen, V, Y, ldp, chunks, g, stride, W, credited, s);
+    if (impl == 0) {
+        if (lq) update_simple<T, C, NB, true>(Cb, lda, qlen, V, Y, ldp, chunks, g, stride, W, credited, s);
+        else update_simple<T, C, NB, false>(Cb, lda, qlen, V, Y, ldp, chunks, g, stride, W, credited, s);
+    } else {
+        if (lq) update_mfma<T, C, NB, true>(Cb, lda, qlen, V, Y, ldp, chunks, g, stride, W, credited, s);
+        else update_mfma<T, C, NB, false>(Cb, lda, qlen, V, Y, ldp, chunks, g, stride, W, credited, s);
+    }
 }
 
 template <typename T, typename C>
