@@ -11,6 +11,7 @@
 // one R is left.  Each domain also produces the compact-WY pair (V, Y = V T)
 // that the trailing update applies with matrix products.
 #include "svb_internal.h"
+#include "mfma_gemm.h"
 
 namespace svb {
 
@@ -181,10 +182,231 @@ __global__ __launch_bounds__(NT) void panel_qr_kernel(C* __restrict__ P, int64_t
     }
 }
 
+// ---------------------------------------------------------------- domain QR, register resident
+// The production panel kernel.  The whole domain (h <= HMAX = (NT/NB)*RPT rows,
+// NB columns) lives in registers: thread (c, rg) = (tid % NB, tid / NB) holds
+// rows rg*RPT .. rg*RPT+RPT-1 of column c (the paper's GEQRT, Algorithm 3, keeps
+// one tile column per thread in the same way; here a column is additionally
+// split over NT/NB threads, the role of the paper's SPLITK).  Per reflector k:
+//   - the thread(s) of column k publish the pivot column in LDS, the row group
+//     that owns row k publishes row k;
+//   - every thread forms the inner product of its rows with the pivot column;
+//     partial sums meet in LDS (column k's own sum is the squared tail norm);
+//   - every thread derives beta, tau and updates its rows (Algorithm 3's
+//     rho / rho' step); columns left of k record v_c^T v_k for the T factor.
+// Two barriers per reflector; the reflector tails stay unscaled in registers
+// (each column remembers its scale) until they are written out.
+// Afterwards T is built in LDS from the recorded inner products (the LAPACK
+// larft recurrence, rows in parallel) and written to Tws for the Y = V T product.
+template <typename C, int NB, int RPT, int NT>
+__global__ __launch_bounds__(NT) void panel_qr_reg_kernel(C* __restrict__ P, int64_t ldp,
+                                                          C* __restrict__ Tws, int chunks, int g,
+                                                          C* __restrict__ Pnext, int64_t ldnext)
+{
+    constexpr int NRG = NT / NB, HMAX = NRG * RPT, LT = NT / NB;  // LT lanes cooperate on one row of T
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    C* Ts = reinterpret_cast<C*>(smem_raw);       // NB x (NB+1)
+    C* Gs = Ts + NB * (NB + 1);                   // NB x NB, column k holds v_c^T v_k, c < k
+    C* xs = Gs + NB * NB;                         // 2 x HMAX
+    C* part = xs + 2 * HMAX;                      // NRG x NB
+    C* rowk = part + NRG * NB;                    // 2 x NB
+    C* taus = rowk + 2 * NB;                      // NB
+
+    const int d = blockIdx.x;
+    const int nch = min(g, chunks - d * g);
+    const int h = nch * NB;
+    C* Pd = P + (int64_t)d * g * NB;
+    C* Td = Tws + (int64_t)d * NB * NB;
+    const int tid = threadIdx.x;
+    const int c = tid % NB, rg = tid / NB, row0 = rg * RPT;
+
+    C a[RPT];
+#pragma unroll
+    for (int r = 0; r < RPT; ++r) {
+        const int row = row0 + r;
+        a[r] = row < h ? Pd[row + (int64_t)c * ldp] : (C)0;
+    }
+    C my_inv = 0;
+
+    for (int k = 0; k < NB; ++k) {
+        const int buf = k & 1, rgk = k / RPT, kk = k % RPT;
+        if (rg == rgk) {
+            C v = a[0];
+#pragma unroll
+            for (int r = 1; r < RPT; ++r) v = (r == kk) ? a[r] : v;
+            rowk[buf * NB + c] = v;
+        }
+        if (c == k) {
+#pragma unroll
+            for (int r = 0; r < RPT; ++r) xs[buf * HMAX + row0 + r] = (row0 + r > k) ? a[r] : (C)0;
+        }
+        __syncthreads();
+        const bool below = row0 + RPT - 1 > k;
+        C p = 0;
+        if (below) {
+#pragma unroll
+            for (int r = 0; r < RPT; ++r) p += xs[buf * HMAX + row0 + r] * a[r];
+        }
+        part[rg * NB + c] = p;
+        __syncthreads();
+        C D = 0, ss = 0;
+#pragma unroll
+        for (int q = 0; q < NRG; ++q) {
+            D += part[q * NB + c];
+            ss += part[q * NB + k];
+        }
+        const C alpha = rowk[buf * NB + k], akc = rowk[buf * NB + c];
+        C tau, beta, inv;
+        if (ss == (C)0) {
+            tau = 0; beta = alpha; inv = 0;
+        } else {
+            const C nrm = sqrt(alpha * alpha + ss);
+            beta = alpha >= (C)0 ? -nrm : nrm;
+            tau = (beta - alpha) / beta;
+            inv = (C)1 / (alpha - beta);
+        }
+        const C w = akc + inv * D;   // v_k^T (column c)
+        const C f = tau * w;
+        if (rg == 0) {
+            if (c < k) Gs[c + k * NB] = my_inv * w;   // v_c^T v_k (v_c's tail is stored unscaled)
+            if (c == k) taus[k] = tau;
+        }
+        if (c == k) my_inv = inv;
+        if (rg == rgk) {
+            const C nv = (c > k) ? akc - f : ((c == k) ? beta : akc);
+#pragma unroll
+            for (int r = 0; r < RPT; ++r) a[r] = (r == kk) ? nv : a[r];
+        }
+        if (c > k && below && tau != (C)0) {
+            const C coef = f * inv;
+#pragma unroll
+            for (int r = 0; r < RPT; ++r) a[r] -= coef * xs[buf * HMAX + row0 + r];
+        }
+    }
+    // R -> next level's panel; explicit V (unit diagonal, zeros above, scaled tails) in place
+#pragma unroll
+    for (int r = 0; r < RPT; ++r) {
+        const int row = row0 + r;
+        if (row < h) {
+            if (row < NB) Pnext[((int64_t)d * NB + row) + (int64_t)c * ldnext] = (row <= c) ? a[r] : (C)0;
+            Pd[row + (int64_t)c * ldp] = (row > c) ? a[r] * my_inv : ((row == c) ? (C)1 : (C)0);
+        }
+    }
+    __syncthreads();
+    // T: T[k][k] = tau_k, T[i][k] = -tau_k * sum_{j=i}^{k-1} T[i][j] G[j][k]  (i < k)
+    {
+        const int i = tid / LT, s = tid % LT;
+        for (int j = s; j < NB; j += LT) Ts[i * (NB + 1) + j] = (j == i) ? taus[i] : (C)0;
+        __syncthreads();
+        for (int k = 1; k < NB; ++k) {
+            C acc = 0;
+            if (i < k)
+                for (int j = i + s; j < k; j += LT) acc += Ts[i * (NB + 1) + j] * Gs[j + k * NB];
+#pragma unroll
+            for (int off = LT / 2; off > 0; off >>= 1) acc += __shfl_xor(acc, off, kWave);
+            if (i < k && s == 0) Ts[i * (NB + 1) + k] = -taus[k] * acc;
+            __syncthreads();
+        }
+        for (int idx = tid; idx < NB * NB; idx += NT) {
+            const int ii = idx % NB, jj = idx / NB;
+            Td[ii + jj * NB] = Ts[ii * (NB + 1) + jj];
+        }
+    }
+}
+
+template <typename C, int NB, int RPT, int NT>
+static void launch_panel_reg(C* P, int64_t ldp, C* Tws, int chunks, int g, C* Pnext, int64_t ldnext,
+                             hipStream_t s)
+{
+    constexpr int NRG = NT / NB, HMAX = NRG * RPT;
+    const size_t smem = sizeof(C) * (size_t)(NB * (NB + 1) + NB * NB + 2 * HMAX + NRG * NB + 2 * NB + NB);
+    static bool attr_set = false;
+    auto kern = panel_qr_reg_kernel<C, NB, RPT, NT>;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        attr_set = true;
+    }
+    const int domains = (chunks + g - 1) / g;
+    hipLaunchKernelGGL(kern, dim3(domains), dim3(NT), smem, s, P, ldp, Tws, chunks, g, Pnext, ldnext);
+}
+
+// rows a register-resident domain can hold, 0 if this (type, nb) has no such kernel
+template <typename C> int panel_reg_rows(int nb);
+template <> int panel_reg_rows<float>(int nb) { return nb == 32 ? 512 : (nb == 64 ? 512 : 512); }
+template <> int panel_reg_rows<double>(int nb) { return nb == 32 ? 512 : (nb == 64 ? 512 : 0); }
+
+template <typename C> struct PanelRegDispatch;
+template <> struct PanelRegDispatch<float> {
+    static void run(int nb, float* P, int64_t ldp, float* Tws, int chunks, int g, float* Pn, int64_t ldn, hipStream_t s)
+    {
+        if (nb == 32) launch_panel_reg<float, 32, 32, 512>(P, ldp, Tws, chunks, g, Pn, ldn, s);
+        else if (nb == 64) launch_panel_reg<float, 64, 64, 512>(P, ldp, Tws, chunks, g, Pn, ldn, s);
+        else launch_panel_reg<float, 128, 64, 1024>(P, ldp, Tws, chunks, g, Pn, ldn, s);
+    }
+};
+template <> struct PanelRegDispatch<double> {
+    static void run(int nb, double* P, int64_t ldp, double* Tws, int chunks, int g, double* Pn, int64_t ldn, hipStream_t s)
+    {
+        if (nb == 32) launch_panel_reg<double, 32, 32, 512>(P, ldp, Tws, chunks, g, Pn, ldn, s);
+        else launch_panel_reg<double, 64, 64, 512>(P, ldp, Tws, chunks, g, Pn, ldn, s);
+    }
+};
+
+// ---------------------------------------------------------------- Y = V T on MFMA
+// D[k][p] = sum_j T(j,k) V(p,j): lanes of an accumulator register run along p,
+// so Y is written along its contiguous direction.
+template <typename C, int NB>
+struct YPol : TileShape<NB, true> {
+    static constexpr bool A_KC = true, B_KC = false;
+    static constexpr int TK = 128 / (int)sizeof(C);
+    const C* V; C* Y; const C* Td; int64_t ldp, p0, rows;
+    __device__ __forceinline__ int ktiles() const { return NB / TK; }
+    __device__ __forceinline__ C loadA(int mn, int kt, int k) const { return Td[(kt * TK + k) + mn * NB]; }
+    __device__ __forceinline__ C loadB(int mn, int kt, int k) const
+    {
+        const int64_t p = p0 + mn;
+        return p < rows ? V[p + (int64_t)(kt * TK + k) * ldp] : (C)0;
+    }
+    __device__ __forceinline__ void store(int m, int n, C v) const
+    {
+        const int64_t p = p0 + n;
+        if (p < rows) Y[p + (int64_t)m * ldp] = v;
+    }
+};
+
+template <typename C, int NB>
+__global__ __launch_bounds__(256) void panel_y_kernel(const C* __restrict__ V, C* __restrict__ Y,
+                                                      const C* __restrict__ Tws, int64_t ldp,
+                                                      int64_t rows, int g)
+{
+    YPol<C, NB> pol;
+    pol.V = V; pol.Y = Y; pol.ldp = ldp; pol.p0 = (int64_t)blockIdx.x * 128; pol.rows = rows;
+    pol.Td = Tws + (pol.p0 / NB / g) * (int64_t)NB * NB;
+    gemm_tile<C>(pol);
+}
+
+template <typename C, int NB>
+static void launch_panel_y(const C* V, C* Y, const C* Tws, int64_t ldp, int64_t rows, int g, hipStream_t s)
+{
+    hipLaunchKernelGGL((panel_y_kernel<C, NB>), dim3((unsigned)((rows + 127) / 128)), dim3(256), 0, s, V, Y,
+                       Tws, ldp, rows, g);
+}
+
 template <typename C>
 void launch_panel_qr(int nb, C* P, int64_t ldp, C* Y, C* Tws, int chunks, int g,
                      C* Pnext, int64_t ldnext, int* /*err*/, hipStream_t s)
 {
+    static const int impl = env_int("SVB_PANEL_IMPL", 1);
+    // register-resident kernel + MFMA Y product when the domain fits (and 128-row Y tiles
+    // never straddle two domains); otherwise the plain kernel below
+    if (impl != 0 && panel_reg_rows<C>(nb) >= g * nb && (g * nb) % 128 == 0) {
+        PanelRegDispatch<C>::run(nb, P, ldp, Tws, chunks, g, Pnext, ldnext, s);
+        const int64_t rows = (int64_t)chunks * nb;
+        if (nb == 32) launch_panel_y<C, 32>(P, Y, Tws, ldp, rows, g, s);
+        else if (nb == 64) launch_panel_y<C, 64>(P, Y, Tws, ldp, rows, g, s);
+        else launch_panel_y<C, 128>(P, Y, Tws, ldp, rows, g, s);
+        return;
+    }
     const int domains = (chunks + g - 1) / g;
     const size_t smem = (size_t)g * nb * sizeof(C);
     constexpr int NT = 512;

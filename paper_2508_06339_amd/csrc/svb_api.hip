@@ -31,12 +31,14 @@ int check_shape(svb_dtype dt, int64_t m, int64_t n, int nb)
     return SVB_OK;
 }
 
-// chunks-per-domain of the panel tree
-int domain_chunks(int nb)
+// chunks-per-domain of the panel tree: as many nb-row tiles as the register-resident
+// panel kernel holds (512 rows), 8 where that kernel does not exist (f64, nb = 128)
+int domain_chunks(svb_dtype dt, int nb)
 {
     int g = env_int("SVB_DOMAIN_CHUNKS", 0);
     if (g >= 2 && g <= 64) return g;
-    return nb == 128 ? 8 : (nb == 64 ? 8 : 8);
+    if (dt == SVB_F64 && nb == 128) return 8;
+    return 512 / nb;
 }
 constexpr int kMinDomainChunks = 2;  // workspace is sized for any g >= this
 
@@ -155,7 +157,7 @@ int ge2gb_impl(int64_t n, T* A, int64_t lda, int nb, C* band, int64_t ldab, unsi
     C* Wb = reinterpret_cast<C*>(work + cv.off_W);
     C* Tb = reinterpret_cast<C*>(work + cv.off_T);
     int* err = reinterpret_cast<int*>(work + cv.off_err);
-    const int g = domain_chunks(nb);
+    const int g = domain_chunks(sizeof(C) == 8 ? SVB_F64 : SVB_F32, nb);
     const int impl = env_int("SVB_UPDATE_IMPL", 1);
     const int64_t N = n / nb;
     Level lv[kMaxLevels];
