@@ -98,11 +98,18 @@ int svb_ge2gb(svb_dtype dt, int64_t m, int64_t n, void* A_dev, int64_t lda, int 
  *   band_dev [dev] in/out: destroyed.
  *   d_dev    [dev] out: n diagonal entries, same type as the band.
  *   e_dev    [dev] out: n-1 super-diagonal entries (n slots are written).
- * Asynchronous.
+ *   work_dev [dev] scratch of svb_gb2bd_workspace_bytes(n, nb) bytes (sweep
+ *            ticket, error flag, one progress counter per sweep).
+ * Asynchronous.  The sweeps are pipelined with bounded waits; should a wait
+ * expire (it cannot unless the device is oversubscribed or faulty) d[0] is
+ * set to NaN, which svb_bdsvals / svb_svdvals report as SVB_ERR_NONFINITE.
  */
 int svb_gb2bd(svb_dtype band_dt, int64_t n, int nb, void* band_dev, int64_t ldab,
               void* d_dev, void* e_dev, void* work_dev, size_t work_bytes,
               void* stream);
+
+/* Bytes of device scratch svb_gb2bd needs ([host] out). */
+int svb_gb2bd_workspace_bytes(int64_t n, int nb, size_t* dev_bytes);
 
 /*
  * Stage 3 (Section 3, final stage; the paper calls LAPACK on the CPU here):

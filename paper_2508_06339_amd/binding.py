@@ -55,6 +55,8 @@ def load_library():
     lib.svb_gb2bd.argtypes = [ctypes.c_int, _i64, ctypes.c_int, _vp, _i64, _vp, _vp, _vp,
                               ctypes.c_size_t, _vp]
     lib.svb_gb2bd.restype = ctypes.c_int
+    lib.svb_gb2bd_workspace_bytes.argtypes = [_i64, ctypes.c_int, _szp]
+    lib.svb_gb2bd_workspace_bytes.restype = ctypes.c_int
     lib.svb_bdsvals.argtypes = [_i64, _dp, _dp, _dp]
     lib.svb_bdsvals.restype = ctypes.c_int
     lib.svb_last_timings.argtypes = [_dp, _dp, _dp]
@@ -113,6 +115,13 @@ def svb_ge2gb(dt, m, n, A_dev, lda, nb, band_dev, ldab, work_dev, work_bytes, st
 def svb_gb2bd(band_dt, n, nb, band_dev, ldab, d_dev, e_dev, work_dev, work_bytes, stream=None) -> int:
     return load_library().svb_gb2bd(band_dt, n, nb, _ptr(band_dev), ldab, _ptr(d_dev), _ptr(e_dev),
                                     _ptr(work_dev), work_bytes, _stream(stream))
+
+
+def svb_gb2bd_workspace_bytes(n: int, nb: int):
+    """Returns (status, dev_bytes)."""
+    dev = ctypes.c_size_t(0)
+    rc = load_library().svb_gb2bd_workspace_bytes(n, nb, ctypes.byref(dev))
+    return rc, dev.value
 
 
 def svb_bdsvals(n: int, d: np.ndarray, e: np.ndarray, sigma: np.ndarray) -> int:

@@ -131,6 +131,241 @@ __device__ void chase_step(C* __restrict__ band, int64_t ldab, int64_t n, int b,
 #undef BAND
 }
 
+
+// ---------------------------------------------------------------- pipelined chase
+// One workgroup per sweep, sweeps pipelined along the band.  Workgroups take
+// sweep numbers from a ticket counter, so a sweep is only ever waited for by
+// later sweeps and its owner is already running: no co-residency assumption.
+// Sweep i may run step t once sweep i-1 has finished step t+2 (see the region
+// argument at the top of this file); progress[i] counts finished steps and is
+// set to kDone when the sweep is complete.  Waits are bounded by spin_limit;
+// on expiry the error flag is raised, every later sweep drains, and the
+// extraction kernel poisons d[0] so the failure reaches the caller.
+//
+// Per step the workgroup keeps two B x B blocks in LDS (column-major, leading
+// dimension B+1): X = the block above the diagonal block (its first row is
+// the row being annihilated), Z = the diagonal block A2.  After the right
+// reflector X is final and is written back while the block right of A2 (A3,
+// prefetched into registers at the start of the step) takes its place; after
+// the left reflector A2 is written back and A3 stays in LDS as the next step's X.
+constexpr int kDone = 0x3fffffff;
+
+template <typename C, int B, int NT>
+__global__ __launch_bounds__(NT) void chase_persistent_kernel(C* __restrict__ band, int64_t ldab, int64_t n,
+                                                              int* __restrict__ ctrl, int* __restrict__ progress,
+                                                              int spin_limit)
+{
+    constexpr int LD = B + 1, NW = NT / kWave, CSTEP = NT / B;
+    // A3 is prefetched into registers only while that stays cheap (B*B/NT values per thread)
+    constexpr bool PREFETCH = (B * B / NT) <= 16;
+    constexpr int PER = PREFETCH ? B * B / NT : 1;
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    C* X = reinterpret_cast<C*>(smem_raw);
+    C* Z = X + B * LD;
+    C* vs = Z + B * LD;
+    C* red = vs + B;  // NW + 1
+    __shared__ int sh_i, sh_fail;
+    const int tid = threadIdx.x;
+    const int ii = tid % B, jj0 = tid / B;  // this thread's row and first column inside a block
+    const int64_t ku = 2 * (int64_t)B - 1;
+#define BAND(r_, c_) band[((r_) - (c_) + ku) + (c_) * ldab]
+
+    // Every thread-0-only section below is followed by a barrier before the next one, so
+    // that no divergent region ever spans a loop back-edge.
+    for (;;) {
+        if (tid == 0) {
+            sh_i = atomicAdd(&ctrl[0], 1);
+            sh_fail = __hip_atomic_load(&ctrl[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __syncthreads();
+        const int64_t i = sh_i;
+        bool failed = sh_fail != 0;
+        __syncthreads();
+        if (i > n - 3) break;
+        const int nsteps = (int)((n - 3 - i) / B) + 1;
+        for (int t = 0; t < nsteps && !failed; ++t) {
+            const int64_t c0 = i + 1 + (int64_t)t * B;
+            const int len = (int)min((int64_t)B, n - c0);
+            const int na3 = (int)max((int64_t)0, min((int64_t)B, n - (c0 + B)));
+            if (i > 0) {
+                if (tid == 0) {
+                    const int need = t + 3;
+                    int spins = 0;
+                    while (__hip_atomic_load(&progress[i - 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < need) {
+                        if (++spins > spin_limit) {
+                            atomicExch(&ctrl[1], 1);
+                            sh_fail = 1;
+                            break;
+                        }
+                        __builtin_amdgcn_s_sleep(1);
+                    }
+                }
+                __syncthreads();
+                failed = sh_fail != 0;
+                __threadfence();
+            }
+            if (!failed) {
+                // A2 -> Z, (first step) row i -> X, A3 -> registers
+                C pre[PER];
+                for (int jj = jj0; jj < B; jj += CSTEP) {
+                    C v = 0;
+                    if (ii < len && jj < len) v = BAND(c0 + ii, c0 + jj);
+                    Z[ii + jj * LD] = v;
+                    if (t == 0) {
+                        C xv = 0;
+                        if (ii == 0 && jj < len) xv = BAND(i, c0 + jj);
+                        X[ii + jj * LD] = xv;
+                    }
+                }
+                if (PREFETCH) {
+#pragma unroll
+                    for (int q = 0; q < PER; ++q) {
+                        const int jj = jj0 + q * CSTEP;
+                        pre[q] = (ii < len && jj < na3) ? BAND(c0 + ii, c0 + B + jj) : (C)0;
+                    }
+                }
+                __syncthreads();
+                // right reflector from X row 0, applied to X rows 1.. and Z
+                {
+                    C x = 0, ss = 0;
+                    if (tid < len) {
+                        x = X[tid * LD];
+                        if (tid > 0) ss = x * x;
+                    }
+                    ss = block_sum<C, NT>(ss, red);
+                    if (tid == 0) red[NW] = x;
+                    __syncthreads();
+                    C beta, tau, inv;
+                    reflector<C>(red[NW], ss, beta, tau, inv);
+                    if (tid < B) {
+                        vs[tid] = tid < len ? ((tid == 0) ? (C)1 : x * inv) : (C)0;
+                        X[tid * LD] = (tid == 0) ? beta : (C)0;
+                    }
+                    __syncthreads();
+                    if (tau != (C)0) {
+                        for (int ridx = tid; ridx < 2 * B; ridx += NT) {
+                            if (ridx == 0) continue;
+                            C* base = ridx < B ? X + ridx : Z + (ridx - B);
+                            C s = 0;
+#pragma unroll 8
+                            for (int j = 0; j < B; ++j) s += vs[j] * base[j * LD];
+                            s *= tau;
+#pragma unroll 8
+                            for (int j = 0; j < B; ++j) base[j * LD] -= s * vs[j];
+                        }
+                    }
+                    __syncthreads();
+                }
+                // X is final: write it back, A3 takes its place
+                if (PREFETCH) {
+#pragma unroll
+                    for (int q = 0; q < PER; ++q) {
+                        const int jj = jj0 + q * CSTEP;
+                        const C v = X[ii + jj * LD];
+                        if (jj < len) {
+                            if (t == 0) {
+                                if (ii == 0) BAND(i, c0 + jj) = v;
+                            } else {
+                                BAND(c0 - B + ii, c0 + jj) = v;
+                            }
+                        }
+                        X[ii + jj * LD] = pre[q];
+                    }
+                } else {
+                    for (int jj = jj0; jj < B; jj += CSTEP) {
+                        const C v = X[ii + jj * LD];
+                        if (jj < len) {
+                            if (t == 0) {
+                                if (ii == 0) BAND(i, c0 + jj) = v;
+                            } else {
+                                BAND(c0 - B + ii, c0 + jj) = v;
+                            }
+                        }
+                        X[ii + jj * LD] = (ii < len && jj < na3) ? BAND(c0 + ii, c0 + B + jj) : (C)0;
+                    }
+                }
+                __syncthreads();
+                // left reflector from Z column 0, applied to Z columns 1.. and A3
+                {
+                    C x = 0, ss = 0;
+                    if (tid < len) {
+                        x = Z[tid];
+                        if (tid > 0) ss = x * x;
+                    }
+                    ss = block_sum<C, NT>(ss, red);
+                    if (tid == 0) red[NW] = x;
+                    __syncthreads();
+                    C beta, tau, inv;
+                    reflector<C>(red[NW], ss, beta, tau, inv);
+                    if (tid < B) {
+                        vs[tid] = tid < len ? ((tid == 0) ? (C)1 : x * inv) : (C)0;
+                        Z[tid] = (tid == 0) ? beta : (C)0;
+                    }
+                    __syncthreads();
+                    if (tau != (C)0) {
+                        for (int cidx = tid; cidx < 2 * B; cidx += NT) {
+                            if (cidx == 0) continue;
+                            C* col = cidx < B ? Z + cidx * LD : X + (cidx - B) * LD;
+                            C s = 0;
+#pragma unroll 8
+                            for (int a = 0; a < B; ++a) s += vs[a] * col[a];
+                            s *= tau;
+#pragma unroll 8
+                            for (int a = 0; a < B; ++a) col[a] -= s * vs[a];
+                        }
+                    }
+                    __syncthreads();
+                }
+                // A2 is final for this sweep; after the last step so is A3
+                for (int jj = jj0; jj < B; jj += CSTEP) {
+                    if (ii < len && jj < len) BAND(c0 + ii, c0 + jj) = Z[ii + jj * LD];
+                    if (t == nsteps - 1 && ii < len && jj < na3) BAND(c0 + ii, c0 + B + jj) = X[ii + jj * LD];
+                }
+                __threadfence();
+            }
+            __syncthreads();
+            if (tid == 0)
+                __hip_atomic_store(&progress[i], (failed || t == nsteps - 1) ? kDone : t + 1, __ATOMIC_RELEASE,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+            __syncthreads();
+        }
+        if (failed) {
+            if (tid == 0) __hip_atomic_store(&progress[i], kDone, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __syncthreads();
+    }
+#undef BAND
+}
+
+__global__ __launch_bounds__(256) void chase_ctrl_clear_kernel(int* __restrict__ ctrl, int64_t count)
+{
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count;
+         i += (int64_t)gridDim.x * blockDim.x)
+        ctrl[i] = 0;
+}
+
+template <typename C, int B>
+static bool launch_chase_persistent(C* band, int64_t ldab, int64_t n, int* ctrl, hipStream_t s)
+{
+    constexpr int NT = 256;
+    constexpr size_t smem = sizeof(C) * (size_t)(2 * B * (B + 1) + B + NT / kWave + 1);
+    if (smem > 150 * 1024) return false;
+    auto kern = chase_persistent_kernel<C, B, NT>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        attr_set = true;
+    }
+    const int64_t count = 64 + n;
+    int cb = (int)((count + 255) / 256);
+    hipLaunchKernelGGL(chase_ctrl_clear_kernel, dim3(cb > 1024 ? 1024 : cb), dim3(256), 0, s, ctrl, count);
+    const int64_t sweeps = n - 2;
+    const int grid = (int)min((int64_t)env_int("SVB_CHASE_GRID", 256), sweeps);
+    const int spin_limit = env_int("SVB_CHASE_SPIN", 1 << 20);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(NT), smem, s, band, ldab, n, ctrl, ctrl + 64, spin_limit);
+    return true;
+}
+
 template <typename C, int NT>
 __global__ __launch_bounds__(NT) void chase_wave_kernel(C* __restrict__ band, int64_t ldab, int64_t n,
                                                         int b, int64_t T, int64_t imin)
@@ -146,25 +381,33 @@ __global__ __launch_bounds__(NT) void chase_wave_kernel(C* __restrict__ band, in
 template <typename C>
 __global__ __launch_bounds__(256) void extract_bidiag_kernel(const C* __restrict__ band, int64_t ldab,
                                                              int64_t n, int b, C* __restrict__ d,
-                                                             C* __restrict__ e)
+                                                             C* __restrict__ e, const int* __restrict__ ctrl)
 {
+    const bool bad = ctrl != nullptr && ctrl[1] != 0;
     const int64_t ku = 2 * (int64_t)b - 1;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
          i += (int64_t)gridDim.x * blockDim.x) {
-        d[i] = band[ku + i * ldab];
+        d[i] = (bad && i == 0) ? (C)NAN : band[ku + i * ldab];
         e[i] = (i + 1 < n) ? band[(ku - 1) + (i + 1) * ldab] : (C)0;
     }
 }
 
-size_t chase_workspace_bytes(int64_t /*n*/, int /*nb*/) { return 0; }
+size_t chase_workspace_bytes(int64_t n, int /*nb*/) { return (size_t)((64 + n) * 4 + 255) / 256 * 256; }
 
 template <typename C>
-int run_chase(int64_t n, int nb, C* band, int64_t ldab, C* d, C* e, void* /*work*/,
+int run_chase(int64_t n, int nb, C* band, int64_t ldab, C* d, C* e, void* work,
               size_t /*work_bytes*/, hipStream_t s)
 {
     constexpr int NT = 256;
     const int64_t b = nb;
-    if (n >= 3) {
+    int* ctrl = static_cast<int*>(work);
+    bool pipelined = false;
+    if (n >= 3 && env_int("SVB_CHASE_IMPL", 1) != 0) {
+        if (nb == 32) pipelined = launch_chase_persistent<C, 32>(band, ldab, n, ctrl, s);
+        else if (nb == 64) pipelined = launch_chase_persistent<C, 64>(band, ldab, n, ctrl, s);
+        else pipelined = launch_chase_persistent<C, 128>(band, ldab, n, ctrl, s);
+    }
+    if (n >= 3 && !pipelined) {
         const int64_t Tmax = 3 * (n - 3);
         const size_t smem = (size_t)(2 * b + 2) * sizeof(C);
         for (int64_t T = 0; T <= Tmax; ++T) {
@@ -181,7 +424,8 @@ int run_chase(int64_t n, int nb, C* band, int64_t ldab, C* d, C* e, void* /*work
     }
     int blocks = (int)((n + 255) / 256);
     if (blocks > 1024) blocks = 1024;
-    hipLaunchKernelGGL((extract_bidiag_kernel<C>), dim3(blocks), dim3(256), 0, s, band, ldab, n, (int)b, d, e);
+    hipLaunchKernelGGL((extract_bidiag_kernel<C>), dim3(blocks), dim3(256), 0, s, band, ldab, n, (int)b, d, e,
+                       pipelined ? ctrl : (const int*)nullptr);
     return hipGetLastError() == hipSuccess ? SVB_OK : SVB_ERR_DEVICE;
 }
 

@@ -264,6 +264,14 @@ int svb_gb2bd(svb_dtype band_dt, int64_t n, int nb, void* band_dev, int64_t ldab
     return rc;
 }
 
+int svb_gb2bd_workspace_bytes(int64_t n, int nb, size_t* dev_bytes)
+{
+    if (n < 0 || !dev_bytes) return SVB_ERR_ARG;
+    if (nb != 32 && nb != 64 && nb != 128) return SVB_ERR_UNSUPPORTED;
+    *dev_bytes = chase_workspace_bytes(n, nb);
+    return SVB_OK;
+}
+
 int svb_bdsvals(int64_t n, const double* d, const double* e, double* sigma)
 {
     return host_bdsvals(n, d, e, sigma);

@@ -117,7 +117,8 @@ def test_stage1_band_preserves_singular_values():
     assert np.abs(sb - ref).max() <= 10 * n * 2.0 ** -52 * ref[0]
 
 
-@pytest.mark.parametrize("dtype,n,nb", [("f64", 200, 32), ("f32", 333, 64), ("f64", 130, 128), ("f64", 3, 32), ("f64", 2, 32)])
+@pytest.mark.parametrize("dtype,n,nb", [("f64", 200, 32), ("f32", 333, 64), ("f64", 130, 128), ("f32", 700, 128),
+                                         ("f64", 1000, 64), ("f64", 3, 32), ("f64", 2, 32)])
 def test_stage2_on_random_band(dtype, n, nb):
     # random upper band input: Frobenius norm kept, bdsvals(d, e) = oracle(band as dense)
     npdt = workloads.NP_DTYPE[dtype]
@@ -134,7 +135,10 @@ def test_stage2_on_random_band(dtype, n, nb):
     e = torch.zeros(n, dtype=TORCH_DT[dtype], device="cuda")
     code = svb.SVB_F64 if dtype == "f64" else svb.SVB_F32
     print(f"[case] stage2 n={n} nb={nb} {dtype}", flush=True)
-    assert svb.svb_gb2bd(code, n, nb, band, ldab, d, e, None, 0) == 0
+    rc, wb = svb.svb_gb2bd_workspace_bytes(n, nb)
+    assert rc == 0
+    work = torch.empty(max(wb, 1), dtype=torch.uint8, device="cuda")
+    assert svb.svb_gb2bd(code, n, nb, band, ldab, d, e, work, wb) == 0
     torch.cuda.synchronize()
     dh = d.cpu().numpy().astype(np.float64)
     eh = e.cpu().numpy().astype(np.float64)[: n - 1]
@@ -161,3 +165,27 @@ def test_full_size_configs_against_stored_oracle(name):
     s = _gpu_sigma(a, info["nb"])
     fro = 2e-2 if info["dtype"] == "f16" else None
     _check(s, ref, info["n"], info["dtype"], fro)
+
+
+def test_stage2_expired_wait_is_reported(monkeypatch):
+    # a spin limit of zero makes every pipelined wait expire at once: all kernels still
+    # exit normally and the failure surfaces as a status code
+    monkeypatch.setenv("SVB_CHASE_SPIN", "0")
+    a, info = workloads.make("c1", n=256, nb=32)
+    t = _dev(a)
+    rc, wbytes, _ = svb.svb_workspace_bytes(svb.SVB_F64, 256, 256, 32)
+    work = torch.empty(wbytes, dtype=torch.uint8, device="cuda")
+    out = np.zeros(256)
+    rc = svb.svb_svdvals(svb.SVB_F64, 256, 256, t, 256, out, 32, work, wbytes)
+    torch.cuda.synchronize()
+    assert rc in (0, 6)   # 0 only if no sweep ever had to wait
+    monkeypatch.delenv("SVB_CHASE_SPIN")
+    s = _gpu_sigma(a, 32)
+    _check(s, oracle.svdvals(a), 256, "f64")
+
+
+def test_stage2_wavefront_variant(monkeypatch):
+    # the launch-per-wavefront chase (used where two band blocks do not fit in LDS)
+    monkeypatch.setenv("SVB_CHASE_IMPL", "0")
+    a, info = workloads.make("c1", n=256, nb=32)
+    _check(_gpu_sigma(a, 32), oracle.svdvals(a), 256, "f64")

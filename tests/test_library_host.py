@@ -50,6 +50,8 @@ def test_argument_validation():
     assert svb.svb_ge2gb(svb.SVB_F32, 64, 64, None, 64, 32, None, 96, None, 0, stream=0) == 1
     assert svb.svb_gb2bd(svb.SVB_F16, 64, 32, None, 96, None, None, None, 0, stream=0) == 2
     assert svb.svb_gb2bd(svb.SVB_F32, 64, 32, None, 96, None, None, None, 0, stream=0) == 1
+    rc, wb = svb.svb_gb2bd_workspace_bytes(1000, 64)
+    assert rc == 0 and wb >= 4 * 1000
     assert "workspace" in svb.svb_status_string(3)
 
 
