@@ -166,6 +166,12 @@ __global__ __launch_bounds__(NT) void chase_persistent_kernel(C* __restrict__ ba
     C* red = vs + B;  // NW + 1
     __shared__ int sh_i, sh_fail;
     const int tid = threadIdx.x;
+#ifdef SVB_CHASE_TIMING
+    unsigned long long tacc[6] = {0, 0, 0, 0, 0, 0}, tlast = 0, nstep_acc = 0;
+#define TMARK(slot_) do { if (tid == 0) { unsigned long long now_ = wall_clock64(); tacc[slot_] += now_ - tlast; tlast = now_; } } while (0)
+#else
+#define TMARK(slot_) do { } while (0)
+#endif
     const int ii = tid % B, jj0 = tid / B;  // this thread's row and first column inside a block
     const int64_t ku = 2 * (int64_t)B - 1;
 #define BAND(r_, c_) band[((r_) - (c_) + ku) + (c_) * ldab]
@@ -187,6 +193,9 @@ __global__ __launch_bounds__(NT) void chase_persistent_kernel(C* __restrict__ ba
             const int64_t c0 = i + 1 + (int64_t)t * B;
             const int len = (int)min((int64_t)B, n - c0);
             const int na3 = (int)max((int64_t)0, min((int64_t)B, n - (c0 + B)));
+#ifdef SVB_CHASE_TIMING
+            if (tid == 0) { tlast = wall_clock64(); ++nstep_acc; }
+#endif
             if (i > 0) {
                 if (tid == 0) {
                     const int need = t + 3;
@@ -202,8 +211,10 @@ __global__ __launch_bounds__(NT) void chase_persistent_kernel(C* __restrict__ ba
                 }
                 __syncthreads();
                 failed = sh_fail != 0;
+                TMARK(0);
                 __threadfence();
             }
+            TMARK(1);
             if (!failed) {
                 // A2 -> Z, (first step) row i -> X, A3 -> registers
                 C pre[PER];
@@ -225,6 +236,7 @@ __global__ __launch_bounds__(NT) void chase_persistent_kernel(C* __restrict__ ba
                     }
                 }
                 __syncthreads();
+                TMARK(2);
                 // right reflector from X row 0, applied to X rows 1.. and Z
                 {
                     C x = 0, ss = 0;
@@ -256,6 +268,7 @@ __global__ __launch_bounds__(NT) void chase_persistent_kernel(C* __restrict__ ba
                     }
                     __syncthreads();
                 }
+                TMARK(3);
                 // X is final: write it back, A3 takes its place
                 if (PREFETCH) {
 #pragma unroll
@@ -316,6 +329,7 @@ __global__ __launch_bounds__(NT) void chase_persistent_kernel(C* __restrict__ ba
                     }
                     __syncthreads();
                 }
+                TMARK(4);
                 // A2 is final for this sweep; after the last step so is A3
                 for (int jj = jj0; jj < B; jj += CSTEP) {
                     if (ii < len && jj < len) BAND(c0 + ii, c0 + jj) = Z[ii + jj * LD];
@@ -324,6 +338,7 @@ __global__ __launch_bounds__(NT) void chase_persistent_kernel(C* __restrict__ ba
                 __threadfence();
             }
             __syncthreads();
+            TMARK(5);
             if (tid == 0)
                 __hip_atomic_store(&progress[i], (failed || t == nsteps - 1) ? kDone : t + 1, __ATOMIC_RELEASE,
                                    __HIP_MEMORY_SCOPE_AGENT);
@@ -334,6 +349,14 @@ __global__ __launch_bounds__(NT) void chase_persistent_kernel(C* __restrict__ ba
         }
         __syncthreads();
     }
+#ifdef SVB_CHASE_TIMING
+    if (tid == 0) {
+        unsigned long long* acc = reinterpret_cast<unsigned long long*>(ctrl + 8);
+        for (int q = 0; q < 6; ++q) atomicAdd(&acc[q], tacc[q]);
+        atomicAdd(&acc[6], nstep_acc);
+    }
+#endif
+#undef TMARK
 #undef BAND
 }
 
