@@ -120,9 +120,26 @@ int svb_gb2bd_workspace_bytes(int64_t n, int nb, size_t* dev_bytes);
 int svb_bdsvals(int64_t n, const double* d, const double* e, double* sigma);
 
 /*
+ * Stage 3 on the device: the same bisection as svb_bdsvals, one singular value
+ * per GPU thread, for callers that keep the bidiagonal in device memory
+ * (svb_svdvals uses it unless the environment variable SVB_STAGE3=host is set).
+ *   band_dt   SVB_F64 or SVB_F32: type of d, e and sigma.
+ *   d_dev, e_dev [dev] in: n and n-1 entries (layout of svb_gb2bd's outputs).
+ *   sigma_dev [dev] out: n values, descending.  Non-finite input gives NaNs.
+ *   rel_tol   bisection stops at interval width rel_tol * sigma (0 = 2^-52 for
+ *             SVB_F64 and 2^-29 for SVB_F32).
+ *   work_dev  [dev] scratch of svb_bdsvals_dev_workspace_bytes(n) bytes.
+ * Asynchronous.
+ */
+int svb_bdsvals_dev_workspace_bytes(int64_t n, size_t* dev_bytes);
+int svb_bdsvals_dev(svb_dtype band_dt, int64_t n, const void* d_dev, const void* e_dev, void* sigma_dev,
+                    double rel_tol, void* work_dev, size_t work_bytes, void* stream);
+
+/*
  * Wall-clock seconds of the stages of the most recent svb_svdvals call of
- * this process (stage 1 and 2 from HIP events on the caller's stream, stage 3
- * from the host clock).  Any pointer may be NULL.
+ * this process (stages 1 and 2, and stage 3 when it runs on the device, from
+ * HIP events on the caller's stream; a host stage 3 from the host clock).  Any
+ * pointer may be NULL.
  */
 int svb_last_timings(double* t_stage1, double* t_stage2, double* t_stage3);
 

@@ -57,6 +57,10 @@ def load_library():
     lib.svb_gb2bd.restype = ctypes.c_int
     lib.svb_gb2bd_workspace_bytes.argtypes = [_i64, ctypes.c_int, _szp]
     lib.svb_gb2bd_workspace_bytes.restype = ctypes.c_int
+    lib.svb_bdsvals_dev_workspace_bytes.argtypes = [_i64, _szp]
+    lib.svb_bdsvals_dev_workspace_bytes.restype = ctypes.c_int
+    lib.svb_bdsvals_dev.argtypes = [ctypes.c_int, _i64, _vp, _vp, _vp, ctypes.c_double, _vp, ctypes.c_size_t, _vp]
+    lib.svb_bdsvals_dev.restype = ctypes.c_int
     lib.svb_bdsvals.argtypes = [_i64, _dp, _dp, _dp]
     lib.svb_bdsvals.restype = ctypes.c_int
     lib.svb_last_timings.argtypes = [_dp, _dp, _dp]
@@ -122,6 +126,18 @@ def svb_gb2bd_workspace_bytes(n: int, nb: int):
     dev = ctypes.c_size_t(0)
     rc = load_library().svb_gb2bd_workspace_bytes(n, nb, ctypes.byref(dev))
     return rc, dev.value
+
+
+def svb_bdsvals_dev_workspace_bytes(n: int):
+    """Returns (status, dev_bytes)."""
+    dev = ctypes.c_size_t(0)
+    rc = load_library().svb_bdsvals_dev_workspace_bytes(n, ctypes.byref(dev))
+    return rc, dev.value
+
+
+def svb_bdsvals_dev(band_dt, n, d_dev, e_dev, sigma_dev, rel_tol, work_dev, work_bytes, stream=None) -> int:
+    return load_library().svb_bdsvals_dev(band_dt, n, _ptr(d_dev), _ptr(e_dev), _ptr(sigma_dev), float(rel_tol),
+                                          _ptr(work_dev), work_bytes, _stream(stream))
 
 
 def svb_bdsvals(n: int, d: np.ndarray, e: np.ndarray, sigma: np.ndarray) -> int:

@@ -1,0 +1,118 @@
+// Stage 3 on the device: singular values of the upper bidiagonal (d, e) by
+// bisection (paper Section 3, final stage; the paper solves the bidiagonal on
+// the CPU with LAPACK and names it the cheapest stage.  Once stages 1-2 run
+// in tens of milliseconds a host solve dominates time-to-singular-values, so
+// the same bisection that the host entry point svb_bdsvals performs is also
+// available on the GPU, one singular value per thread).
+//
+// Count of singular values below x: with B^T B - x^2 I = L D L^T,
+//   t_1 = -x^2,  D_j = d_j^2 + t_j,  t_{j+1} = -x^2 + e_j^2 * t_j / D_j,
+// the number of negative D_j (the differential stationary qd form of the Sturm
+// sequence: one division per row, n rows).  Squares are taken after scaling by
+// the largest entry, always in fp64.
+#include "svb_internal.h"
+
+namespace svb {
+
+namespace {
+
+constexpr int kPrepThreads = 1024;
+
+// ws[0] = scale, ws[1] = upper bound for sigma_max / scale; d2 = ws + 8, e2 = d2 + n.
+template <typename C>
+__global__ __launch_bounds__(kPrepThreads) void bd_prep_kernel(const C* __restrict__ d, const C* __restrict__ e,
+                                                               int64_t n, double* __restrict__ ws)
+{
+    __shared__ double red[2][kPrepThreads / kWave];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    double zmax = 0.0, bound = 0.0;
+    bool bad = false;
+    for (int64_t j = tid; j < n; j += kPrepThreads) {
+        const double a = fabs((double)d[j]);
+        const double b = j + 1 < n ? fabs((double)e[j]) : 0.0;
+        const double bp = j > 0 ? fabs((double)e[j - 1]) : 0.0;
+        bad = bad || !(a <= 1.79e308) || !(b <= 1.79e308);
+        zmax = fmax(zmax, fmax(a, b));
+        bound = fmax(bound, a + fmax(b, bp));
+    }
+    if (bad) { zmax = NAN; bound = NAN; }
+    for (int off = 32; off > 0; off >>= 1) {
+        const double z2 = __shfl_xor(zmax, off, kWave), b2 = __shfl_xor(bound, off, kWave);
+        zmax = (zmax != zmax || z2 != z2) ? NAN : fmax(zmax, z2);
+        bound = (bound != bound || b2 != b2) ? NAN : fmax(bound, b2);
+    }
+    if (lane == 0) { red[0][wave] = zmax; red[1][wave] = bound; }
+    __syncthreads();
+    zmax = 0.0; bound = 0.0;
+    for (int w = 0; w < kPrepThreads / kWave; ++w) {
+        const double z2 = red[0][w], b2 = red[1][w];
+        zmax = (zmax != zmax || z2 != z2) ? NAN : fmax(zmax, z2);
+        bound = (bound != bound || b2 != b2) ? NAN : fmax(bound, b2);
+    }
+    const double scale = zmax > 0.0 ? zmax : 1.0;  // NaN stays NaN through the comparisons below
+    if (tid == 0) {
+        ws[0] = (zmax != zmax) ? NAN : scale;
+        ws[1] = bound / scale * (1.0 + 1e-14) + 1e-300;
+    }
+    double* d2 = ws + 8;
+    double* e2 = d2 + n;
+    for (int64_t j = tid; j < n; j += kPrepThreads) {
+        const double a = (double)d[j] / scale;
+        const double b = j + 1 < n ? (double)e[j] / scale : 0.0;
+        d2[j] = a * a;
+        e2[j] = b * b;
+    }
+}
+
+template <typename C>
+__global__ __launch_bounds__(64) void bd_bisect_kernel(const double* __restrict__ ws, int64_t n,
+                                                        C* __restrict__ sigma, double rel_tol)
+{
+    const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;  // ascending index
+    const double scale = ws[0], hi0 = ws[1];
+    const double* __restrict__ d2 = ws + 8;
+    const double* __restrict__ e2 = d2 + n;
+    if (k >= n) return;
+    if (scale != scale) {  // non-finite input: poison the output, the caller maps it to a status
+        sigma[n - 1 - k] = (C)NAN;
+        return;
+    }
+    const double pivmin = 1e-300;
+    double lo = 0.0, hi = hi0;
+    for (int it = 0; it < 200; ++it) {
+        const double mid = 0.5 * (lo + hi);
+        if (!(hi - lo > rel_tol * hi + 1e-38 * hi0) || !(mid > lo && mid < hi)) break;
+        const double x2 = mid * mid;
+        double t = -x2;
+        int64_t cnt = 0;
+        for (int64_t j = 0; j < n; ++j) {
+            double D = d2[j] + t;
+            if (fabs(D) < pivmin) D = -pivmin;
+            cnt += D < 0.0 ? 1 : 0;
+            double r = __builtin_amdgcn_rcp(D);      // reciprocal + one Newton step instead of a full division
+            r = fma(r, fma(-D, r, 1.0), r);
+            t = e2[j] * (t * r) - x2;
+        }
+        if (cnt >= k + 1) hi = mid;
+        else lo = mid;
+    }
+    sigma[n - 1 - k] = (C)(0.5 * (lo + hi) * scale);
+}
+
+}  // namespace
+
+size_t bdsvals_dev_workspace_bytes(int64_t n) { return (size_t)(8 + 2 * n) * sizeof(double); }
+
+template <typename C>
+int run_bdsvals_dev(int64_t n, const C* d, const C* e, C* sigma, void* work, double rel_tol, hipStream_t s)
+{
+    double* ws = static_cast<double*>(work);
+    hipLaunchKernelGGL((bd_prep_kernel<C>), dim3(1), dim3(kPrepThreads), 0, s, d, e, n, ws);
+    hipLaunchKernelGGL((bd_bisect_kernel<C>), dim3((unsigned)((n + 63) / 64)), dim3(64), 0, s, ws, n, sigma, rel_tol);
+    return hipGetLastError() == hipSuccess ? SVB_OK : SVB_ERR_DEVICE;
+}
+
+template int run_bdsvals_dev<double>(int64_t, const double*, const double*, double*, void*, double, hipStream_t);
+template int run_bdsvals_dev<float>(int64_t, const float*, const float*, float*, void*, double, hipStream_t);
+
+}  // namespace svb

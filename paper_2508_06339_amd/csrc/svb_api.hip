@@ -1,5 +1,6 @@
 // C-ABI entry points and the host-side stage driver.
 #include <chrono>
+#include <cmath>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -48,7 +49,7 @@ struct Carve {
     size_t w_elems;      // W of the largest level
     size_t t_elems;      // T factors of one level
     size_t band_elems, de_elems;
-    size_t off_V, off_Y, off_W, off_T, off_band, off_d, off_e, off_err, total;
+    size_t off_V, off_Y, off_W, off_T, off_band, off_d, off_e, off_sig, off_s3, off_err, total;
 };
 
 Carve carve(svb_dtype dt, int64_t n, int nb)
@@ -69,6 +70,8 @@ Carve carve(svb_dtype dt, int64_t n, int nb)
     c.off_band = off; off += align_up(c.band_elems * cs);
     c.off_d = off; off += align_up(c.de_elems * cs);
     c.off_e = off; off += align_up(c.de_elems * cs);
+    c.off_sig = off; off += align_up(c.de_elems * cs);
+    c.off_s3 = off; off += align_up(bdsvals_dev_workspace_bytes(n));
     c.off_err = off; off += 256;
     off += chase_workspace_bytes(n, nb);
     c.total = off;
@@ -272,6 +275,28 @@ int svb_gb2bd_workspace_bytes(int64_t n, int nb, size_t* dev_bytes)
     return SVB_OK;
 }
 
+int svb_bdsvals_dev_workspace_bytes(int64_t n, size_t* dev_bytes)
+{
+    if (n < 0 || !dev_bytes) return SVB_ERR_ARG;
+    *dev_bytes = bdsvals_dev_workspace_bytes(n);
+    return SVB_OK;
+}
+
+int svb_bdsvals_dev(svb_dtype band_dt, int64_t n, const void* d_dev, const void* e_dev, void* sigma_dev,
+                    double rel_tol, void* work_dev, size_t work_bytes, void* stream)
+{
+    if (n < 0) return SVB_ERR_ARG;
+    if (band_dt != SVB_F64 && band_dt != SVB_F32) return SVB_ERR_UNSUPPORTED;
+    if (n == 0) return SVB_OK;
+    if (!d_dev || !e_dev || !sigma_dev || !work_dev || rel_tol < 0.0) return SVB_ERR_ARG;
+    if (work_bytes < bdsvals_dev_workspace_bytes(n)) return SVB_ERR_WORKSPACE;
+    if (rel_tol == 0.0) rel_tol = band_dt == SVB_F64 ? 0x1p-52 : 0x1p-29;
+    hipStream_t s = (hipStream_t)stream;
+    if (band_dt == SVB_F64)
+        return run_bdsvals_dev<double>(n, (const double*)d_dev, (const double*)e_dev, (double*)sigma_dev, work_dev, rel_tol, s);
+    return run_bdsvals_dev<float>(n, (const float*)d_dev, (const float*)e_dev, (float*)sigma_dev, work_dev, rel_tol, s);
+}
+
 int svb_bdsvals(int64_t n, const double* d, const double* e, double* sigma)
 {
     return host_bdsvals(n, d, e, sigma);
@@ -305,9 +330,31 @@ int svb_svdvals(svb_dtype dt, int64_t m, int64_t n, void* A_dev, int64_t lda, vo
         rc = svb_gb2bd(bdt, n, nb, band, ldab, dd, de, cw, chase_workspace_bytes(n, nb), s);
     }
     (void)hipEventRecord(ev2, s);
-    std::vector<double> hd((size_t)n), he((size_t)n), hs((size_t)n);
-    if (rc == SVB_OK) {
-        const size_t cs = compute_size(dt);
+    const bool host3 = [] { const char* v = std::getenv("SVB_STAGE3"); return v && std::strcmp(v, "host") == 0; }();
+    const size_t cs = compute_size(dt);
+    double total3 = 0.0;
+    hipEvent_t ev3 = nullptr;
+    std::vector<double> hs((size_t)n);
+    if (rc == SVB_OK && !host3) {
+        // stage 3 on the device, then one copy of n values
+        void* sig = w + cv.off_sig;
+        const double tol = dt == SVB_F64 ? 0x1p-52 : 0x1p-29;
+        if (dt == SVB_F64)
+            rc = run_bdsvals_dev<double>(n, (const double*)dd, (const double*)de, (double*)sig, w + cv.off_s3, tol, s);
+        else
+            rc = run_bdsvals_dev<float>(n, (const float*)dd, (const float*)de, (float*)sig, w + cv.off_s3, tol, s);
+        if (hipEventCreate(&ev3) == hipSuccess) (void)hipEventRecord(ev3, s);
+        if (rc == SVB_OK &&
+            (hipMemcpyAsync(S_out_host, sig, (size_t)n * cs, hipMemcpyDeviceToHost, s) != hipSuccess ||
+             hipStreamSynchronize(s) != hipSuccess))
+            rc = SVB_ERR_DEVICE;
+        if (rc == SVB_OK) {
+            const bool bad = dt == SVB_F64 ? std::isnan(static_cast<double*>(S_out_host)[0])
+                                           : std::isnan(static_cast<float*>(S_out_host)[0]);
+            if (bad) rc = SVB_ERR_NONFINITE;
+        }
+    } else if (rc == SVB_OK) {
+        std::vector<double> hd((size_t)n), he((size_t)n);
         std::vector<unsigned char> raw(2 * (size_t)n * cs);
         if (hipMemcpyAsync(raw.data(), dd, (size_t)n * cs, hipMemcpyDeviceToHost, s) != hipSuccess ||
             hipMemcpyAsync(raw.data() + (size_t)n * cs, de, (size_t)n * cs, hipMemcpyDeviceToHost, s) != hipSuccess ||
@@ -323,31 +370,33 @@ int svb_svdvals(svb_dtype dt, int64_t m, int64_t n, void* A_dev, int64_t lda, vo
                 he[(size_t)i] = fd[n + i];
             }
         }
+        const auto t3a = std::chrono::steady_clock::now();
+        if (rc == SVB_OK) rc = host_bdsvals(n, hd.data(), he.data(), hs.data());
+        total3 = std::chrono::duration<double>(std::chrono::steady_clock::now() - t3a).count();
+        if (rc == SVB_OK) {
+            if (dt == SVB_F64) std::memcpy(S_out_host, hs.data(), (size_t)n * 8);
+            else
+                for (int64_t i = 0; i < n; ++i) static_cast<float*>(S_out_host)[i] = (float)hs[(size_t)i];
+        }
     } else {
         (void)hipStreamSynchronize(s);
     }
     float ms1 = 0, ms2 = 0;
     (void)hipEventElapsedTime(&ms1, ev0, ev1);
     (void)hipEventElapsedTime(&ms2, ev1, ev2);
+    if (ev3) {
+        float ms3 = 0;
+        if (hipEventElapsedTime(&ms3, ev2, ev3) == hipSuccess) total3 = ms3 * 1e-3;
+        (void)hipEventDestroy(ev3);
+    }
     (void)hipEventDestroy(ev0);
     (void)hipEventDestroy(ev1);
     (void)hipEventDestroy(ev2);
     if (rc == SVB_OK && hipGetLastError() != hipSuccess) rc = SVB_ERR_DEVICE;
-    double t3 = 0;
-    if (rc == SVB_OK) {
-        const auto t0 = std::chrono::steady_clock::now();
-        rc = host_bdsvals(n, hd.data(), he.data(), hs.data());
-        t3 = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
-        if (rc == SVB_OK) {
-            if (dt == SVB_F64) std::memcpy(S_out_host, hs.data(), (size_t)n * 8);
-            else
-                for (int64_t i = 0; i < n; ++i) static_cast<float*>(S_out_host)[i] = (float)hs[(size_t)i];
-        }
-    }
     if (g_prof.on) g_prof.collect();
     g_last.s1 = ms1 * 1e-3;
     g_last.s2 = ms2 * 1e-3;
-    g_last.s3 = t3;
+    g_last.s3 = total3;
     return rc;
 }
 

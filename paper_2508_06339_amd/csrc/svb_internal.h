@@ -81,6 +81,11 @@ size_t chase_workspace_bytes(int64_t n, int nb);
 // ---- stage 3 (host) -----------------------------------------------------------
 int host_bdsvals(int64_t n, const double* d, const double* e, double* sigma);
 
+// ---- stage 3 (device) ---------------------------------------------------------
+template <typename C>
+int run_bdsvals_dev(int64_t n, const C* d, const C* e, C* sigma, void* work, double rel_tol, hipStream_t s);
+size_t bdsvals_dev_workspace_bytes(int64_t n);
+
 int env_int(const char* name, int dflt);
 
 }  // namespace svb

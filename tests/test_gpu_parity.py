@@ -189,3 +189,41 @@ def test_stage2_wavefront_variant(monkeypatch):
     monkeypatch.setenv("SVB_CHASE_IMPL", "0")
     a, info = workloads.make("c1", n=256, nb=32)
     _check(_gpu_sigma(a, 32), oracle.svdvals(a), 256, "f64")
+
+
+@pytest.mark.parametrize("dtype,n", [("f64", 1), ("f64", 2), ("f64", 257), ("f64", 3000), ("f32", 1000)])
+def test_stage3_device_closed_form_and_oracle(dtype, n):
+    tdt = TORCH_DT[dtype]
+    code = svb.SVB_F64 if dtype == "f64" else svb.SVB_F32
+    eps = workloads.EPS[dtype]
+    rc, wb = svb.svb_bdsvals_dev_workspace_bytes(n)
+    work = torch.empty(wb, dtype=torch.uint8, device="cuda")
+
+    def run(dh, eh):
+        d = torch.from_numpy(np.asarray(dh)).to(tdt).cuda()
+        e = torch.from_numpy(np.concatenate([np.asarray(eh), [0.0]])).to(tdt).cuda()
+        sig = torch.zeros(n, dtype=tdt, device="cuda")
+        assert svb.svb_bdsvals_dev(code, n, d, e, sig, 0.0, work, wb) == 0
+        torch.cuda.synchronize()
+        return sig.cpu().numpy().astype(np.float64)
+
+    # bidiagonal of ones: sigma_k = 2 cos(k pi / (2n+1))
+    s = run(np.ones(n), np.ones(n - 1))
+    k = np.arange(1, n + 1)
+    np.testing.assert_allclose(s, 2 * np.cos(k * np.pi / (2 * n + 1)), rtol=0, atol=64 * eps * 2)
+    # random, against the oracle's bidiagonal solver on the same (rounded) entries
+    dh = workloads.normal(91 + n, 0, n).astype(workloads.NP_DTYPE[dtype]).astype(np.float64)
+    eh = workloads.normal(92 + n, 0, max(n - 1, 0)).astype(workloads.NP_DTYPE[dtype]).astype(np.float64)
+    s = run(dh, eh)
+    ref = oracle.bdsvals(dh, eh)
+    assert np.abs(s - ref).max() <= 64 * eps * max(ref[0], 1e-300)
+    if n > 2:
+        bad = dh.copy()
+        bad[1] = np.inf
+        assert np.all(np.isnan(run(bad, eh)))
+
+
+def test_host_stage3_variant(monkeypatch):
+    monkeypatch.setenv("SVB_STAGE3", "host")
+    a, info = workloads.make("c2", n=256, nb=32)
+    _check(_gpu_sigma(a, 32), oracle.svdvals(a), 256, "f32")
