@@ -158,7 +158,7 @@ def main():
         "config": {"workload": f"{args.config}: {n}x{n} {dtype}, nb={nb}, "
                                f"{workloads.CONFIGS[args.config]['kind']}"},
         "time_to_singular_values_ms": ms_per_step,
-        "stage_ms": {"stage1": st[0] * 1e3, "stage2": st[1] * 1e3, "stage3_host": st[2] * 1e3,
+        "stage_ms": {"stage1": st[0] * 1e3, "stage2": st[1] * 1e3, "stage3": st[2] * 1e3,
                      "panel": prof["panel"]["seconds"] / args.steps * 1e3,
                      "update": upd_s / args.steps * 1e3},
         "stage1_effective_tflops": flops / st[0] / 1e12 if st[0] > 0 else None,

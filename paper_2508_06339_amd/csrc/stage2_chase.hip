@@ -148,7 +148,114 @@ __device__ void chase_step(C* __restrict__ band, int64_t ldab, int64_t n, int b,
 // reflector X is final and is written back while the block right of A2 (A3,
 // prefetched into registers at the start of the step) takes its place; after
 // the left reflector A2 is written back and A3 stays in LDS as the next step's X.
+
+// Reflector from the strided vector src[0], src[inc], ... (len entries, first one the
+// pivot), built by wave 0: vs <- v (v_0 = 1, zero beyond len), red[0] <- tau, and the vector
+// itself is replaced by (beta, 0, ...).  Other waves pass through.
+template <typename C, int B>
+__device__ __forceinline__ void house_wave(C* src, int inc, int len, C* vs, C* red)
+{
+    if (threadIdx.x >= kWave) return;
+    constexpr int PL = (B + kWave - 1) / kWave;
+    const int lane = threadIdx.x;
+    C x[PL];
+    C ss = 0;
+#pragma unroll
+    for (int q = 0; q < PL; ++q) {
+        const int idx = lane + q * kWave;
+        x[q] = idx < len ? src[idx * inc] : (C)0;
+        if (idx > 0) ss += x[q] * x[q];
+    }
+    ss = wsum(ss);
+    const C alpha = __shfl(x[0], 0, kWave);
+    C beta, tau, inv;
+    reflector<C>(alpha, ss, beta, tau, inv);
+#pragma unroll
+    for (int q = 0; q < PL; ++q) {
+        const int idx = lane + q * kWave;
+        if (idx < B) {
+            vs[idx] = idx < len ? ((idx == 0) ? (C)1 : x[q] * inv) : (C)0;
+            src[idx * inc] = (idx == 0) ? beta : (C)0;
+        }
+    }
+    if (lane == 0) red[0] = tau;
+}
+
+// Rows 1..B-1 of X and 0..B-1 of Z (column-major, leading dimension LD) get
+// row <- row - tau (row . v) v.  A row is split over NT/(2B) threads.
+template <typename C, int B, int NT>
+__device__ __forceinline__ void apply_rows(C* X, C* Z, int LD, const C* vs, const C* red, C* part)
+{
+    constexpr int SPLIT = NT / (2 * B) > 0 ? NT / (2 * B) : 1, W = B / SPLIT;
+    const C tau = red[0];
+    const int tid = threadIdx.x, ridx = tid % (2 * B), h = tid / (2 * B);
+    C* base = (ridx < B ? X + ridx : Z + (ridx - B)) + h * W * LD;
+    const C* v = vs + h * W;
+    C row[W];
+    C s = 0;
+#pragma unroll
+    for (int j = 0; j < W; ++j) {
+        row[j] = base[j * LD];
+        s += v[j] * row[j];
+    }
+    if (SPLIT > 1) {
+        part[tid] = s;
+        __syncthreads();
+        s = 0;
+#pragma unroll
+        for (int q = 0; q < SPLIT; ++q) s += part[ridx + q * 2 * B];
+    }
+    s *= tau;
+    if (ridx != 0 && tau != (C)0) {
+#pragma unroll
+        for (int j = 0; j < W; ++j) base[j * LD] = row[j] - s * v[j];
+    }
+}
+
+// Columns 1..B-1 of Z and 0..B-1 of X get col <- col - tau (v . col) v.
+template <typename C, int B, int NT>
+__device__ __forceinline__ void apply_cols(C* Z, C* X, int LD, const C* vs, const C* red, C* part)
+{
+    constexpr int SPLIT = NT / (2 * B) > 0 ? NT / (2 * B) : 1, W = B / SPLIT;
+    const C tau = red[0];
+    const int tid = threadIdx.x, cidx = tid % (2 * B), h = tid / (2 * B);
+    C* col = (cidx < B ? Z + cidx * LD : X + (cidx - B) * LD) + h * W;
+    const C* v = vs + h * W;
+    C cv[W];
+    C s = 0;
+#pragma unroll
+    for (int a = 0; a < W; ++a) {
+        cv[a] = col[a];
+        s += v[a] * cv[a];
+    }
+    if (SPLIT > 1) {
+        part[tid] = s;
+        __syncthreads();
+        s = 0;
+#pragma unroll
+        for (int q = 0; q < SPLIT; ++q) s += part[cidx + q * 2 * B];
+    }
+    s *= tau;
+    if (cidx != 0 && tau != (C)0) {
+#pragma unroll
+        for (int a = 0; a < W; ++a) col[a] = cv[a] - s * v[a];
+    }
+}
+
 constexpr int kDone = 0x3fffffff;
+
+// Band entries travel between workgroups (possibly on different XCDs, each with its own
+// L2) while the kernel runs: they are read and written with device-scope accesses that
+// bypass the non-coherent cache levels, so that no whole-cache write-back or invalidate
+// is needed per step.
+template <typename C> __device__ __forceinline__ C gld(const C* p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+template <typename C> __device__ __forceinline__ void gst(C* p, C v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 
 template <typename C, int B, int NT>
 __global__ __launch_bounds__(NT) void chase_persistent_kernel(C* __restrict__ band, int64_t ldab, int64_t n,
@@ -164,6 +271,7 @@ __global__ __launch_bounds__(NT) void chase_persistent_kernel(C* __restrict__ ba
     C* Z = X + B * LD;
     C* vs = Z + B * LD;
     C* red = vs + B;  // NW + 1
+    C* part = red + NW + 1;  // NT
     __shared__ int sh_i, sh_fail;
     const int tid = threadIdx.x;
 #ifdef SVB_CHASE_TIMING
@@ -212,62 +320,44 @@ __global__ __launch_bounds__(NT) void chase_persistent_kernel(C* __restrict__ ba
                 __syncthreads();
                 failed = sh_fail != 0;
                 TMARK(0);
-                __threadfence();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
             }
             TMARK(1);
             if (!failed) {
-                // A2 -> Z, (first step) row i -> X, A3 -> registers
+                // A2 -> Z, (first step) row i -> X, A3 -> registers.  All global loads are
+                // issued before the first LDS write so that their latencies overlap.
+                constexpr int ZPER = B * B / NT;
                 C pre[PER];
-                for (int jj = jj0; jj < B; jj += CSTEP) {
-                    C v = 0;
-                    if (ii < len && jj < len) v = BAND(c0 + ii, c0 + jj);
-                    Z[ii + jj * LD] = v;
-                    if (t == 0) {
-                        C xv = 0;
-                        if (ii == 0 && jj < len) xv = BAND(i, c0 + jj);
-                        X[ii + jj * LD] = xv;
-                    }
+                C zr[ZPER];
+#pragma unroll
+                for (int q = 0; q < ZPER; ++q) {
+                    const int jj = jj0 + q * CSTEP;
+                    zr[q] = (ii < len && jj < len) ? gld(&BAND(c0 + ii, c0 + jj)) : (C)0;
                 }
                 if (PREFETCH) {
 #pragma unroll
                     for (int q = 0; q < PER; ++q) {
                         const int jj = jj0 + q * CSTEP;
-                        pre[q] = (ii < len && jj < na3) ? BAND(c0 + ii, c0 + B + jj) : (C)0;
+                        pre[q] = (ii < len && jj < na3) ? gld(&BAND(c0 + ii, c0 + B + jj)) : (C)0;
                     }
                 }
+                if (t == 0) {
+                    for (int jj = jj0; jj < B; jj += CSTEP) {
+                        C xv = 0;
+                        if (ii == 0 && jj < len) xv = gld(&BAND(i, c0 + jj));
+                        X[ii + jj * LD] = xv;
+                    }
+                }
+#pragma unroll
+                for (int q = 0; q < ZPER; ++q) Z[ii + (jj0 + q * CSTEP) * LD] = zr[q];
                 __syncthreads();
                 TMARK(2);
-                // right reflector from X row 0, applied to X rows 1.. and Z
-                {
-                    C x = 0, ss = 0;
-                    if (tid < len) {
-                        x = X[tid * LD];
-                        if (tid > 0) ss = x * x;
-                    }
-                    ss = block_sum<C, NT>(ss, red);
-                    if (tid == 0) red[NW] = x;
-                    __syncthreads();
-                    C beta, tau, inv;
-                    reflector<C>(red[NW], ss, beta, tau, inv);
-                    if (tid < B) {
-                        vs[tid] = tid < len ? ((tid == 0) ? (C)1 : x * inv) : (C)0;
-                        X[tid * LD] = (tid == 0) ? beta : (C)0;
-                    }
-                    __syncthreads();
-                    if (tau != (C)0) {
-                        for (int ridx = tid; ridx < 2 * B; ridx += NT) {
-                            if (ridx == 0) continue;
-                            C* base = ridx < B ? X + ridx : Z + (ridx - B);
-                            C s = 0;
-#pragma unroll 8
-                            for (int j = 0; j < B; ++j) s += vs[j] * base[j * LD];
-                            s *= tau;
-#pragma unroll 8
-                            for (int j = 0; j < B; ++j) base[j * LD] -= s * vs[j];
-                        }
-                    }
-                    __syncthreads();
-                }
+                // right reflector from X row 0 (built by wave 0 alone: one barrier instead of a
+                // block-wide reduction), applied to X rows 1.. and Z by all threads
+                house_wave<C, B>(X, LD, len, vs, red);
+                __syncthreads();
+                apply_rows<C, B, NT>(X, Z, LD, vs, red, part);
+                __syncthreads();
                 TMARK(3);
                 // X is final: write it back, A3 takes its place
                 if (PREFETCH) {
@@ -277,70 +367,51 @@ __global__ __launch_bounds__(NT) void chase_persistent_kernel(C* __restrict__ ba
                         const C v = X[ii + jj * LD];
                         if (jj < len) {
                             if (t == 0) {
-                                if (ii == 0) BAND(i, c0 + jj) = v;
+                                if (ii == 0) gst(&BAND(i, c0 + jj), v);
                             } else {
-                                BAND(c0 - B + ii, c0 + jj) = v;
+                                gst(&BAND(c0 - B + ii, c0 + jj), v);
                             }
                         }
                         X[ii + jj * LD] = pre[q];
                     }
                 } else {
-                    for (int jj = jj0; jj < B; jj += CSTEP) {
+#pragma unroll
+                    for (int q = 0; q < ZPER; ++q) {
+                        const int jj = jj0 + q * CSTEP;
+                        zr[q] = (ii < len && jj < na3) ? gld(&BAND(c0 + ii, c0 + B + jj)) : (C)0;
+                    }
+#pragma unroll
+                    for (int q = 0; q < ZPER; ++q) {
+                        const int jj = jj0 + q * CSTEP;
                         const C v = X[ii + jj * LD];
                         if (jj < len) {
                             if (t == 0) {
-                                if (ii == 0) BAND(i, c0 + jj) = v;
+                                if (ii == 0) gst(&BAND(i, c0 + jj), v);
                             } else {
-                                BAND(c0 - B + ii, c0 + jj) = v;
+                                gst(&BAND(c0 - B + ii, c0 + jj), v);
                             }
                         }
-                        X[ii + jj * LD] = (ii < len && jj < na3) ? BAND(c0 + ii, c0 + B + jj) : (C)0;
+                        X[ii + jj * LD] = zr[q];
                     }
                 }
                 __syncthreads();
                 // left reflector from Z column 0, applied to Z columns 1.. and A3
-                {
-                    C x = 0, ss = 0;
-                    if (tid < len) {
-                        x = Z[tid];
-                        if (tid > 0) ss = x * x;
-                    }
-                    ss = block_sum<C, NT>(ss, red);
-                    if (tid == 0) red[NW] = x;
-                    __syncthreads();
-                    C beta, tau, inv;
-                    reflector<C>(red[NW], ss, beta, tau, inv);
-                    if (tid < B) {
-                        vs[tid] = tid < len ? ((tid == 0) ? (C)1 : x * inv) : (C)0;
-                        Z[tid] = (tid == 0) ? beta : (C)0;
-                    }
-                    __syncthreads();
-                    if (tau != (C)0) {
-                        for (int cidx = tid; cidx < 2 * B; cidx += NT) {
-                            if (cidx == 0) continue;
-                            C* col = cidx < B ? Z + cidx * LD : X + (cidx - B) * LD;
-                            C s = 0;
-#pragma unroll 8
-                            for (int a = 0; a < B; ++a) s += vs[a] * col[a];
-                            s *= tau;
-#pragma unroll 8
-                            for (int a = 0; a < B; ++a) col[a] -= s * vs[a];
-                        }
-                    }
-                    __syncthreads();
-                }
+                house_wave<C, B>(Z, 1, len, vs, red);
+                __syncthreads();
+                apply_cols<C, B, NT>(Z, X, LD, vs, red, part);
+                __syncthreads();
                 TMARK(4);
                 // A2 is final for this sweep; after the last step so is A3
                 for (int jj = jj0; jj < B; jj += CSTEP) {
-                    if (ii < len && jj < len) BAND(c0 + ii, c0 + jj) = Z[ii + jj * LD];
-                    if (t == nsteps - 1 && ii < len && jj < na3) BAND(c0 + ii, c0 + B + jj) = X[ii + jj * LD];
+                    if (ii < len && jj < len) gst(&BAND(c0 + ii, c0 + jj), Z[ii + jj * LD]);
+                    if (t == nsteps - 1 && ii < len && jj < na3) gst(&BAND(c0 + ii, c0 + B + jj), X[ii + jj * LD]);
                 }
-                __threadfence();
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
             }
             __syncthreads();
             TMARK(5);
             if (tid == 0)
-                __hip_atomic_store(&progress[i], (failed || t == nsteps - 1) ? kDone : t + 1, __ATOMIC_RELEASE,
+                __hip_atomic_store(&progress[i], (failed || t == nsteps - 1) ? kDone : t + 1, __ATOMIC_RELAXED,
                                    __HIP_MEMORY_SCOPE_AGENT);
             __syncthreads();
         }
@@ -371,7 +442,7 @@ template <typename C, int B>
 static bool launch_chase_persistent(C* band, int64_t ldab, int64_t n, int* ctrl, hipStream_t s)
 {
     constexpr int NT = 256;
-    constexpr size_t smem = sizeof(C) * (size_t)(2 * B * (B + 1) + B + NT / kWave + 1);
+    constexpr size_t smem = sizeof(C) * (size_t)(2 * B * (B + 1) + B + NT / kWave + 1 + NT);
     if (smem > 150 * 1024) return false;
     auto kern = chase_persistent_kernel<C, B, NT>;
     static bool attr_set = false;
