@@ -37,7 +37,10 @@ template <> struct Mfma<double> {
 };
 
 // Pol supplies: TM, TN, WM, WN, A_KC, B_KC (operand contiguous along k?),
-// ktiles(), loadA(mn, kt, k), loadB(mn, kt, k), store(m, n, value).
+// ktiles(), loadA(mn, kt, k), loadB(mn, kt, k), store(m, n, value) and RMW.
+// With RMW the tile of the destination is read into registers before the k loop
+// (loadC(m, n)), so that its latency hides behind the product, and
+// store(m, n, c - value) writes the difference.
 template <typename C, typename Pol>
 __device__ __forceinline__ void gemm_tile(const Pol& pol)
 {
@@ -61,6 +64,17 @@ __device__ __forceinline__ void gemm_tile(const Pol& pol)
         for (int j = 0; j < FN; ++j)
 #pragma unroll
             for (int r = 0; r < M::NACC; ++r) acc[i][j][r] = 0;
+
+    typename M::acc_t cin[Pol::RMW ? FM : 1][Pol::RMW ? FN : 1];
+    if (Pol::RMW) {
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int r = 0; r < M::NACC; ++r)
+                    cin[i][j][r] = pol.loadC(wm0 + i * M::BM + M::row(r, lane), wn0 + j * M::BN + M::col(lane));
+    }
 
     C ra[NA], rb[NBE];
     auto fetch = [&](int kt) {
@@ -123,7 +137,8 @@ __device__ __forceinline__ void gemm_tile(const Pol& pol)
         for (int j = 0; j < FN; ++j)
 #pragma unroll
             for (int r = 0; r < M::NACC; ++r)
-                pol.store(wm0 + i * M::BM + M::row(r, lane), wn0 + j * M::BN + M::col(lane), acc[i][j][r]);
+                pol.store(wm0 + i * M::BM + M::row(r, lane), wn0 + j * M::BN + M::col(lane),
+                          Pol::RMW ? cin[Pol::RMW ? i : 0][Pol::RMW ? j : 0][r] - acc[i][j][r] : acc[i][j][r]);
 }
 
 template <int NB, bool TRANSPOSED> struct TileShape;  // TRANSPOSED: TM = NB, TN = 128

@@ -357,7 +357,8 @@ template <> struct PanelRegDispatch<double> {
 // so Y is written along its contiguous direction.
 template <typename C, int NB>
 struct YPol : TileShape<NB, true> {
-    static constexpr bool A_KC = true, B_KC = false;
+    static constexpr bool A_KC = true, B_KC = false, RMW = false;
+    __device__ __forceinline__ C loadC(int, int) const { return (C)0; }
     static constexpr int TK = 128 / (int)sizeof(C);
     const C* V; C* Y; const C* Td; int64_t ldp, p0, rows;
     __device__ __forceinline__ int ktiles() const { return NB / TK; }

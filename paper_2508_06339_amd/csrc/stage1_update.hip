@@ -161,7 +161,8 @@ static void update_simple(T* Cb, int64_t lda, int64_t qlen, const C* V, const C*
 // K1: D[q][kk] = sum over the domain's rows p of C(p,q) * Y(p,kk)
 template <typename T, typename C, int NB, bool LQ>
 struct K1Pol : TileShape<NB, false> {
-    static constexpr bool A_KC = !LQ, B_KC = true;
+    static constexpr bool A_KC = !LQ, B_KC = true, RMW = false;
+    __device__ __forceinline__ C loadC(int, int) const { return (C)0; }
     static constexpr int TK = 128 / (int)sizeof(C);
     static constexpr int KPC = NB / TK;  // k-tiles per chunk
     const T* Cb; int64_t sp, sq, qlen, q0; const C* Y; int64_t ldp; int64_t ch0; int nch; int64_t stride; C* Wd;
@@ -201,7 +202,12 @@ __global__ __launch_bounds__(256) void k1_mfma(const T* __restrict__ Cb, int64_t
 // K2, QR sweep: D[q][p] = sum_kk W(kk,q) V(p,kk);  C(p,q) -= D
 template <typename T, typename C, int NB>
 struct K2QrPol : TileShape<NB, false> {
-    static constexpr bool A_KC = true, B_KC = false;
+    static constexpr bool A_KC = true, B_KC = false, RMW = true;
+    __device__ __forceinline__ C loadC(int m, int n) const
+    {
+        const int64_t q = q0 + m;
+        return q < qlen ? ld_as<C, T>(&Cb[(ch * stride + n) * sp + q * sq]) : (C)0;
+    }
     static constexpr int TK = 128 / (int)sizeof(C);
     T* Cb; int64_t sp, sq, qlen, q0; const C* V; int64_t ldp; int64_t ch; int64_t stride; const C* Wd;
     __device__ __forceinline__ int ktiles() const { return NB / TK; }
@@ -217,17 +223,19 @@ struct K2QrPol : TileShape<NB, false> {
     __device__ __forceinline__ void store(int m, int n, C v) const
     {
         const int64_t q = q0 + m;
-        if (q < qlen) {
-            T* ptr = &Cb[(ch * stride + n) * sp + q * sq];
-            st_as<T, C>(ptr, ld_as<C, T>(ptr) - v);
-        }
+        if (q < qlen) st_as<T, C>(&Cb[(ch * stride + n) * sp + q * sq], v);
     }
 };
 
 // K2, LQ sweep: D[p][q] = sum_kk V(p,kk) W(kk,q);  C(p,q) -= D
 template <typename T, typename C, int NB>
 struct K2LqPol : TileShape<NB, true> {
-    static constexpr bool A_KC = false, B_KC = true;
+    static constexpr bool A_KC = false, B_KC = true, RMW = true;
+    __device__ __forceinline__ C loadC(int m, int n) const
+    {
+        const int64_t q = q0 + n;
+        return q < qlen ? ld_as<C, T>(&Cb[(ch * stride + m) * sp + q * sq]) : (C)0;
+    }
     static constexpr int TK = 128 / (int)sizeof(C);
     T* Cb; int64_t sp, sq, qlen, q0; const C* V; int64_t ldp; int64_t ch; int64_t stride; const C* Wd;
     __device__ __forceinline__ int ktiles() const { return NB / TK; }
@@ -243,10 +251,7 @@ struct K2LqPol : TileShape<NB, true> {
     __device__ __forceinline__ void store(int m, int n, C v) const
     {
         const int64_t q = q0 + n;
-        if (q < qlen) {
-            T* ptr = &Cb[(ch * stride + m) * sp + q * sq];
-            st_as<T, C>(ptr, ld_as<C, T>(ptr) - v);
-        }
+        if (q < qlen) st_as<T, C>(&Cb[(ch * stride + m) * sp + q * sq], v);
     }
 };
 
