@@ -25,7 +25,7 @@ PEAK_TFLOPS = {"f64": 78.6, "f32": 157.3, "f16": 157.3}   # MFMA peak of the ari
 PEAK_HBM_GBS = 8000.0
 
 
-def device_matrix(name, torch):
+def device_matrix(name, torch, gaussian=False):
     """The workload matrix in HBM (column-major n x n in the storage dtype).
 
     iid workloads come from the shared CPU generator; the prescribed-spectrum
@@ -35,6 +35,12 @@ def device_matrix(name, torch):
     cfg = workloads.CONFIGS[name]
     n = cfg["n"]
     tdt = {"f64": torch.float64, "f32": torch.float32, "f16": torch.float16}[cfg["dtype"]]
+    if gaussian:
+        # counter-collection runs only: same shape and dtype, iid N(0,1/n) drawn on the device
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(workloads.config_seed(cfg["seed_id"]))
+        a = torch.randn(n, n, dtype=torch.float32, device="cuda", generator=gen) / float(np.sqrt(n))
+        return a.to(tdt), dict(name=name, n=n, nb=cfg["nb"], dtype=cfg["dtype"], seed=0, sigma=None)
     if cfg["kind"] == "iid":
         a, info = workloads.make(name)
         return torch.from_numpy(np.ascontiguousarray(a.T)).cuda(), info
@@ -78,6 +84,9 @@ def main():
     ap.add_argument("--config", default="c4", help="workload name from workloads.CONFIGS")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-n", type=int, default=3072)
+    ap.add_argument("--gaussian-input", action="store_true",
+                    help="profiling aid: replace the workload's values by iid Gaussians of the same shape "
+                         "(no QR-based synthesis on the device); the result line is marked accordingly")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -90,7 +99,7 @@ def main():
 
     svb.load_library()  # raises when the HIP library is missing: there is no fallback
     torch.cuda.set_device(0)
-    a0, info = device_matrix(args.config, torch)
+    a0, info = device_matrix(args.config, torch, args.gaussian_input)
     n, nb, dtype = info["n"], info["nb"], info["dtype"]
     dt_code = svb.dtype_code(a0.dtype)
     rc, wbytes, _ = svb.svb_workspace_bytes(dt_code, n, n, nb)
@@ -144,11 +153,29 @@ def main():
     roofline = dict(kernel=dom, bound="mfma", achieved=ach, peak=peak, unit="TFLOP/s", frac=ach / peak,
                     traffic=None, launches=pk["launches"],
                     avg_launch_ms=pk["seconds"] / max(pk["launches"], 1) * 1e3)
+    # HBM bytes per launch from the committed rocprofv3 --pmc summary of this workload, if there is one
+    tfile = os.path.join(ROOT, "profiles", f"hbm_traffic_{args.config}_{n}_{dtype}_nb{nb}.json")
+    if os.path.exists(tfile):
+        tr = json.load(open(tfile))
+        rd = sum(v["read_GB"] for k, v in tr.items() if k.startswith(dom + "_mfma"))
+        wr = sum(v["write_GB"] for k, v in tr.items() if k.startswith(dom + "_mfma"))
+        nl = sum(v["launches"] for k, v in tr.items() if k.startswith(dom + "_mfma"))
+        if nl:
+            roofline["traffic"] = (rd + wr) * 1e9 / nl
+            roofline["traffic_unit"] = "HBM bytes per launch (FETCH_SIZE + WRITE_SIZE, calibrated)"
+            roofline["algorithmic_bytes_per_launch"] = pk["bytes"] / max(pk["launches"], 1)
+        chk = [v for k, v in tr.items() if k.startswith("chase_persistent")]
+        if chk:
+            roofline_stage2_traffic = (chk[0]["read_GB"] + chk[0]["write_GB"]) * 1e9
+        else:
+            roofline_stage2_traffic = None
+    else:
+        roofline_stage2_traffic = None
     upd_s = prof["k1"]["seconds"] + prof["k2"]["seconds"]
     ch = prof["chase"]
     ch_gbs = ch["bytes"] / ch["seconds"] / 1e9 if ch["seconds"] > 0 else 0.0
     roofline_stage2 = dict(kernel="chase", bound="hbm", achieved=ch_gbs, peak=PEAK_HBM_GBS, unit="GB/s",
-                           frac=ch_gbs / PEAK_HBM_GBS, traffic=None)
+                           frac=ch_gbs / PEAK_HBM_GBS, traffic=roofline_stage2_traffic)
 
     res = {
         "metric": "svdvals effective TFLOP/s (8/3 n^3 / time-to-singular-values)",
@@ -156,7 +183,7 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": dtype, "data": "synthetic",
         "config": {"workload": f"{args.config}: {n}x{n} {dtype}, nb={nb}, "
-                               f"{workloads.CONFIGS[args.config]['kind']}"},
+                               f"{'gaussian stand-in' if args.gaussian_input else workloads.CONFIGS[args.config]['kind']}"},
         "time_to_singular_values_ms": ms_per_step,
         "stage_ms": {"stage1": st[0] * 1e3, "stage2": st[1] * 1e3, "stage3": st[2] * 1e3,
                      "panel": prof["panel"]["seconds"] / args.steps * 1e3,
