@@ -258,9 +258,12 @@ struct K2LqPol : TileShape<NB, true> {
 template <typename T, typename C, int NB, bool LQ>
 __global__ __launch_bounds__(256) void k2_mfma(T* __restrict__ Cb, int64_t sp, int64_t sq, int64_t qlen,
                                                const C* __restrict__ V, int64_t ldp, int g,
-                                               int64_t stride, const C* __restrict__ W)
+                                               int64_t stride, const C* __restrict__ W, int sel)
 {
-    const int64_t ch = blockIdx.y;
+    // sel 0: every chunk; 1: the first chunk of every domain (the rows the next panel and
+    // the next tree level read); 2: all the others
+    const int64_t y = blockIdx.y;
+    const int64_t ch = sel == 0 ? y : (sel == 1 ? y * g : (y / (g - 1)) * g + 1 + y % (g - 1));
     typename std::conditional<LQ, K2LqPol<T, C, NB>, K2QrPol<T, C, NB>>::type pol;
     pol.Cb = Cb; pol.sp = sp; pol.sq = sq; pol.qlen = qlen; pol.q0 = (int64_t)blockIdx.x * 128;
     pol.V = V; pol.ldp = ldp; pol.ch = ch; pol.stride = stride;
@@ -270,52 +273,60 @@ __global__ __launch_bounds__(256) void k2_mfma(T* __restrict__ Cb, int64_t sp, i
 
 template <typename T, typename C, int NB, bool LQ>
 static void update_mfma(T* Cb, int64_t lda, int64_t qlen, const C* V, const C* Y, int64_t ldp,
-                        int chunks, int g, int64_t stride, C* W, bool credited, hipStream_t s)
+                        int chunks, int g, int64_t stride, C* W, bool credited, int phase, hipStream_t s)
 {
     const int64_t sp = LQ ? lda : 1, sq = LQ ? 1 : lda;
     const int domains = (chunks + g - 1) / g;
     const double fl = credited ? 2.0 * chunks * NB * (double)NB * (double)qlen : 0.0;
     const double by = credited ? (double)chunks * NB * (double)qlen * sizeof(T) : 0.0;
     const unsigned qt = (unsigned)((qlen + 127) / 128);
-    prof_begin(SVB_PROF_K1, s, fl, by);
-    hipLaunchKernelGGL((k1_mfma<T, C, NB, LQ>), dim3(qt, (unsigned)domains), dim3(256), 0, s, Cb, sp, sq,
-                       qlen, Y, ldp, chunks, g, stride, W);
-    prof_end(s);
-    prof_begin(SVB_PROF_K2, s, fl, 2.0 * by);
-    hipLaunchKernelGGL((k2_mfma<T, C, NB, LQ>), dim3(qt, (unsigned)chunks), dim3(256), 0, s, Cb, sp, sq,
-                       qlen, V, ldp, g, stride, W);
-    prof_end(s);
+    if (phase != 2) {
+        prof_begin(SVB_PROF_K1, s, fl, by);
+        hipLaunchKernelGGL((k1_mfma<T, C, NB, LQ>), dim3(qt, (unsigned)domains), dim3(256), 0, s, Cb, sp, sq,
+                           qlen, Y, ldp, chunks, g, stride, W);
+        prof_end(s);
+    }
+    // phase 0: all of K2; 1: first chunks only; 2: the remaining chunks
+    const int ny = phase == 0 ? chunks : (phase == 1 ? domains : chunks - domains);
+    if (ny > 0) {
+        const double share = (double)ny / chunks;
+        prof_begin(SVB_PROF_K2, s, fl * share, 2.0 * by * share);
+        hipLaunchKernelGGL((k2_mfma<T, C, NB, LQ>), dim3(qt, (unsigned)ny), dim3(256), 0, s, Cb, sp, sq,
+                           qlen, V, ldp, g, stride, W, phase);
+        prof_end(s);
+    }
 }
 
 template <typename T, typename C, int NB>
 static void update_nb(bool lq, T* Cb, int64_t lda, int64_t qlen, const C* V, const C* Y,
                       int64_t ldp, int chunks, int g, int64_t stride, C* W, int impl, bool credited,
-                      hipStream_t s)
+                      int phase, hipStream_t s)
 {
     if (impl == 0) {
+        if (phase == 2) return;  // the plain kernels always do all of K2 in phase 0 / 1
         if (lq) update_simple<T, C, NB, true>(Cb, lda, qlen, V, Y, ldp, chunks, g, stride, W, credited, s);
         else update_simple<T, C, NB, false>(Cb, lda, qlen, V, Y, ldp, chunks, g, stride, W, credited, s);
     } else {
-        if (lq) update_mfma<T, C, NB, true>(Cb, lda, qlen, V, Y, ldp, chunks, g, stride, W, credited, s);
-        else update_mfma<T, C, NB, false>(Cb, lda, qlen, V, Y, ldp, chunks, g, stride, W, credited, s);
+        if (lq) update_mfma<T, C, NB, true>(Cb, lda, qlen, V, Y, ldp, chunks, g, stride, W, credited, phase, s);
+        else update_mfma<T, C, NB, false>(Cb, lda, qlen, V, Y, ldp, chunks, g, stride, W, credited, phase, s);
     }
 }
 
 template <typename T, typename C>
 void launch_update(int nb, bool lq, T* Cbase, int64_t lda, int64_t qlen, const C* V, const C* Y,
                    int64_t ldp, int chunks, int g, int64_t stride, C* W, int impl, bool credited,
-                   hipStream_t s)
+                   int phase, hipStream_t s)
 {
     if (qlen <= 0) return;
     switch (nb) {
-    case 32: update_nb<T, C, 32>(lq, Cbase, lda, qlen, V, Y, ldp, chunks, g, stride, W, impl, credited, s); break;
-    case 64: update_nb<T, C, 64>(lq, Cbase, lda, qlen, V, Y, ldp, chunks, g, stride, W, impl, credited, s); break;
-    default: update_nb<T, C, 128>(lq, Cbase, lda, qlen, V, Y, ldp, chunks, g, stride, W, impl, credited, s); break;
+    case 32: update_nb<T, C, 32>(lq, Cbase, lda, qlen, V, Y, ldp, chunks, g, stride, W, impl, credited, phase, s); break;
+    case 64: update_nb<T, C, 64>(lq, Cbase, lda, qlen, V, Y, ldp, chunks, g, stride, W, impl, credited, phase, s); break;
+    default: update_nb<T, C, 128>(lq, Cbase, lda, qlen, V, Y, ldp, chunks, g, stride, W, impl, credited, phase, s); break;
     }
 }
 
-template void launch_update<double, double>(int, bool, double*, int64_t, int64_t, const double*, const double*, int64_t, int, int, int64_t, double*, int, bool, hipStream_t);
-template void launch_update<float, float>(int, bool, float*, int64_t, int64_t, const float*, const float*, int64_t, int, int, int64_t, float*, int, bool, hipStream_t);
-template void launch_update<__half, float>(int, bool, __half*, int64_t, int64_t, const float*, const float*, int64_t, int, int, int64_t, float*, int, bool, hipStream_t);
+template void launch_update<double, double>(int, bool, double*, int64_t, int64_t, const double*, const double*, int64_t, int, int, int64_t, double*, int, bool, int, hipStream_t);
+template void launch_update<float, float>(int, bool, float*, int64_t, int64_t, const float*, const float*, int64_t, int, int, int64_t, float*, int, bool, int, hipStream_t);
+template void launch_update<__half, float>(int, bool, __half*, int64_t, int64_t, const float*, const float*, int64_t, int, int, int64_t, float*, int, bool, int, hipStream_t);
 
 }  // namespace svb

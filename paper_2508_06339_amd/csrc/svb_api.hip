@@ -49,7 +49,7 @@ struct Carve {
     size_t w_elems;      // W of the largest level
     size_t t_elems;      // T factors of one level
     size_t band_elems, de_elems;
-    size_t off_V, off_Y, off_W, off_T, off_band, off_d, off_e, off_sig, off_s3, off_err, total;
+    size_t off_V[2], off_Y[2], off_W[2], off_T[2], off_band, off_d, off_e, off_sig, off_s3, off_err, total;
 };
 
 Carve carve(svb_dtype dt, int64_t n, int nb)
@@ -58,15 +58,19 @@ Carve carve(svb_dtype dt, int64_t n, int nb)
     const size_t cs = compute_size(dt);
     // levels shrink by >= kMinDomainChunks: sum of panel rows <= 2n (+ one chunk per level)
     c.panel_elems = (size_t)(2 * n + (int64_t)(kMaxLevels + 2) * nb) * nb;
-    c.w_elems = (size_t)n * (size_t)n / kMinDomainChunks + (size_t)n * nb;
+    // W of every tree level: n^2/g * (1 + 1/g + ...) <= n^2 for g >= 2
+    c.w_elems = (size_t)n * (size_t)n + (size_t)n * nb * (kMaxLevels + 1);
     c.t_elems = (size_t)(n / nb + 1) * nb * nb;
     c.band_elems = (size_t)(3 * nb) * (size_t)n;
     c.de_elems = (size_t)n;
     size_t off = 0;
-    c.off_V = off; off += align_up(c.panel_elems * cs);
-    c.off_Y = off; off += align_up(c.panel_elems * cs);
-    c.off_W = off; off += align_up(c.w_elems * cs);
-    c.off_T = off; off += align_up(c.t_elems * cs);
+    // two sets: a half-sweep's deferred update still reads its set while the next panel is built
+    for (int b = 0; b < 2; ++b) {
+        c.off_V[b] = off; off += align_up(c.panel_elems * cs);
+        c.off_Y[b] = off; off += align_up(c.panel_elems * cs);
+        c.off_W[b] = off; off += align_up(c.w_elems * cs);
+        c.off_T[b] = off; off += align_up(c.t_elems * cs);
+    }
     c.off_band = off; off += align_up(c.band_elems * cs);
     c.off_d = off; off += align_up(c.de_elems * cs);
     c.off_e = off; off += align_up(c.de_elems * cs);
@@ -90,7 +94,6 @@ int build_levels(int64_t len, int nb, int g, Level* lv)
         L.stride = stride;
         L.poff = poff;
         L.ldp = (int64_t)chunks * nb;
-        L.woff = 0;
         poff += L.ldp * nb;
         ++nl;
         if (L.domains == 1 || nl == kMaxLevels) break;
@@ -151,25 +154,53 @@ struct Profiler {
     }
 } g_prof;
 
+// Helper stream and events for the look-ahead (created once per process).
+struct Lookahead {
+    hipStream_t h = nullptr;
+    hipEvent_t crit[2] = {nullptr, nullptr}, rest[2] = {nullptr, nullptr};
+    bool ok = false;
+    bool init()
+    {
+        if (ok) return true;
+        if (hipStreamCreateWithFlags(&h, hipStreamNonBlocking) != hipSuccess) return false;
+        for (int i = 0; i < 2; ++i)
+            if (hipEventCreateWithFlags(&crit[i], hipEventDisableTiming) != hipSuccess ||
+                hipEventCreateWithFlags(&rest[i], hipEventDisableTiming) != hipSuccess)
+                return false;
+        ok = true;
+        return true;
+    }
+} g_la;
+
+// Stage 1 driver.  Per half-sweep: panel tree on the caller's stream; then, level by
+// level, K1 and the part of K2 that the next level and the next panel read (the first
+// chunk of every domain); the rest of K2 (the bulk of its work) is handed to a helper
+// stream and overlaps the next half-sweep's panel, which only touches the first chunk.
+// The next half-sweep's K1 waits for it.
 template <typename T, typename C>
 int ge2gb_impl(int64_t n, T* A, int64_t lda, int nb, C* band, int64_t ldab, unsigned char* work,
                const Carve& cv, hipStream_t s)
 {
-    C* Vb = reinterpret_cast<C*>(work + cv.off_V);
-    C* Yb = reinterpret_cast<C*>(work + cv.off_Y);
-    C* Wb = reinterpret_cast<C*>(work + cv.off_W);
-    C* Tb = reinterpret_cast<C*>(work + cv.off_T);
     int* err = reinterpret_cast<int*>(work + cv.off_err);
     const int g = domain_chunks(sizeof(C) == 8 ? SVB_F64 : SVB_F32, nb);
     const int impl = env_int("SVB_UPDATE_IMPL", 1);
+    const bool la = impl != 0 && env_int("SVB_LOOKAHEAD", 1) != 0 && g_la.init();
     const int64_t N = n / nb;
     Level lv[kMaxLevels];
+    int64_t woff[kMaxLevels];
 
     launch_band_clear<C>(band, ldab, n, s);
+    int hs = 0;            // half-sweep counter: selects the buffer set and the events
+    bool pending = false;  // deferred K2 work of the previous half-sweep is in flight on the helper stream
     for (int64_t k = 0; k < N; ++k) {
         for (int half = 0; half < 2; ++half) {
             const bool lq = half == 1;
             if (lq && k == N - 1) break;
+            const int set = hs & 1;
+            C* Vb = reinterpret_cast<C*>(work + cv.off_V[set]);
+            C* Yb = reinterpret_cast<C*>(work + cv.off_Y[set]);
+            C* Wb = reinterpret_cast<C*>(work + cv.off_W[set]);
+            C* Tb = reinterpret_cast<C*>(work + cv.off_T[set]);
             // panel: QR -> rows k*nb.., columns k*nb..; LQ -> rows k*nb.., columns (k+1)*nb..
             const int64_t row0 = k * nb;
             const int64_t col0 = lq ? (k + 1) * nb : k * nb;
@@ -188,16 +219,40 @@ int ge2gb_impl(int64_t n, T* A, int64_t lda, int nb, C* band, int64_t ldab, unsi
                     launch_scatter_r<C>(Vb + next_off, ldnext, nb, band, ldab, row0, col0, lq, s);
             }
             g_prof.end(s);
+            // the previous half-sweep's deferred update must be complete before this one's K1
+            if (pending) {
+                (void)hipStreamWaitEvent(s, g_la.rest[(hs - 1) & 1], 0);
+                pending = false;
+            }
             // trailing matrix: QR -> rows k*nb.., columns (k+1)*nb..;  LQ -> rows (k+1)*nb.., columns (k+1)*nb..
             const int64_t qlen = n - (k + 1) * nb;
             if (qlen > 0) {
                 T* Cb = lq ? A + (k + 1) * nb + (k + 1) * nb * lda : A + k * nb + (k + 1) * nb * lda;
+                int64_t wo = 0;
+                bool any_rest = false;
+                for (int L = 0; L < nl; ++L) {
+                    woff[L] = wo;
+                    wo += (int64_t)lv[L].domains * nb * qlen;
+                    any_rest = any_rest || lv[L].chunks > lv[L].domains;
+                }
+                const bool defer = la && any_rest;
                 for (int L = 0; L < nl; ++L)
                     launch_update<T, C>(nb, lq, Cb, lda, qlen, Vb + lv[L].poff, Yb + lv[L].poff, lv[L].ldp,
-                                        lv[L].chunks, g, lv[L].stride, Wb, impl, L == 0, s);
+                                        lv[L].chunks, g, lv[L].stride, Wb + woff[L], impl, L == 0, defer ? 1 : 0, s);
+                if (defer) {
+                    (void)hipEventRecord(g_la.crit[set], s);
+                    (void)hipStreamWaitEvent(g_la.h, g_la.crit[set], 0);
+                    for (int L = 0; L < nl; ++L)
+                        launch_update<T, C>(nb, lq, Cb, lda, qlen, Vb + lv[L].poff, Yb + lv[L].poff, lv[L].ldp,
+                                            lv[L].chunks, g, lv[L].stride, Wb + woff[L], impl, L == 0, 2, g_la.h);
+                    (void)hipEventRecord(g_la.rest[set], g_la.h);
+                    pending = true;
+                }
             }
+            ++hs;
         }
     }
+    if (pending) (void)hipStreamWaitEvent(s, g_la.rest[(hs - 1) & 1], 0);
     return hipGetLastError() == hipSuccess ? SVB_OK : SVB_ERR_DEVICE;
 }
 

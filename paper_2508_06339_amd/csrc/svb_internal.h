@@ -66,7 +66,7 @@ void launch_band_clear(C* band, int64_t ldab, int64_t n, hipStream_t s);
 template <typename T, typename C>
 void launch_update(int nb, bool lq, T* Cbase, int64_t lda, int64_t qlen,
                    const C* V, const C* Y, int64_t ldp, int chunks, int g, int64_t stride,
-                   C* W, int impl, bool credited, hipStream_t s);
+                   C* W, int impl, bool credited, int phase, hipStream_t s);
 
 // per-kernel timing hooks (no-ops unless profiling is enabled)
 void prof_begin(int kind, hipStream_t s, double flops, double bytes);
