@@ -84,6 +84,8 @@ def main():
     ap.add_argument("--config", default="c4", help="workload name from workloads.CONFIGS")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-n", type=int, default=3072)
+    ap.add_argument("--lda-pad", type=int, default=0,
+                    help="leading dimension of the matrix handed to the library = n + this many elements")
     ap.add_argument("--gaussian-input", action="store_true",
                     help="profiling aid: replace the workload's values by iid Gaussians of the same shape "
                          "(no QR-based synthesis on the device); the result line is marked accordingly")
@@ -105,7 +107,9 @@ def main():
     rc, wbytes, _ = svb.svb_workspace_bytes(dt_code, n, n, nb)
     assert rc == 0, svb.svb_status_string(rc)
     work = torch.empty(wbytes, dtype=torch.uint8, device="cuda")
-    a = torch.empty_like(a0)
+    lda = n + args.lda_pad
+    abuf = torch.empty((n, lda), dtype=a0.dtype, device="cuda")   # row j of this tensor = column j of the matrix
+    a = abuf[:, :n]
     out = np.empty(n, dtype=np.float64 if dtype == "f64" else np.float32)
     stream = torch.cuda.current_stream().cuda_stream
 
@@ -113,7 +117,7 @@ def main():
         a.copy_(a0)                      # stage 1 destroys its input; the refresh is not timed
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        rc = svb.svb_svdvals(dt_code, n, n, a, n, out, nb, work, wbytes, stream)
+        rc = svb.svb_svdvals(dt_code, n, n, abuf, lda, out, nb, work, wbytes, stream)
         torch.cuda.synchronize()
         t1 = time.perf_counter()
         assert rc == 0, svb.svb_status_string(rc)
@@ -182,7 +186,7 @@ def main():
         "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": dtype, "data": "synthetic",
-        "config": {"workload": f"{args.config}: {n}x{n} {dtype}, nb={nb}, "
+        "config": {"lda": lda, "workload": f"{args.config}: {n}x{n} {dtype}, nb={nb}, "
                                f"{'gaussian stand-in' if args.gaussian_input else workloads.CONFIGS[args.config]['kind']}"},
         "time_to_singular_values_ms": ms_per_step,
         "stage_ms": {"stage1": st[0] * 1e3, "stage2": st[1] * 1e3, "stage3": st[2] * 1e3,

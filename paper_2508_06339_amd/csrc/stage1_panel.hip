@@ -358,20 +358,20 @@ template <> struct PanelRegDispatch<double> {
 template <typename C, int NB>
 struct YPol : TileShape<NB, true> {
     static constexpr bool A_KC = true, B_KC = false, RMW = false;
-    __device__ __forceinline__ C loadC(int, int) const { return (C)0; }
+    typedef C TA; typedef C TB; typedef C TD;
     static constexpr int TK = 128 / (int)sizeof(C);
     const C* V; C* Y; const C* Td; int64_t ldp, p0, rows;
     __device__ __forceinline__ int ktiles() const { return NB / TK; }
-    __device__ __forceinline__ C loadA(int mn, int kt, int k) const { return Td[(kt * TK + k) + mn * NB]; }
-    __device__ __forceinline__ C loadB(int mn, int kt, int k) const
+    __device__ __forceinline__ const C* ptrA(int mn, int kt, int k) const { return &Td[(kt * TK + k) + mn * NB]; }
+    __device__ __forceinline__ const C* ptrB(int mn, int kt, int k) const
     {
         const int64_t p = p0 + mn;
-        return p < rows ? V[p + (int64_t)(kt * TK + k) * ldp] : (C)0;
+        return p < rows ? &V[p + (int64_t)(kt * TK + k) * ldp] : nullptr;
     }
-    __device__ __forceinline__ void store(int m, int n, C v) const
+    __device__ __forceinline__ C* ptrD(int m, int n) const
     {
         const int64_t p = p0 + n;
-        if (p < rows) Y[p + (int64_t)m * ldp] = v;
+        return p < rows ? &Y[p + (int64_t)m * ldp] : nullptr;
     }
 };
 

@@ -162,27 +162,27 @@ static void update_simple(T* Cb, int64_t lda, int64_t qlen, const C* V, const C*
 template <typename T, typename C, int NB, bool LQ>
 struct K1Pol : TileShape<NB, false> {
     static constexpr bool A_KC = !LQ, B_KC = true, RMW = false;
-    __device__ __forceinline__ C loadC(int, int) const { return (C)0; }
+    typedef T TA; typedef C TB; typedef C TD;
     static constexpr int TK = 128 / (int)sizeof(C);
     static constexpr int KPC = NB / TK;  // k-tiles per chunk
     const T* Cb; int64_t sp, sq, qlen, q0; const C* Y; int64_t ldp; int64_t ch0; int nch; int64_t stride; C* Wd;
     __device__ __forceinline__ int ktiles() const { return nch * KPC; }
-    __device__ __forceinline__ C loadA(int mn, int kt, int k) const
+    __device__ __forceinline__ const T* ptrA(int mn, int kt, int k) const
     {
         const int64_t q = q0 + mn;
-        if (q >= qlen) return (C)0;
+        if (q >= qlen) return nullptr;
         const int64_t p = (ch0 + kt / KPC) * stride + (kt % KPC) * TK + k;
-        return ld_as<C, T>(&Cb[p * sp + q * sq]);
+        return &Cb[p * sp + q * sq];
     }
-    __device__ __forceinline__ C loadB(int mn, int kt, int k) const
+    __device__ __forceinline__ const C* ptrB(int mn, int kt, int k) const
     {
         const int64_t row = (ch0 + kt / KPC) * NB + (kt % KPC) * TK + k;
-        return Y[row + (int64_t)mn * ldp];
+        return &Y[row + (int64_t)mn * ldp];
     }
-    __device__ __forceinline__ void store(int m, int n, C v) const
+    __device__ __forceinline__ C* ptrD(int m, int n) const
     {
         const int64_t q = q0 + m;
-        if (q < qlen) Wd[n + q * NB] = v;
+        return q < qlen ? &Wd[n + q * NB] : nullptr;
     }
 };
 
@@ -203,27 +203,23 @@ __global__ __launch_bounds__(256) void k1_mfma(const T* __restrict__ Cb, int64_t
 template <typename T, typename C, int NB>
 struct K2QrPol : TileShape<NB, false> {
     static constexpr bool A_KC = true, B_KC = false, RMW = true;
-    __device__ __forceinline__ C loadC(int m, int n) const
-    {
-        const int64_t q = q0 + m;
-        return q < qlen ? ld_as<C, T>(&Cb[(ch * stride + n) * sp + q * sq]) : (C)0;
-    }
+    typedef C TA; typedef C TB; typedef T TD;
     static constexpr int TK = 128 / (int)sizeof(C);
     T* Cb; int64_t sp, sq, qlen, q0; const C* V; int64_t ldp; int64_t ch; int64_t stride; const C* Wd;
     __device__ __forceinline__ int ktiles() const { return NB / TK; }
-    __device__ __forceinline__ C loadA(int mn, int kt, int k) const
+    __device__ __forceinline__ const C* ptrA(int mn, int kt, int k) const
     {
         const int64_t q = q0 + mn;
-        return q < qlen ? Wd[(kt * TK + k) + q * NB] : (C)0;
+        return q < qlen ? &Wd[(kt * TK + k) + q * NB] : nullptr;
     }
-    __device__ __forceinline__ C loadB(int mn, int kt, int k) const
+    __device__ __forceinline__ const C* ptrB(int mn, int kt, int k) const
     {
-        return V[(ch * NB + mn) + (int64_t)(kt * TK + k) * ldp];
+        return &V[(ch * NB + mn) + (int64_t)(kt * TK + k) * ldp];
     }
-    __device__ __forceinline__ void store(int m, int n, C v) const
+    __device__ __forceinline__ T* ptrD(int m, int n) const
     {
         const int64_t q = q0 + m;
-        if (q < qlen) st_as<T, C>(&Cb[(ch * stride + n) * sp + q * sq], v);
+        return q < qlen ? &Cb[(ch * stride + n) * sp + q * sq] : nullptr;
     }
 };
 
@@ -231,27 +227,23 @@ struct K2QrPol : TileShape<NB, false> {
 template <typename T, typename C, int NB>
 struct K2LqPol : TileShape<NB, true> {
     static constexpr bool A_KC = false, B_KC = true, RMW = true;
-    __device__ __forceinline__ C loadC(int m, int n) const
-    {
-        const int64_t q = q0 + n;
-        return q < qlen ? ld_as<C, T>(&Cb[(ch * stride + m) * sp + q * sq]) : (C)0;
-    }
+    typedef C TA; typedef C TB; typedef T TD;
     static constexpr int TK = 128 / (int)sizeof(C);
     T* Cb; int64_t sp, sq, qlen, q0; const C* V; int64_t ldp; int64_t ch; int64_t stride; const C* Wd;
     __device__ __forceinline__ int ktiles() const { return NB / TK; }
-    __device__ __forceinline__ C loadA(int mn, int kt, int k) const
+    __device__ __forceinline__ const C* ptrA(int mn, int kt, int k) const
     {
-        return V[(ch * NB + mn) + (int64_t)(kt * TK + k) * ldp];
+        return &V[(ch * NB + mn) + (int64_t)(kt * TK + k) * ldp];
     }
-    __device__ __forceinline__ C loadB(int mn, int kt, int k) const
+    __device__ __forceinline__ const C* ptrB(int mn, int kt, int k) const
     {
         const int64_t q = q0 + mn;
-        return q < qlen ? Wd[(kt * TK + k) + q * NB] : (C)0;
+        return q < qlen ? &Wd[(kt * TK + k) + q * NB] : nullptr;
     }
-    __device__ __forceinline__ void store(int m, int n, C v) const
+    __device__ __forceinline__ T* ptrD(int m, int n) const
     {
         const int64_t q = q0 + n;
-        if (q < qlen) st_as<T, C>(&Cb[(ch * stride + m) * sp + q * sq], v);
+        return q < qlen ? &Cb[(ch * stride + m) * sp + q * sq] : nullptr;
     }
 };
 

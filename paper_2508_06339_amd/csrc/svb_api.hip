@@ -32,6 +32,12 @@ int check_shape(svb_dtype dt, int64_t m, int64_t n, int nb)
     return SVB_OK;
 }
 
+// the update kernels move 16-byte vectors along both directions of A
+bool aligned_for_vectors(const void* A, int64_t lda)
+{
+    return reinterpret_cast<uintptr_t>(A) % 16 == 0 && lda % 4 == 0;
+}
+
 // chunks-per-domain of the panel tree: as many nb-row tiles as the register-resident
 // panel kernel holds (512 rows), 8 where that kernel does not exist (f64, nb = 128)
 int domain_chunks(svb_dtype dt, int nb)
@@ -295,6 +301,7 @@ int svb_ge2gb(svb_dtype dt, int64_t m, int64_t n, void* A_dev, int64_t lda, int 
     const int rc = check_shape(dt, m, n, nb);
     if (rc != SVB_OK) return rc;
     if (!A_dev || !band_dev || !work_dev || lda < m || ldab < 3 * (int64_t)nb) return SVB_ERR_ARG;
+    if (!aligned_for_vectors(A_dev, lda) || reinterpret_cast<uintptr_t>(work_dev) % 256 != 0) return SVB_ERR_UNSUPPORTED;
     const Carve cv = carve(dt, n, nb);
     if (work_bytes < cv.total) return SVB_ERR_WORKSPACE;
     return ge2gb_dispatch(dt, n, A_dev, lda, nb, band_dev, ldab, work_dev, cv, (hipStream_t)stream);
@@ -363,6 +370,7 @@ int svb_svdvals(svb_dtype dt, int64_t m, int64_t n, void* A_dev, int64_t lda, vo
     int rc = check_shape(dt, m, n, nb);
     if (rc != SVB_OK) return rc;
     if (!A_dev || !S_out_host || !work_dev || lda < m) return SVB_ERR_ARG;
+    if (!aligned_for_vectors(A_dev, lda) || reinterpret_cast<uintptr_t>(work_dev) % 256 != 0) return SVB_ERR_UNSUPPORTED;
     const Carve cv = carve(dt, n, nb);
     if (work_bytes < cv.total) return SVB_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
