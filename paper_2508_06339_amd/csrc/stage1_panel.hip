@@ -205,9 +205,12 @@ __global__ __launch_bounds__(NT) void panel_qr_reg_kernel(C* __restrict__ P, int
 {
     constexpr int NRG = NT / NB, HMAX = NRG * RPT, LT = NT / NB;  // LT lanes cooperate on one row of T
     extern __shared__ __align__(16) unsigned char smem_raw[];
+    // G (NB x NB, column k holds v_c^T v_k for c < k) sits in LDS when it fits next to T,
+    // otherwise in the second half of this domain's slot of Tws
+    constexpr bool G_GLOBAL = sizeof(C) * (size_t)(NB * (NB + 1) + NB * NB) > 140 * 1024;
     C* Ts = reinterpret_cast<C*>(smem_raw);       // NB x (NB+1)
-    C* Gs = Ts + NB * (NB + 1);                   // NB x NB, column k holds v_c^T v_k, c < k
-    C* xs = Gs + NB * NB;                         // 2 x HMAX
+    C* Gs = G_GLOBAL ? Tws + ((int64_t)gridDim.x + blockIdx.x) * NB * NB : Ts + NB * (NB + 1);
+    C* xs = Ts + NB * (NB + 1) + (G_GLOBAL ? 0 : NB * NB);  // 2 x HMAX
     C* part = xs + 2 * HMAX;                      // NRG x NB
     C* rowk = part + NRG * NB;                    // 2 x NB
     C* taus = rowk + 2 * NB;                      // NB
@@ -319,7 +322,8 @@ static void launch_panel_reg(C* P, int64_t ldp, C* Tws, int chunks, int g, C* Pn
                              hipStream_t s)
 {
     constexpr int NRG = NT / NB, HMAX = NRG * RPT;
-    const size_t smem = sizeof(C) * (size_t)(NB * (NB + 1) + NB * NB + 2 * HMAX + NRG * NB + 2 * NB + NB);
+    constexpr bool G_GLOBAL = sizeof(C) * (size_t)(NB * (NB + 1) + NB * NB) > 140 * 1024;
+    const size_t smem = sizeof(C) * (size_t)(NB * (NB + 1) + (G_GLOBAL ? 0 : NB * NB) + 2 * HMAX + NRG * NB + 2 * NB + NB);
     static bool attr_set = false;
     auto kern = panel_qr_reg_kernel<C, NB, RPT, NT>;
     if (!attr_set) {
@@ -333,7 +337,7 @@ static void launch_panel_reg(C* P, int64_t ldp, C* Tws, int chunks, int g, C* Pn
 // rows a register-resident domain can hold, 0 if this (type, nb) has no such kernel
 template <typename C> int panel_reg_rows(int nb);
 template <> int panel_reg_rows<float>(int nb) { return nb == 32 ? 512 : (nb == 64 ? 512 : 512); }
-template <> int panel_reg_rows<double>(int nb) { return nb == 32 ? 512 : (nb == 64 ? 512 : 0); }
+template <> int panel_reg_rows<double>(int nb) { return nb == 32 ? 512 : (nb == 64 ? 512 : 256); }
 
 template <typename C> struct PanelRegDispatch;
 template <> struct PanelRegDispatch<float> {
@@ -348,7 +352,8 @@ template <> struct PanelRegDispatch<double> {
     static void run(int nb, double* P, int64_t ldp, double* Tws, int chunks, int g, double* Pn, int64_t ldn, hipStream_t s)
     {
         if (nb == 32) launch_panel_reg<double, 32, 32, 512>(P, ldp, Tws, chunks, g, Pn, ldn, s);
-        else launch_panel_reg<double, 64, 64, 512>(P, ldp, Tws, chunks, g, Pn, ldn, s);
+        else if (nb == 64) launch_panel_reg<double, 64, 64, 512>(P, ldp, Tws, chunks, g, Pn, ldn, s);
+        else launch_panel_reg<double, 128, 64, 512>(P, ldp, Tws, chunks, g, Pn, ldn, s);  // 4 row groups x 64 rows
     }
 };
 

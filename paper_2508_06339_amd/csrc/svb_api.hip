@@ -39,12 +39,12 @@ bool aligned_for_vectors(const void* A, int64_t lda)
 }
 
 // chunks-per-domain of the panel tree: as many nb-row tiles as the register-resident
-// panel kernel holds (512 rows), 8 where that kernel does not exist (f64, nb = 128)
+// panel kernel holds (512 rows; 256 for f64 at nb = 128)
 int domain_chunks(svb_dtype dt, int nb)
 {
     int g = env_int("SVB_DOMAIN_CHUNKS", 0);
     if (g >= 2 && g <= 64) return g;
-    if (dt == SVB_F64 && nb == 128) return 8;
+    if (dt == SVB_F64 && nb == 128) return 2;
     return 512 / nb;
 }
 constexpr int kMinDomainChunks = 2;  // workspace is sized for any g >= this
@@ -66,7 +66,7 @@ Carve carve(svb_dtype dt, int64_t n, int nb)
     c.panel_elems = (size_t)(2 * n + (int64_t)(kMaxLevels + 2) * nb) * nb;
     // W of every tree level: n^2/g * (1 + 1/g + ...) <= n^2 for g >= 2
     c.w_elems = (size_t)n * (size_t)n + (size_t)n * nb * (kMaxLevels + 1);
-    c.t_elems = (size_t)(n / nb + 1) * nb * nb;
+    c.t_elems = 2 * (size_t)(n / nb + 1) * nb * nb;  // T per domain, plus room for the v^T v products
     c.band_elems = (size_t)(3 * nb) * (size_t)n;
     c.de_elems = (size_t)n;
     size_t off = 0;
