@@ -431,6 +431,174 @@ __global__ __launch_bounds__(NT) void chase_persistent_kernel(C* __restrict__ ba
 #undef BAND
 }
 
+
+// Rows (or columns) of ONE B x B block: line <- line - tau (line . v) v for lines first..B-1.
+// ROWS: a line is a row (stride LD), else a column (contiguous).  A line is split over NT/B threads.
+template <typename C, int B, int NT, bool ROWS>
+__device__ __forceinline__ void apply_one(C* buf, int LD, const C* vs, const C* red, C* part, int first)
+{
+    constexpr int SPLIT = NT / B, W = B / SPLIT;
+    const C tau = red[0];
+    const int tid = threadIdx.x, idx = tid % B, h = tid / B;
+    C* base = ROWS ? buf + idx + h * W * LD : buf + idx * LD + h * W;
+    const int inc = ROWS ? LD : 1;
+    const C* v = vs + h * W;
+    C line[W];
+    C s = 0;
+#pragma unroll
+    for (int j = 0; j < W; ++j) {
+        line[j] = base[j * inc];
+        s += v[j] * line[j];
+    }
+    if (SPLIT > 1) {
+        part[tid] = s;
+        __syncthreads();
+        s = 0;
+#pragma unroll
+        for (int q = 0; q < SPLIT; ++q) s += part[idx + q * B];
+    }
+    s *= tau;
+    if (idx >= first && tau != (C)0) {
+#pragma unroll
+        for (int j = 0; j < W; ++j) base[j * inc] = line[j] - s * v[j];
+    }
+}
+
+// Variant of the pipelined chase that keeps ONE B x B block in LDS (for block sizes of
+// which two do not fit: f64 at B = 128).  Same pipeline protocol and the same arithmetic
+// as chase_persistent_kernel; per step the single buffer holds, in turn, the block above
+// the diagonal block (X), the diagonal block (A2) and the block right of it (A3), each
+// loaded from and stored to the band once.
+template <typename C, int B, int NT>
+__global__ __launch_bounds__(NT) void chase_persistent_1buf_kernel(C* __restrict__ band, int64_t ldab, int64_t n,
+                                                                   int* __restrict__ ctrl, int* __restrict__ progress,
+                                                                   int spin_limit)
+{
+    constexpr int LD = B + 1, CSTEP = NT / B, PER = B * B / NT;
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    C* Wb = reinterpret_cast<C*>(smem_raw);
+    C* vs = Wb + B * LD;
+    C* red = vs + B;    // 2
+    C* part = red + 2;  // NT
+    __shared__ int sh_i, sh_fail;
+    const int tid = threadIdx.x;
+    const int ii = tid % B, jj0 = tid / B;
+    const int64_t ku = 2 * (int64_t)B - 1;
+#define BAND(r_, c_) band[((r_) - (c_) + ku) + (c_) * ldab]
+
+    for (;;) {
+        if (tid == 0) {
+            sh_i = atomicAdd(&ctrl[0], 1);
+            sh_fail = __hip_atomic_load(&ctrl[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __syncthreads();
+        const int64_t i = sh_i;
+        bool failed = sh_fail != 0;
+        __syncthreads();
+        if (i > n - 3) break;
+        const int nsteps = (int)((n - 3 - i) / B) + 1;
+        for (int t = 0; t < nsteps && !failed; ++t) {
+            const int64_t c0 = i + 1 + (int64_t)t * B;
+            const int len = (int)min((int64_t)B, n - c0);
+            const int na3 = (int)max((int64_t)0, min((int64_t)B, n - (c0 + B)));
+            if (i > 0) {
+                if (tid == 0) {
+                    const int need = t + 3;
+                    int spins = 0;
+                    while (__hip_atomic_load(&progress[i - 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < need) {
+                        if (++spins > spin_limit) {
+                            atomicExch(&ctrl[1], 1);
+                            sh_fail = 1;
+                            break;
+                        }
+                        __builtin_amdgcn_s_sleep(1);
+                    }
+                }
+                __syncthreads();
+                failed = sh_fail != 0;
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+            }
+            if (!failed) {
+                C zr[PER];
+                // A2 -> registers (its latency overlaps the work on X)
+#pragma unroll
+                for (int q = 0; q < PER; ++q) {
+                    const int jj = jj0 + q * CSTEP;
+                    zr[q] = (ii < len && jj < len) ? gld(&BAND(c0 + ii, c0 + jj)) : (C)0;
+                }
+                if (t == 0) {
+                    for (int jj = jj0; jj < B; jj += CSTEP) {
+                        C xv = 0;
+                        if (ii == 0 && jj < len) xv = gld(&BAND(i, c0 + jj));
+                        Wb[ii + jj * LD] = xv;
+                    }
+                    __syncthreads();
+                }
+                // right reflector from X row 0; X rows 1.. updated; X is final: store it
+                house_wave<C, B>(Wb, LD, len, vs, red);
+                __syncthreads();
+                apply_one<C, B, NT, true>(Wb, LD, vs, red, part, 1);
+                __syncthreads();
+#pragma unroll
+                for (int q = 0; q < PER; ++q) {
+                    const int jj = jj0 + q * CSTEP;
+                    const C v = Wb[ii + jj * LD];
+                    if (jj < len) {
+                        if (t == 0) {
+                            if (ii == 0) gst(&BAND(i, c0 + jj), v);
+                        } else {
+                            gst(&BAND(c0 - B + ii, c0 + jj), v);
+                        }
+                    }
+                    Wb[ii + jj * LD] = zr[q];   // A2 takes the buffer
+                }
+                __syncthreads();
+                // A3 -> registers, then the right reflector on every row of A2
+#pragma unroll
+                for (int q = 0; q < PER; ++q) {
+                    const int jj = jj0 + q * CSTEP;
+                    zr[q] = (ii < len && jj < na3) ? gld(&BAND(c0 + ii, c0 + B + jj)) : (C)0;
+                }
+                apply_one<C, B, NT, true>(Wb, LD, vs, red, part, 0);
+                __syncthreads();
+                // left reflector from A2 column 0; columns 1.. updated; A2 is final: store it
+                house_wave<C, B>(Wb, 1, len, vs, red);
+                __syncthreads();
+                apply_one<C, B, NT, false>(Wb, LD, vs, red, part, 1);
+                __syncthreads();
+#pragma unroll
+                for (int q = 0; q < PER; ++q) {
+                    const int jj = jj0 + q * CSTEP;
+                    if (ii < len && jj < len) gst(&BAND(c0 + ii, c0 + jj), Wb[ii + jj * LD]);
+                    Wb[ii + jj * LD] = zr[q];   // A3 takes the buffer
+                }
+                __syncthreads();
+                // the left reflector on every column of A3, which stays as the next step's X
+                apply_one<C, B, NT, false>(Wb, LD, vs, red, part, 0);
+                __syncthreads();
+                if (t == nsteps - 1) {
+#pragma unroll
+                    for (int q = 0; q < PER; ++q) {
+                        const int jj = jj0 + q * CSTEP;
+                        if (ii < len && jj < na3) gst(&BAND(c0 + ii, c0 + B + jj), Wb[ii + jj * LD]);
+                    }
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+            }
+            __syncthreads();
+            if (tid == 0)
+                __hip_atomic_store(&progress[i], (failed || t == nsteps - 1) ? kDone : t + 1, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+            __syncthreads();
+        }
+        if (failed) {
+            if (tid == 0) __hip_atomic_store(&progress[i], kDone, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __syncthreads();
+    }
+#undef BAND
+}
+
 __global__ __launch_bounds__(256) void chase_ctrl_clear_kernel(int* __restrict__ ctrl, int64_t count)
 {
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count;
@@ -441,10 +609,14 @@ __global__ __launch_bounds__(256) void chase_ctrl_clear_kernel(int* __restrict__
 template <typename C, int B>
 static bool launch_chase_persistent(C* band, int64_t ldab, int64_t n, int* ctrl, hipStream_t s)
 {
-    constexpr int NT = 256;
-    constexpr size_t smem = sizeof(C) * (size_t)(2 * B * (B + 1) + B + NT / kWave + 1 + NT);
+    constexpr size_t smem2 = sizeof(C) * (size_t)(2 * B * (B + 1) + B + 256 / kWave + 1 + 256);
+    constexpr bool ONEBUF = smem2 > 150 * 1024;   // two blocks do not fit: single-buffer variant, 512 threads
+    constexpr int NT = ONEBUF ? 512 : 256;
+    constexpr size_t smem = ONEBUF ? sizeof(C) * (size_t)(B * (B + 1) + B + 2 + NT) : smem2;
     if (smem > 150 * 1024) return false;
-    auto kern = chase_persistent_kernel<C, B, NT>;
+    void (*kern)(C*, int64_t, int64_t, int*, int*, int);
+    if (ONEBUF) kern = chase_persistent_1buf_kernel<C, B, ONEBUF ? 512 : 256>;
+    else kern = chase_persistent_kernel<C, B, 256>;
     static bool attr_set = false;
     if (!attr_set) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
