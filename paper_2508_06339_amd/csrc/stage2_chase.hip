@@ -695,6 +695,16 @@ int run_chase(int64_t n, int nb, C* band, int64_t ldab, C* d, C* e, void* work,
     return hipGetLastError() == hipSuccess ? SVB_OK : SVB_ERR_DEVICE;
 }
 
+template <typename C>
+void launch_extract_bidiag(const C* band, int64_t ldab, int64_t n, int b, C* d, C* e, const int* ctrl, hipStream_t s)
+{
+    int blocks = (int)((n + 255) / 256);
+    if (blocks > 1024) blocks = 1024;
+    hipLaunchKernelGGL((extract_bidiag_kernel<C>), dim3(blocks), dim3(256), 0, s, band, ldab, n, b, d, e, ctrl);
+}
+template void launch_extract_bidiag<double>(const double*, int64_t, int64_t, int, double*, double*, const int*, hipStream_t);
+template void launch_extract_bidiag<float>(const float*, int64_t, int64_t, int, float*, float*, const int*, hipStream_t);
+
 template int run_chase<double>(int64_t, int, double*, int64_t, double*, double*, void*, size_t, hipStream_t);
 template int run_chase<float>(int64_t, int, float*, int64_t, float*, float*, void*, size_t, hipStream_t);
 

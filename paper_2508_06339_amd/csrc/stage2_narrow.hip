@@ -1,0 +1,313 @@
+// Stage 2, narrow bands: band -> bidiagonal for a band of D = 8 super-diagonals
+// (paper Section 3, second stage; the paper points to cache-efficient tile kernels and a
+// communication-avoiding strategy without giving the algorithm).
+//
+// The chase itself is the one described in stage2_chase.hip (sweep i, step t at
+// c0 = i + 1 + t*D: right reflector from row r on columns c0.., left reflector from column
+// c0 on rows c0..; step t of sweep i+1 after step t+2 of sweep i).  What changes is where
+// the hand-over between consecutive sweeps happens.  With one workgroup per sweep every
+// hand-over goes through device memory, and the 3n dependent steps each pay that latency.
+// Here a workgroup owns a BUNDLE of NW consecutive sweeps, one per wave, and a sliding
+// window of the band in LDS: in super-step T wave w performs step T - 3w of its sweep, a
+// workgroup barrier separates super-steps, so the hand-over between the waves of a bundle
+// is an LDS access.  Device memory is touched in chunks of CH = 8*D columns: a chunk enters
+// the window two groups (of 8 super-steps) before it is needed, and leaves it once the last
+// wave has passed.  Bundles are pipelined over workgroups through a ticket counter and a
+// per-bundle count of flushed columns (bounded waits, as in stage2_chase.hip).
+//
+// Packed band: entry (i,j) at band[(i - j + ku) + j*ldab]; ku >= 2D-1 and ldab >= ku + D.
+#include "svb_internal.h"
+
+namespace svb {
+
+namespace {
+
+constexpr int kAllFlushed = 0x7fffffff;
+
+template <typename C> __device__ __forceinline__ C ngld(const C* p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+template <typename C> __device__ __forceinline__ void ngst(C* p, C v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+template <typename C>
+__device__ __forceinline__ void nreflector(C alpha, C ss, C& beta, C& tau, C& inv)
+{
+    if (ss == (C)0) {
+        beta = alpha; tau = 0; inv = 0;
+    } else {
+        const C nrm = sqrt(alpha * alpha + ss);
+        beta = alpha >= (C)0 ? -nrm : nrm;
+        tau = (beta - alpha) / beta;
+        inv = (C)1 / (alpha - beta);
+    }
+}
+
+// One chase step of one sweep, done by one wave on the LDS window.
+template <typename C, int D, int WC>
+__device__ __forceinline__ void narrow_step(C* win, int64_t i, int64_t t, int64_t n)
+{
+    constexpr int RS = 3 * D;
+    const int lane = threadIdx.x & 63;
+#define WIN(r_, c_) win[(int)((c_) & (WC - 1)) * RS + (int)((r_) - (c_)) + 2 * D - 1]
+    const int64_t c0 = i + 1 + t * D;
+    const int len = (int)min((int64_t)D, n - c0);
+    const int64_t r = (t == 0) ? i : c0 - D;
+    // ---- right reflector from row r, applied to rows r+1 .. c0+len-1
+    {
+        C x = (lane < len) ? WIN(r, c0 + lane) : (C)0;
+        C ss = (lane > 0 && lane < len) ? x * x : (C)0;
+#pragma unroll
+        for (int off = 1; off < D; off <<= 1) ss += __shfl_xor(ss, off, 64);
+        ss = __shfl(ss, 0, 64);   // every lane needs the reflector, not only the first D
+        const C alpha = __shfl(x, 0, 64);
+        C beta, tau, inv;
+        nreflector<C>(alpha, ss, beta, tau, inv);
+        const C v = (lane < len) ? ((lane == 0) ? (C)1 : x * inv) : (C)0;
+        if (lane < len) WIN(r, c0 + lane) = (lane == 0) ? beta : (C)0;
+        const int rows = (int)(c0 + len - 1 - r);
+        const int64_t q = r + 1 + lane;
+        C s = 0;
+        C a[D];
+#pragma unroll
+        for (int j = 0; j < D; ++j) {
+            const C vj = __shfl(v, j, 64);
+            a[j] = (lane < rows && j < len) ? WIN(q, c0 + j) : (C)0;
+            s += vj * a[j];
+        }
+        s *= tau;
+        if (tau != (C)0) {
+#pragma unroll
+            for (int j = 0; j < D; ++j) {
+                const C vj = __shfl(v, j, 64);
+                if (lane < rows && j < len) WIN(q, c0 + j) = a[j] - s * vj;
+            }
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    // ---- left reflector from column c0, applied to columns c0+1 .. min(n-1, c0+len-1+D)
+    {
+        C x = (lane < len) ? WIN(c0 + lane, c0) : (C)0;
+        C ss = (lane > 0 && lane < len) ? x * x : (C)0;
+#pragma unroll
+        for (int off = 1; off < D; off <<= 1) ss += __shfl_xor(ss, off, 64);
+        ss = __shfl(ss, 0, 64);   // every lane needs the reflector, not only the first D
+        const C alpha = __shfl(x, 0, 64);
+        C beta, tau, inv;
+        nreflector<C>(alpha, ss, beta, tau, inv);
+        const C v = (lane < len) ? ((lane == 0) ? (C)1 : x * inv) : (C)0;
+        if (lane < len) WIN(c0 + lane, c0) = (lane == 0) ? beta : (C)0;
+        const int cols = (int)(min(n - 1, c0 + len - 1 + D) - c0);
+        const int64_t c = c0 + 1 + lane;
+        C s = 0;
+        C a[D];
+#pragma unroll
+        for (int j = 0; j < D; ++j) {
+            const C vj = __shfl(v, j, 64);
+            a[j] = (lane < cols && j < len) ? WIN(c0 + j, c) : (C)0;
+            s += vj * a[j];
+        }
+        s *= tau;
+        if (tau != (C)0) {
+#pragma unroll
+            for (int j = 0; j < D; ++j) {
+                const C vj = __shfl(v, j, 64);
+                if (lane < cols && j < len) WIN(c0 + j, c) = a[j] - s * vj;
+            }
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+#undef WIN
+}
+
+template <typename C, int D, int NW, int WC>
+__global__ __launch_bounds__(NW * 64) void chase_narrow_kernel(C* __restrict__ band, int64_t ldab, int64_t ku,
+                                                               int64_t n, int* __restrict__ ctrl,
+                                                               int* __restrict__ flushed, int spin_limit)
+{
+    constexpr int NT = NW * 64, RS = 3 * D, CH = 8 * D, GS = 8;
+    constexpr int LAGC = (3 * (NW - 1) + 7) / 8;          // chunks the flush trails the load front by
+    constexpr int PER = (CH * RS + NT - 1) / NT;
+    static_assert((LAGC + 4) * CH <= WC, "window too small");
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    C* win = reinterpret_cast<C*>(smem_raw);  // WC columns x RS
+    __shared__ int sh_b, sh_fail;
+    const int tid = threadIdx.x, wave = tid >> 6;
+    const int64_t nsweeps = n - 2;                         // sweeps 0 .. n-3
+    const int64_t nbundles = (nsweeps + NW - 1) / NW;
+
+    // element e of a chunk: column e / RS, storage row e % RS (row 3D-1 is unused padding)
+    auto chunk_ptr = [&](int64_t col0, int e, bool& ok) -> C* {
+        const int cl = e / RS, sr = e % RS;
+        const int64_t j = col0 + cl;
+        const int64_t i = j + sr - (2 * D - 1);
+        ok = e < CH * RS && sr < RS - 1 && j < n && i >= 0 && i < n;
+        return band + (i - j + ku) + j * ldab;
+    };
+
+    for (;;) {
+        if (tid == 0) {
+            sh_b = atomicAdd(&ctrl[0], 1);
+            sh_fail = __hip_atomic_load(&ctrl[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __syncthreads();
+        const int64_t b = sh_b;
+        bool failed = sh_fail != 0;
+        __syncthreads();
+        if (b >= nbundles) break;
+        const int64_t i0 = b * NW;
+        const int64_t my_i = i0 + wave;
+        const bool have = my_i <= n - 3;
+        const int64_t my_steps = have ? (n - 3 - my_i) / D + 1 : 0;
+        // super-steps of this bundle: wave 0 has the most steps, later waves start 3 apart
+        int64_t ttot = 0;
+        for (int w = 0; w < NW; ++w) {
+            const int64_t iw = i0 + w;
+            if (iw <= n - 3) ttot = max(ttot, (int64_t)3 * w + (n - 3 - iw) / D + 1);
+        }
+        const int64_t ngroups = (ttot + GS - 1) / GS;
+        const int64_t nchunks = (n - i0 + CH - 1) / CH;    // chunks that hold columns < n
+
+        // waits until the previous bundle has flushed every column below `upto`
+        auto wait_prev = [&](int64_t upto) {
+            if (b > 0) {
+                if (tid == 0) {
+                    const int need = (int)min(upto, n);
+                    int spins = 0;
+                    while (__hip_atomic_load(&flushed[b - 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < need) {
+                        if (++spins > spin_limit) {
+                            atomicExch(&ctrl[1], 1);
+                            sh_fail = 1;
+                            break;
+                        }
+                        __builtin_amdgcn_s_sleep(2);
+                    }
+                }
+                __syncthreads();
+                failed = failed || sh_fail != 0;
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+            }
+        };
+        auto load_chunk_direct = [&](int64_t k) {
+            const int64_t col0 = i0 + k * CH;
+#pragma unroll
+            for (int q = 0; q < PER; ++q) {
+                const int e = tid + q * NT;
+                bool ok;
+                C* p = chunk_ptr(col0, e, ok);
+                if (e < CH * RS) win[(int)((col0 + e / RS) & (WC - 1)) * RS + e % RS] = ok ? ngld(p) : (C)0;
+            }
+        };
+        auto flush_chunk = [&](int64_t k) {
+            const int64_t col0 = i0 + k * CH;
+#pragma unroll
+            for (int q = 0; q < PER; ++q) {
+                const int e = tid + q * NT;
+                bool ok;
+                C* p = chunk_ptr(col0, e, ok);
+                if (ok) ngst(p, win[(int)((col0 + e / RS) & (WC - 1)) * RS + e % RS]);
+            }
+        };
+
+        if (!failed) wait_prev(i0 + 2 * CH);
+        if (!failed) {
+            load_chunk_direct(0);
+            if (nchunks > 1) load_chunk_direct(1);
+        }
+        __syncthreads();
+        int64_t next_flush = 0;                            // first chunk not yet flushed
+        for (int64_t g = 0; g < ngroups && !failed; ++g) {
+            // chunk g+2 is requested now and lands in the window at the end of the group
+            C pre[PER];
+            const bool want = g + 2 < nchunks;
+            if (want) wait_prev(i0 + (g + 3) * CH);
+            if (failed) break;
+            if (want) {
+#pragma unroll
+                for (int q = 0; q < PER; ++q) {
+                    bool ok;
+                    C* p = chunk_ptr(i0 + (g + 2) * CH, tid + q * NT, ok);
+                    pre[q] = ok ? ngld(p) : (C)0;
+                }
+            }
+            for (int ts = 0; ts < GS; ++ts) {
+                const int64_t T = g * GS + ts;
+                const int64_t t = T - 3 * wave;
+                if (have && t >= 0 && t < my_steps) narrow_step<C, D, WC>(win, my_i, t, n);
+                __syncthreads();
+            }
+            if (want) {
+                const int64_t col0 = i0 + (g + 2) * CH;
+#pragma unroll
+                for (int q = 0; q < PER; ++q) {
+                    const int e = tid + q * NT;
+                    if (e < CH * RS) win[(int)((col0 + e / RS) & (WC - 1)) * RS + e % RS] = pre[q];
+                }
+            }
+            const int64_t f = g - LAGC;
+            if (f >= 0 && f < nchunks) {
+                flush_chunk(f);
+                next_flush = f + 1;
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+                __syncthreads();
+                if (tid == 0)
+                    __hip_atomic_store(&flushed[b], (int)min(i0 + (f + 1) * CH, (int64_t)kAllFlushed - 1),
+                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            __syncthreads();
+        }
+        if (!failed) {
+            // everything that entered the window and has not been written back yet
+            const int64_t last = min(nchunks, ngroups + 2);
+            for (int64_t k = next_flush; k < last; ++k) flush_chunk(k);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+        }
+        __syncthreads();
+        if (tid == 0) __hip_atomic_store(&flushed[b], kAllFlushed, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+    }
+}
+
+__global__ __launch_bounds__(256) void narrow_clear_kernel(int* __restrict__ p, int64_t count)
+{
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (int64_t)gridDim.x * blockDim.x)
+        p[i] = 0;
+}
+
+}  // namespace
+
+// ctrl: 64 ints (ticket, error flag) followed by one flushed counter per bundle
+size_t chase_narrow_workspace_bytes(int64_t n) { return (size_t)(64 + n / 8 + 8) * sizeof(int); }
+
+template <typename C>
+int run_chase_narrow(int64_t n, C* band, int64_t ldab, int64_t ku, int* ctrl, hipStream_t s)
+{
+    constexpr int D = 8;
+    constexpr int NW = sizeof(C) == 8 ? 8 : 16;
+    constexpr int WC = sizeof(C) == 8 ? 512 : 1024;
+    if (n < 3) return SVB_OK;
+    const size_t smem = sizeof(C) * (size_t)WC * 3 * D;
+    auto kern = chase_narrow_kernel<C, D, NW, WC>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        attr_set = true;
+    }
+    const int64_t nbundles = (n - 2 + NW - 1) / NW;
+    const int64_t count = 64 + nbundles + 1;
+    int cb = (int)((count + 255) / 256);
+    hipLaunchKernelGGL(narrow_clear_kernel, dim3(cb > 256 ? 256 : cb), dim3(256), 0, s, ctrl, count);
+    const int grid = (int)min((int64_t)env_int("SVB_NARROW_GRID", 128), nbundles);
+    const int spin_limit = env_int("SVB_CHASE_SPIN", 1 << 20);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(NW * 64), smem, s, band, ldab, ku, n, ctrl, ctrl + 64, spin_limit);
+    return hipGetLastError() == hipSuccess ? SVB_OK : SVB_ERR_DEVICE;
+}
+
+template int run_chase_narrow<double>(int64_t, double*, int64_t, int64_t, int*, hipStream_t);
+template int run_chase_narrow<float>(int64_t, float*, int64_t, int64_t, int*, hipStream_t);
+
+}  // namespace svb

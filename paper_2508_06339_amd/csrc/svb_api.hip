@@ -32,6 +32,13 @@ int check_shape(svb_dtype dt, int64_t m, int64_t n, int nb)
     return SVB_OK;
 }
 
+// scratch of stage 2: whichever of the two chase variants needs more
+size_t gb2bd_bytes(int64_t n, int nb)
+{
+    const size_t a = nb == 8 ? 0 : chase_workspace_bytes(n, nb), b = chase_narrow_workspace_bytes(n);
+    return (a > b ? a : b);
+}
+
 // the update kernels move 16-byte vectors along both directions of A
 bool aligned_for_vectors(const void* A, int64_t lda)
 {
@@ -83,7 +90,7 @@ Carve carve(svb_dtype dt, int64_t n, int nb)
     c.off_sig = off; off += align_up(c.de_elems * cs);
     c.off_s3 = off; off += align_up(bdsvals_dev_workspace_bytes(n));
     c.off_err = off; off += 256;
-    off += chase_workspace_bytes(n, nb);
+    off += align_up(gb2bd_bytes(n, nb));
     c.total = off;
     return c;
 }
@@ -312,19 +319,30 @@ int svb_gb2bd(svb_dtype band_dt, int64_t n, int nb, void* band_dev, int64_t ldab
 {
     if (n < 0) return SVB_ERR_ARG;
     if (band_dt != SVB_F64 && band_dt != SVB_F32) return SVB_ERR_UNSUPPORTED;
-    if (nb != 32 && nb != 64 && nb != 128) return SVB_ERR_UNSUPPORTED;
+    if (nb != 8 && nb != 32 && nb != 64 && nb != 128) return SVB_ERR_UNSUPPORTED;
     if (n == 0) return SVB_OK;
     if (!band_dev || !d_dev || !e_dev || ldab < 3 * (int64_t)nb) return SVB_ERR_ARG;
-    if (work_bytes < chase_workspace_bytes(n, nb)) return SVB_ERR_WORKSPACE;
-    if (chase_workspace_bytes(n, nb) > 0 && !work_dev) return SVB_ERR_ARG;
+    if (work_bytes < gb2bd_bytes(n, nb)) return SVB_ERR_WORKSPACE;
+    if (!work_dev) return SVB_ERR_ARG;
     hipStream_t s = (hipStream_t)stream;
     const double cs = band_dt == SVB_F64 ? 8.0 : 4.0;
     prof_begin(SVB_PROF_CHASE, s, 6.0 * (double)n * (double)n * nb, 3.0 * (double)n * (double)n * nb * cs);
     int rc;
-    if (band_dt == SVB_F64)
+    if (nb == 8) {
+        // narrow band: bundles of sweeps inside LDS windows
+        int* ctrl = static_cast<int*>(work_dev);
+        if (band_dt == SVB_F64) {
+            rc = run_chase_narrow<double>(n, (double*)band_dev, ldab, 15, ctrl, s);
+            launch_extract_bidiag<double>((const double*)band_dev, ldab, n, 8, (double*)d_dev, (double*)e_dev, ctrl, s);
+        } else {
+            rc = run_chase_narrow<float>(n, (float*)band_dev, ldab, 15, ctrl, s);
+            launch_extract_bidiag<float>((const float*)band_dev, ldab, n, 8, (float*)d_dev, (float*)e_dev, ctrl, s);
+        }
+    } else if (band_dt == SVB_F64) {
         rc = run_chase<double>(n, nb, (double*)band_dev, ldab, (double*)d_dev, (double*)e_dev, work_dev, work_bytes, s);
-    else
+    } else {
         rc = run_chase<float>(n, nb, (float*)band_dev, ldab, (float*)d_dev, (float*)e_dev, work_dev, work_bytes, s);
+    }
     prof_end(s);
     return rc;
 }
@@ -332,8 +350,8 @@ int svb_gb2bd(svb_dtype band_dt, int64_t n, int nb, void* band_dev, int64_t ldab
 int svb_gb2bd_workspace_bytes(int64_t n, int nb, size_t* dev_bytes)
 {
     if (n < 0 || !dev_bytes) return SVB_ERR_ARG;
-    if (nb != 32 && nb != 64 && nb != 128) return SVB_ERR_UNSUPPORTED;
-    *dev_bytes = chase_workspace_bytes(n, nb);
+    if (nb != 8 && nb != 32 && nb != 64 && nb != 128) return SVB_ERR_UNSUPPORTED;
+    *dev_bytes = gb2bd_bytes(n, nb);
     return SVB_OK;
 }
 
@@ -390,7 +408,7 @@ int svb_svdvals(svb_dtype dt, int64_t m, int64_t n, void* A_dev, int64_t lda, vo
     (void)hipEventRecord(ev1, s);
     if (rc == SVB_OK) {
         void* cw = w + cv.off_err + 256;
-        rc = svb_gb2bd(bdt, n, nb, band, ldab, dd, de, cw, chase_workspace_bytes(n, nb), s);
+        rc = svb_gb2bd(bdt, n, nb, band, ldab, dd, de, cw, gb2bd_bytes(n, nb), s);
     }
     (void)hipEventRecord(ev2, s);
     const bool host3 = [] { const char* v = std::getenv("SVB_STAGE3"); return v && std::strcmp(v, "host") == 0; }();

@@ -118,7 +118,9 @@ def test_stage1_band_preserves_singular_values():
 
 
 @pytest.mark.parametrize("dtype,n,nb", [("f64", 200, 32), ("f32", 333, 64), ("f64", 130, 128), ("f32", 700, 128),
-                                         ("f64", 1000, 64), ("f64", 3, 32), ("f64", 2, 32)])
+                                         ("f64", 1000, 64), ("f64", 3, 32), ("f64", 2, 32),
+                                         ("f64", 9, 8), ("f64", 130, 8), ("f32", 1000, 8), ("f64", 1337, 8),
+                                         ("f32", 5000, 8)])
 def test_stage2_on_random_band(dtype, n, nb):
     # random upper band input: Frobenius norm kept, bdsvals(d, e) = oracle(band as dense)
     npdt = workloads.NP_DTYPE[dtype]
