@@ -7,11 +7,11 @@
 // c0 on rows c0..; step t of sweep i+1 after step t+2 of sweep i).  What changes is where
 // the hand-over between consecutive sweeps happens.  With one workgroup per sweep every
 // hand-over goes through device memory, and the 3n dependent steps each pay that latency.
-// Here a workgroup owns a BUNDLE of NW consecutive sweeps, one per wave, and a sliding
-// window of the band in LDS: in super-step T wave w performs step T - 3w of its sweep, a
+// Here a workgroup owns a BUNDLE of NW consecutive sweeps, four per wave (16 lanes each), and
+// a sliding window of the band in LDS: in super-step T sweep w of the bundle performs its step T - 3w, a
 // workgroup barrier separates super-steps, so the hand-over between the waves of a bundle
-// is an LDS access.  Device memory is touched in chunks of CH = 8*D columns: a chunk enters
-// the window two groups (of 8 super-steps) before it is needed, and leaves it once the last
+// is an LDS access.  Device memory is touched in chunks of CH = 8*D or 16*D columns: a chunk enters
+// the window two groups (of 8 or 16 super-steps) before it is needed, and leaves it once the last
 // wave has passed.  Bundles are pipelined over workgroups through a ticket counter and a
 // per-bundle count of flushed columns (bounded waits, as in stage2_chase.hip).
 //
@@ -46,97 +46,111 @@ __device__ __forceinline__ void nreflector(C alpha, C ss, C& beta, C& tau, C& in
     }
 }
 
-// One chase step of one sweep, done by one wave on the LDS window.
+// One chase step for each of the four sweeps of a wave: lanes 16g .. 16g+15 work on the
+// sweep of group g (its own i, t; act = false if that sweep has no step now).  vbuf holds
+// the reflector of each group (4 x D entries per wave) so that every lane can read all of it.
 template <typename C, int D, int WC>
-__device__ __forceinline__ void narrow_step(C* win, int64_t i, int64_t t, int64_t n)
+__device__ __forceinline__ void narrow_step4(C* win, C* vbuf, int i, int t, bool act, int n)
 {
     constexpr int RS = 3 * D;
-    const int lane = threadIdx.x & 63;
-#define WIN(r_, c_) win[(int)((c_) & (WC - 1)) * RS + (int)((r_) - (c_)) + 2 * D - 1]
-    const int64_t c0 = i + 1 + t * D;
-    const int len = (int)min((int64_t)D, n - c0);
-    const int64_t r = (t == 0) ? i : c0 - D;
+    const int lane = threadIdx.x & 63, sub = lane & 15, grp = lane >> 4;
+#define WIN(r_, c_) win[((c_) & (WC - 1)) * RS + ((r_) - (c_)) + 2 * D - 1]
+    const int c0 = i + 1 + t * D;
+    const int len = act ? min(D, n - c0) : 0;
+    const int r = (t == 0) ? i : c0 - D;
+    C* vb = vbuf + grp * D;
     // ---- right reflector from row r, applied to rows r+1 .. c0+len-1
     {
-        C x = (lane < len) ? WIN(r, c0 + lane) : (C)0;
-        C ss = (lane > 0 && lane < len) ? x * x : (C)0;
+        // the pivot row goes through vb so that every lane can form the reflector itself
+        const C x = (sub < len) ? WIN(r, c0 + sub) : (C)0;
+        if (sub < D) vb[sub] = x;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+        C v[D];
+        C ss = 0;
 #pragma unroll
-        for (int off = 1; off < D; off <<= 1) ss += __shfl_xor(ss, off, 64);
-        ss = __shfl(ss, 0, 64);   // every lane needs the reflector, not only the first D
-        const C alpha = __shfl(x, 0, 64);
-        C beta, tau, inv;
-        nreflector<C>(alpha, ss, beta, tau, inv);
-        const C v = (lane < len) ? ((lane == 0) ? (C)1 : x * inv) : (C)0;
-        if (lane < len) WIN(r, c0 + lane) = (lane == 0) ? beta : (C)0;
-        const int rows = (int)(c0 + len - 1 - r);
-        const int64_t q = r + 1 + lane;
-        C s = 0;
-        C a[D];
-#pragma unroll
-        for (int j = 0; j < D; ++j) {
-            const C vj = __shfl(v, j, 64);
-            a[j] = (lane < rows && j < len) ? WIN(q, c0 + j) : (C)0;
-            s += vj * a[j];
+        for (int jj = 0; jj < D; ++jj) {
+            v[jj] = vb[jj];
+            if (jj > 0) ss += v[jj] * v[jj];
         }
-        s *= tau;
-        if (tau != (C)0) {
+        C beta, tau, inv;
+        nreflector<C>(v[0], ss, beta, tau, inv);
+        v[0] = (C)1;
 #pragma unroll
-            for (int j = 0; j < D; ++j) {
-                const C vj = __shfl(v, j, 64);
-                if (lane < rows && j < len) WIN(q, c0 + j) = a[j] - s * vj;
+        for (int jj = 1; jj < D; ++jj) v[jj] *= inv;
+        if (sub < len) WIN(r, c0 + sub) = (sub == 0) ? beta : (C)0;
+        const int rows = c0 + len - 1 - r;
+        if (sub < rows && tau != (C)0) {
+            const int q = r + 1 + sub;
+            C a[D];
+            C s = 0;
+#pragma unroll
+            for (int jj = 0; jj < D; ++jj) {
+                a[jj] = (jj < len) ? WIN(q, c0 + jj) : (C)0;
+                s += v[jj] * a[jj];
             }
+            s *= tau;
+#pragma unroll
+            for (int jj = 0; jj < D; ++jj)
+                if (jj < len) WIN(q, c0 + jj) = a[jj] - s * v[jj];
         }
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
     // ---- left reflector from column c0, applied to columns c0+1 .. min(n-1, c0+len-1+D)
     {
-        C x = (lane < len) ? WIN(c0 + lane, c0) : (C)0;
-        C ss = (lane > 0 && lane < len) ? x * x : (C)0;
+        const C x = (sub < len) ? WIN(c0 + sub, c0) : (C)0;
+        if (sub < D) vb[sub] = x;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+        C v[D];
+        C ss = 0;
 #pragma unroll
-        for (int off = 1; off < D; off <<= 1) ss += __shfl_xor(ss, off, 64);
-        ss = __shfl(ss, 0, 64);   // every lane needs the reflector, not only the first D
-        const C alpha = __shfl(x, 0, 64);
-        C beta, tau, inv;
-        nreflector<C>(alpha, ss, beta, tau, inv);
-        const C v = (lane < len) ? ((lane == 0) ? (C)1 : x * inv) : (C)0;
-        if (lane < len) WIN(c0 + lane, c0) = (lane == 0) ? beta : (C)0;
-        const int cols = (int)(min(n - 1, c0 + len - 1 + D) - c0);
-        const int64_t c = c0 + 1 + lane;
-        C s = 0;
-        C a[D];
-#pragma unroll
-        for (int j = 0; j < D; ++j) {
-            const C vj = __shfl(v, j, 64);
-            a[j] = (lane < cols && j < len) ? WIN(c0 + j, c) : (C)0;
-            s += vj * a[j];
+        for (int jj = 0; jj < D; ++jj) {
+            v[jj] = vb[jj];
+            if (jj > 0) ss += v[jj] * v[jj];
         }
-        s *= tau;
-        if (tau != (C)0) {
+        C beta, tau, inv;
+        nreflector<C>(v[0], ss, beta, tau, inv);
+        v[0] = (C)1;
 #pragma unroll
-            for (int j = 0; j < D; ++j) {
-                const C vj = __shfl(v, j, 64);
-                if (lane < cols && j < len) WIN(c0 + j, c) = a[j] - s * vj;
+        for (int jj = 1; jj < D; ++jj) v[jj] *= inv;
+        if (sub < len) WIN(c0 + sub, c0) = (sub == 0) ? beta : (C)0;
+        const int cols = act ? min(n - 1, c0 + len - 1 + D) - c0 : 0;
+        if (sub < cols && tau != (C)0) {
+            const int c = c0 + 1 + sub;
+            C a[D];
+            C s = 0;
+#pragma unroll
+            for (int jj = 0; jj < D; ++jj) {
+                a[jj] = (jj < len) ? WIN(c0 + jj, c) : (C)0;
+                s += v[jj] * a[jj];
             }
+            s *= tau;
+#pragma unroll
+            for (int jj = 0; jj < D; ++jj)
+                if (jj < len) WIN(c0 + jj, c) = a[jj] - s * v[jj];
         }
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
 #undef WIN
 }
 
-template <typename C, int D, int NW, int WC>
-__global__ __launch_bounds__(NW * 64) void chase_narrow_kernel(C* __restrict__ band, int64_t ldab, int64_t ku,
+template <typename C, int D, int NW, int WC, int GS>
+__global__ __launch_bounds__(NW * 16) void chase_narrow_kernel(C* __restrict__ band, int64_t ldab, int64_t ku,
                                                                int64_t n, int* __restrict__ ctrl,
                                                                int* __restrict__ flushed, int spin_limit)
 {
-    constexpr int NT = NW * 64, RS = 3 * D, CH = 8 * D, GS = 8;
-    constexpr int LAGC = (3 * (NW - 1) + 7) / 8;          // chunks the flush trails the load front by
+    constexpr int NT = NW * 16, RS = 3 * D, CH = GS * D;   // four sweeps per wave
+    constexpr int LAGC = (3 * (NW - 1) + GS - 1) / GS;    // chunks the flush trails the load front by
     constexpr int PER = (CH * RS + NT - 1) / NT;
     static_assert((LAGC + 4) * CH <= WC, "window too small");
     extern __shared__ __align__(16) unsigned char smem_raw[];
     C* win = reinterpret_cast<C*>(smem_raw);  // WC columns x RS
+    C* vbuf = win + WC * RS + (threadIdx.x >> 6) * 4 * D;
     __shared__ int sh_b, sh_fail;
-    const int tid = threadIdx.x, wave = tid >> 6;
+    const int tid = threadIdx.x;
+    const int slot = ((tid >> 6) << 2) + ((tid & 63) >> 4);   // which sweep of the bundle this lane works on
     const int64_t nsweeps = n - 2;                         // sweeps 0 .. n-3
     const int64_t nbundles = (nsweeps + NW - 1) / NW;
 
@@ -160,7 +174,7 @@ __global__ __launch_bounds__(NW * 64) void chase_narrow_kernel(C* __restrict__ b
         __syncthreads();
         if (b >= nbundles) break;
         const int64_t i0 = b * NW;
-        const int64_t my_i = i0 + wave;
+        const int64_t my_i = i0 + slot;
         const bool have = my_i <= n - 3;
         const int64_t my_steps = have ? (n - 3 - my_i) / D + 1 : 0;
         // super-steps of this bundle: wave 0 has the most steps, later waves start 3 apart
@@ -236,8 +250,9 @@ __global__ __launch_bounds__(NW * 64) void chase_narrow_kernel(C* __restrict__ b
             }
             for (int ts = 0; ts < GS; ++ts) {
                 const int64_t T = g * GS + ts;
-                const int64_t t = T - 3 * wave;
-                if (have && t >= 0 && t < my_steps) narrow_step<C, D, WC>(win, my_i, t, n);
+                const int64_t t = T - 3 * slot;
+                const bool act = have && t >= 0 && t < my_steps;
+                narrow_step4<C, D, WC>(win, vbuf, (int)my_i, act ? (int)t : 0, act, (int)n);
                 __syncthreads();
             }
             if (want) {
@@ -289,9 +304,10 @@ int run_chase_narrow(int64_t n, C* band, int64_t ldab, int64_t ku, int* ctrl, hi
     constexpr int D = 8;
     constexpr int NW = sizeof(C) == 8 ? 8 : 16;
     constexpr int WC = sizeof(C) == 8 ? 512 : 1024;
+    constexpr int GS = 8;   // super-steps per group (chunk = GS*D columns)
     if (n < 3) return SVB_OK;
-    const size_t smem = sizeof(C) * (size_t)WC * 3 * D;
-    auto kern = chase_narrow_kernel<C, D, NW, WC>;
+    const size_t smem = sizeof(C) * ((size_t)WC * 3 * D + (size_t)(NW / 4) * 4 * D);
+    auto kern = chase_narrow_kernel<C, D, NW, WC, GS>;
     static bool attr_set = false;
     if (!attr_set) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -303,7 +319,7 @@ int run_chase_narrow(int64_t n, C* band, int64_t ldab, int64_t ku, int* ctrl, hi
     hipLaunchKernelGGL(narrow_clear_kernel, dim3(cb > 256 ? 256 : cb), dim3(256), 0, s, ctrl, count);
     const int grid = (int)min((int64_t)env_int("SVB_NARROW_GRID", 128), nbundles);
     const int spin_limit = env_int("SVB_CHASE_SPIN", 1 << 20);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(NW * 64), smem, s, band, ldab, ku, n, ctrl, ctrl + 64, spin_limit);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(NW * 16), smem, s, band, ldab, ku, n, ctrl, ctrl + 64, spin_limit);
     return hipGetLastError() == hipSuccess ? SVB_OK : SVB_ERR_DEVICE;
 }
 
