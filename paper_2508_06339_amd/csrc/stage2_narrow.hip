@@ -8,8 +8,9 @@
 // the hand-over between consecutive sweeps happens.  With one workgroup per sweep every
 // hand-over goes through device memory, and the 3n dependent steps each pay that latency.
 // Here a workgroup owns a BUNDLE of NW consecutive sweeps, four per wave (16 lanes each), and
-// a sliding window of the band in LDS: in super-step T sweep w of the bundle performs its step T - 3w, a
-// workgroup barrier separates super-steps, so the hand-over between the waves of a bundle
+// a sliding window of the band in LDS: a super-step is one HALF step (right or left reflector) of every
+// sweep of the bundle, sweep w running 4w half steps behind sweep 0 (half step h of sweep i+1 needs
+// half step h+3 of sweep i); a workgroup barrier separates super-steps, so the hand-over between the waves of a bundle
 // is an LDS access.  Device memory is touched in chunks of CH = 8*D or 16*D columns: a chunk enters
 // the window two groups (of 8 or 16 super-steps) before it is needed, and leaves it once the last
 // wave has passed.  Bundles are pipelined over workgroups through a ticket counter and a
@@ -33,6 +34,29 @@ template <typename C> __device__ __forceinline__ void ngst(C* p, C v)
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// LDS hand-over inside a wave / between waves without waiting for outstanding global loads
+// (a workgroup-scope fence would also drain vmcnt, i.e. stall on the chunk prefetch):
+// s_waitcnt lgkmcnt(0) only (gfx9 encoding: vmcnt = 63, expcnt = 7, lgkmcnt = 0).
+__device__ __forceinline__ void lds_wave_sync()
+{
+    __builtin_amdgcn_s_waitcnt(0xc07f);
+    __builtin_amdgcn_wave_barrier();
+}
+__device__ __forceinline__ void lds_block_sync()
+{
+    __builtin_amdgcn_s_waitcnt(0xc07f);
+    __builtin_amdgcn_s_barrier();
+}
+
+// Reciprocal with the hardware instruction (1 ulp) plus, for f64, one Newton step: the
+// reflector scalars sit on the serial path of every step.
+__device__ __forceinline__ float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
+__device__ __forceinline__ double fast_rcp(double x)
+{
+    double r = __builtin_amdgcn_rcp(x);
+    return fma(r, fma(-x, r, 1.0), r);
+}
+
 template <typename C>
 __device__ __forceinline__ void nreflector(C alpha, C ss, C& beta, C& tau, C& inv)
 {
@@ -41,16 +65,18 @@ __device__ __forceinline__ void nreflector(C alpha, C ss, C& beta, C& tau, C& in
     } else {
         const C nrm = sqrt(alpha * alpha + ss);
         beta = alpha >= (C)0 ? -nrm : nrm;
-        tau = (beta - alpha) / beta;
-        inv = (C)1 / (alpha - beta);
+        tau = (beta - alpha) * fast_rcp(beta);
+        inv = fast_rcp(alpha - beta);
     }
 }
 
-// One chase step for each of the four sweeps of a wave: lanes 16g .. 16g+15 work on the
-// sweep of group g (its own i, t; act = false if that sweep has no step now).  vbuf holds
-// the reflector of each group (4 x D entries per wave) so that every lane can read all of it.
+// One HALF step (the right reflector of step t if left == false, else its left reflector)
+// for each of the four sweeps of a wave: lanes 16g .. 16g+15 work on the sweep of group g
+// (its own i, t; act = false if that sweep has nothing to do now).  Consecutive sweeps are
+// four half steps apart, so all sweeps of a bundle do the same kind of half step at a time.
+// vbuf holds the pivot row / column of each group so that every lane can form the reflector.
 template <typename C, int D, int WC>
-__device__ __forceinline__ void narrow_step4(C* win, C* vbuf, int i, int t, bool act, int n)
+__device__ __forceinline__ void narrow_half4(C* win, C* vbuf, int i, int t, bool left, bool act, int n)
 {
     constexpr int RS = 3 * D;
     const int lane = threadIdx.x & 63, sub = lane & 15, grp = lane >> 4;
@@ -59,13 +85,17 @@ __device__ __forceinline__ void narrow_step4(C* win, C* vbuf, int i, int t, bool
     const int len = act ? min(D, n - c0) : 0;
     const int r = (t == 0) ? i : c0 - D;
     C* vb = vbuf + grp * D;
-    // ---- right reflector from row r, applied to rows r+1 .. c0+len-1
-    {
-        // the pivot row goes through vb so that every lane can form the reflector itself
+    C a[D];
+    if (!left) {
+        // right reflector from row r, applied to rows r+1 .. c0+len-1 (lane = row)
         const C x = (sub < len) ? WIN(r, c0 + sub) : (C)0;
         if (sub < D) vb[sub] = x;
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+        const int rows = c0 + len - 1 - r;
+        const int q = r + 1 + sub;
+        const bool mine = sub < rows;
+#pragma unroll
+        for (int jj = 0; jj < D; ++jj) a[jj] = (mine && jj < len) ? WIN(q, c0 + jj) : (C)0;
+        lds_wave_sync();
         C v[D];
         C ss = 0;
 #pragma unroll
@@ -76,33 +106,29 @@ __device__ __forceinline__ void narrow_step4(C* win, C* vbuf, int i, int t, bool
         C beta, tau, inv;
         nreflector<C>(v[0], ss, beta, tau, inv);
         v[0] = (C)1;
+        C s = a[0];
 #pragma unroll
-        for (int jj = 1; jj < D; ++jj) v[jj] *= inv;
+        for (int jj = 1; jj < D; ++jj) {
+            v[jj] *= inv;
+            s += v[jj] * a[jj];
+        }
+        s *= tau;
         if (sub < len) WIN(r, c0 + sub) = (sub == 0) ? beta : (C)0;
-        const int rows = c0 + len - 1 - r;
-        if (sub < rows && tau != (C)0) {
-            const int q = r + 1 + sub;
-            C a[D];
-            C s = 0;
-#pragma unroll
-            for (int jj = 0; jj < D; ++jj) {
-                a[jj] = (jj < len) ? WIN(q, c0 + jj) : (C)0;
-                s += v[jj] * a[jj];
-            }
-            s *= tau;
+        if (mine && tau != (C)0) {
 #pragma unroll
             for (int jj = 0; jj < D; ++jj)
                 if (jj < len) WIN(q, c0 + jj) = a[jj] - s * v[jj];
         }
-    }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-    // ---- left reflector from column c0, applied to columns c0+1 .. min(n-1, c0+len-1+D)
-    {
+    } else {
+        // left reflector from column c0, applied to columns c0+1 .. min(n-1, c0+len-1+D) (lane = column)
         const C x = (sub < len) ? WIN(c0 + sub, c0) : (C)0;
         if (sub < D) vb[sub] = x;
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+        const int cols = act ? min(n - 1, c0 + len - 1 + D) - c0 : 0;
+        const int c = c0 + 1 + sub;
+        const bool mine = sub < cols;
+#pragma unroll
+        for (int jj = 0; jj < D; ++jj) a[jj] = (mine && jj < len) ? WIN(c0 + jj, c) : (C)0;
+        lds_wave_sync();
         C v[D];
         C ss = 0;
 #pragma unroll
@@ -113,26 +139,20 @@ __device__ __forceinline__ void narrow_step4(C* win, C* vbuf, int i, int t, bool
         C beta, tau, inv;
         nreflector<C>(v[0], ss, beta, tau, inv);
         v[0] = (C)1;
+        C s = a[0];
 #pragma unroll
-        for (int jj = 1; jj < D; ++jj) v[jj] *= inv;
+        for (int jj = 1; jj < D; ++jj) {
+            v[jj] *= inv;
+            s += v[jj] * a[jj];
+        }
+        s *= tau;
         if (sub < len) WIN(c0 + sub, c0) = (sub == 0) ? beta : (C)0;
-        const int cols = act ? min(n - 1, c0 + len - 1 + D) - c0 : 0;
-        if (sub < cols && tau != (C)0) {
-            const int c = c0 + 1 + sub;
-            C a[D];
-            C s = 0;
-#pragma unroll
-            for (int jj = 0; jj < D; ++jj) {
-                a[jj] = (jj < len) ? WIN(c0 + jj, c) : (C)0;
-                s += v[jj] * a[jj];
-            }
-            s *= tau;
+        if (mine && tau != (C)0) {
 #pragma unroll
             for (int jj = 0; jj < D; ++jj)
                 if (jj < len) WIN(c0 + jj, c) = a[jj] - s * v[jj];
         }
     }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
 #undef WIN
 }
 
@@ -142,7 +162,8 @@ __global__ __launch_bounds__(NW * 16) void chase_narrow_kernel(C* __restrict__ b
                                                                int* __restrict__ flushed, int spin_limit)
 {
     constexpr int NT = NW * 16, RS = 3 * D, CH = GS * D;   // four sweeps per wave
-    constexpr int LAGC = (3 * (NW - 1) + GS - 1) / GS;    // chunks the flush trails the load front by
+    // GS lead steps (2*GS half steps) per group; sweep w runs 4w half steps = 2w steps behind sweep 0
+    constexpr int LAGC = (2 * (NW - 1) + GS - 1) / GS;    // chunks the flush trails the load front by
     constexpr int PER = (CH * RS + NT - 1) / NT;
     static_assert((LAGC + 4) * CH <= WC, "window too small");
     extern __shared__ __align__(16) unsigned char smem_raw[];
@@ -151,6 +172,12 @@ __global__ __launch_bounds__(NW * 16) void chase_narrow_kernel(C* __restrict__ b
     __shared__ int sh_b, sh_fail;
     const int tid = threadIdx.x;
     const int slot = ((tid >> 6) << 2) + ((tid & 63) >> 4);   // which sweep of the bundle this lane works on
+#ifdef SVB_CHASE_TIMING
+    unsigned long long tacc[4] = {0, 0, 0, 0}, tlast = 0, ngrp = 0;
+#define NMARK(slot_) do { if (tid == 0) { unsigned long long now_ = wall_clock64(); tacc[slot_] += now_ - tlast; tlast = now_; } } while (0)
+#else
+#define NMARK(slot_) do { } while (0)
+#endif
     const int64_t nsweeps = n - 2;                         // sweeps 0 .. n-3
     const int64_t nbundles = (nsweeps + NW - 1) / NW;
 
@@ -177,13 +204,13 @@ __global__ __launch_bounds__(NW * 16) void chase_narrow_kernel(C* __restrict__ b
         const int64_t my_i = i0 + slot;
         const bool have = my_i <= n - 3;
         const int64_t my_steps = have ? (n - 3 - my_i) / D + 1 : 0;
-        // super-steps of this bundle: wave 0 has the most steps, later waves start 3 apart
-        int64_t ttot = 0;
+        // half steps of this bundle: sweep 0 has the most steps, later sweeps start 4 half steps apart
+        int64_t htot = 0;
         for (int w = 0; w < NW; ++w) {
             const int64_t iw = i0 + w;
-            if (iw <= n - 3) ttot = max(ttot, (int64_t)3 * w + (n - 3 - iw) / D + 1);
+            if (iw <= n - 3) htot = max(htot, (int64_t)4 * w + 2 * ((n - 3 - iw) / D + 1));
         }
-        const int64_t ngroups = (ttot + GS - 1) / GS;
+        const int64_t ngroups = (htot + 2 * GS - 1) / (2 * GS);
         const int64_t nchunks = (n - i0 + CH - 1) / CH;    // chunks that hold columns < n
 
         // waits until the previous bundle has flushed every column below `upto`
@@ -237,9 +264,13 @@ __global__ __launch_bounds__(NW * 16) void chase_narrow_kernel(C* __restrict__ b
         for (int64_t g = 0; g < ngroups && !failed; ++g) {
             // chunk g+2 is requested now and lands in the window at the end of the group
             C pre[PER];
+#ifdef SVB_CHASE_TIMING
+            if (tid == 0) { tlast = wall_clock64(); ++ngrp; }
+#endif
             const bool want = g + 2 < nchunks;
             if (want) wait_prev(i0 + (g + 3) * CH);
             if (failed) break;
+            NMARK(0);
             if (want) {
 #pragma unroll
                 for (int q = 0; q < PER; ++q) {
@@ -248,13 +279,13 @@ __global__ __launch_bounds__(NW * 16) void chase_narrow_kernel(C* __restrict__ b
                     pre[q] = ok ? ngld(p) : (C)0;
                 }
             }
-            for (int ts = 0; ts < GS; ++ts) {
-                const int64_t T = g * GS + ts;
-                const int64_t t = T - 3 * slot;
-                const bool act = have && t >= 0 && t < my_steps;
-                narrow_step4<C, D, WC>(win, vbuf, (int)my_i, act ? (int)t : 0, act, (int)n);
-                __syncthreads();
+            for (int hs = 0; hs < 2 * GS; ++hs) {
+                const int64_t h = g * 2 * GS + hs - 4 * slot;      // this sweep's half step
+                const bool act = have && h >= 0 && h < 2 * my_steps;
+                narrow_half4<C, D, WC>(win, vbuf, (int)my_i, act ? (int)(h >> 1) : 0, (hs & 1) != 0, act, (int)n);
+                lds_block_sync();
             }
+            NMARK(1);
             if (want) {
                 const int64_t col0 = i0 + (g + 2) * CH;
 #pragma unroll
@@ -263,6 +294,7 @@ __global__ __launch_bounds__(NW * 16) void chase_narrow_kernel(C* __restrict__ b
                     if (e < CH * RS) win[(int)((col0 + e / RS) & (WC - 1)) * RS + e % RS] = pre[q];
                 }
             }
+            NMARK(2);
             const int64_t f = g - LAGC;
             if (f >= 0 && f < nchunks) {
                 flush_chunk(f);
@@ -274,6 +306,7 @@ __global__ __launch_bounds__(NW * 16) void chase_narrow_kernel(C* __restrict__ b
                                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
             __syncthreads();
+            NMARK(3);
         }
         if (!failed) {
             // everything that entered the window and has not been written back yet
@@ -285,6 +318,14 @@ __global__ __launch_bounds__(NW * 16) void chase_narrow_kernel(C* __restrict__ b
         if (tid == 0) __hip_atomic_store(&flushed[b], kAllFlushed, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __syncthreads();
     }
+#ifdef SVB_CHASE_TIMING
+    if (tid == 0) {
+        unsigned long long* acc = reinterpret_cast<unsigned long long*>(ctrl + 8);
+        for (int q = 0; q < 4; ++q) atomicAdd(&acc[q], tacc[q]);
+        atomicAdd(&acc[4], ngrp);
+    }
+#endif
+#undef NMARK
 }
 
 __global__ __launch_bounds__(256) void narrow_clear_kernel(int* __restrict__ p, int64_t count)
@@ -302,7 +343,7 @@ template <typename C>
 int run_chase_narrow(int64_t n, C* band, int64_t ldab, int64_t ku, int* ctrl, hipStream_t s)
 {
     constexpr int D = 8;
-    constexpr int NW = sizeof(C) == 8 ? 8 : 16;
+    constexpr int NW = sizeof(C) == 8 ? 16 : 32;   // sweeps per bundle (four per wave)
     constexpr int WC = sizeof(C) == 8 ? 512 : 1024;
     constexpr int GS = 8;   // super-steps per group (chunk = GS*D columns)
     if (n < 3) return SVB_OK;
