@@ -647,9 +647,10 @@ __global__ __launch_bounds__(NT) void chase_wave_kernel(C* __restrict__ band, in
 template <typename C>
 __global__ __launch_bounds__(256) void extract_bidiag_kernel(const C* __restrict__ band, int64_t ldab,
                                                              int64_t n, int b, C* __restrict__ d,
-                                                             C* __restrict__ e, const int* __restrict__ ctrl)
+                                                             C* __restrict__ e, const int* __restrict__ ctrl,
+                                                             const int* __restrict__ ctrl2)
 {
-    const bool bad = ctrl != nullptr && ctrl[1] != 0;
+    const bool bad = (ctrl != nullptr && ctrl[1] != 0) || (ctrl2 != nullptr && ctrl2[1] != 0);
     const int64_t ku = 2 * (int64_t)b - 1;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
          i += (int64_t)gridDim.x * blockDim.x) {
@@ -691,19 +692,20 @@ int run_chase(int64_t n, int nb, C* band, int64_t ldab, C* d, C* e, void* work,
     int blocks = (int)((n + 255) / 256);
     if (blocks > 1024) blocks = 1024;
     hipLaunchKernelGGL((extract_bidiag_kernel<C>), dim3(blocks), dim3(256), 0, s, band, ldab, n, (int)b, d, e,
-                       pipelined ? ctrl : (const int*)nullptr);
+                       pipelined ? ctrl : (const int*)nullptr, (const int*)nullptr);
     return hipGetLastError() == hipSuccess ? SVB_OK : SVB_ERR_DEVICE;
 }
 
 template <typename C>
-void launch_extract_bidiag(const C* band, int64_t ldab, int64_t n, int b, C* d, C* e, const int* ctrl, hipStream_t s)
+void launch_extract_bidiag(const C* band, int64_t ldab, int64_t n, int b, C* d, C* e, const int* ctrl,
+                           const int* ctrl2, hipStream_t s)
 {
     int blocks = (int)((n + 255) / 256);
     if (blocks > 1024) blocks = 1024;
-    hipLaunchKernelGGL((extract_bidiag_kernel<C>), dim3(blocks), dim3(256), 0, s, band, ldab, n, b, d, e, ctrl);
+    hipLaunchKernelGGL((extract_bidiag_kernel<C>), dim3(blocks), dim3(256), 0, s, band, ldab, n, b, d, e, ctrl, ctrl2);
 }
-template void launch_extract_bidiag<double>(const double*, int64_t, int64_t, int, double*, double*, const int*, hipStream_t);
-template void launch_extract_bidiag<float>(const float*, int64_t, int64_t, int, float*, float*, const int*, hipStream_t);
+template void launch_extract_bidiag<double>(const double*, int64_t, int64_t, int, double*, double*, const int*, const int*, hipStream_t);
+template void launch_extract_bidiag<float>(const float*, int64_t, int64_t, int, float*, float*, const int*, const int*, hipStream_t);
 
 template int run_chase<double>(int64_t, int, double*, int64_t, double*, double*, void*, size_t, hipStream_t);
 template int run_chase<float>(int64_t, int, float*, int64_t, float*, float*, void*, size_t, hipStream_t);

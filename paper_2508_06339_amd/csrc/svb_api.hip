@@ -32,11 +32,43 @@ int check_shape(svb_dtype dt, int64_t m, int64_t n, int nb)
     return SVB_OK;
 }
 
-// scratch of stage 2: whichever of the two chase variants needs more
+// scratch of stage 2: counters of the band reduction (or of the one-phase chase, whichever
+// is larger) followed by those of the narrow chase
+size_t gb2bd_first_bytes(int64_t n, int nb)
+{
+    if (nb == 8) return 0;
+    const size_t a = chase_workspace_bytes(n, nb), b = band_reduce_workspace_bytes(n);
+    return align_up(a > b ? a : b);
+}
 size_t gb2bd_bytes(int64_t n, int nb)
 {
-    const size_t a = nb == 8 ? 0 : chase_workspace_bytes(n, nb), b = chase_narrow_workspace_bytes(n);
-    return (a > b ? a : b);
+    return gb2bd_first_bytes(n, nb) + align_up(chase_narrow_workspace_bytes(n));
+}
+
+// two-phase stage 2 (band -> 8 super-diagonals -> bidiagonal) unless switched off or unsupported
+bool two_phase(int nb, size_t elem_size, int64_t n)
+{
+    return nb != 8 && n >= 3 && env_int("SVB_CHASE_IMPL", 2) == 2 && band_reduce_supported(nb, elem_size);
+}
+
+template <typename C>
+int gb2bd_typed(int64_t n, int nb, C* band, int64_t ldab, C* d, C* e, void* work, size_t work_bytes, hipStream_t s)
+{
+    int* ctrl = static_cast<int*>(work);
+    if (nb == 8) {
+        // narrow band: bundles of sweeps inside LDS windows
+        const int rc = run_chase_narrow<C>(n, band, ldab, 15, ctrl, s);
+        launch_extract_bidiag<C>(band, ldab, n, 8, d, e, ctrl, nullptr, s);
+        return rc;
+    }
+    if (two_phase(nb, sizeof(C), n)) {
+        int* ctrl2 = reinterpret_cast<int*>(static_cast<unsigned char*>(work) + gb2bd_first_bytes(n, nb));
+        int rc = run_band_reduce<C>(n, nb, band, ldab, ctrl, s);
+        if (rc == SVB_OK) rc = run_chase_narrow<C>(n, band, ldab, 2 * (int64_t)nb - 1, ctrl2, s);
+        launch_extract_bidiag<C>(band, ldab, n, nb, d, e, ctrl, ctrl2, s);
+        return rc;
+    }
+    return run_chase<C>(n, nb, band, ldab, d, e, work, work_bytes, s);
 }
 
 // the update kernels move 16-byte vectors along both directions of A
@@ -328,21 +360,10 @@ int svb_gb2bd(svb_dtype band_dt, int64_t n, int nb, void* band_dev, int64_t ldab
     const double cs = band_dt == SVB_F64 ? 8.0 : 4.0;
     prof_begin(SVB_PROF_CHASE, s, 6.0 * (double)n * (double)n * nb, 3.0 * (double)n * (double)n * nb * cs);
     int rc;
-    if (nb == 8) {
-        // narrow band: bundles of sweeps inside LDS windows
-        int* ctrl = static_cast<int*>(work_dev);
-        if (band_dt == SVB_F64) {
-            rc = run_chase_narrow<double>(n, (double*)band_dev, ldab, 15, ctrl, s);
-            launch_extract_bidiag<double>((const double*)band_dev, ldab, n, 8, (double*)d_dev, (double*)e_dev, ctrl, s);
-        } else {
-            rc = run_chase_narrow<float>(n, (float*)band_dev, ldab, 15, ctrl, s);
-            launch_extract_bidiag<float>((const float*)band_dev, ldab, n, 8, (float*)d_dev, (float*)e_dev, ctrl, s);
-        }
-    } else if (band_dt == SVB_F64) {
-        rc = run_chase<double>(n, nb, (double*)band_dev, ldab, (double*)d_dev, (double*)e_dev, work_dev, work_bytes, s);
-    } else {
-        rc = run_chase<float>(n, nb, (float*)band_dev, ldab, (float*)d_dev, (float*)e_dev, work_dev, work_bytes, s);
-    }
+    if (band_dt == SVB_F64)
+        rc = gb2bd_typed<double>(n, nb, (double*)band_dev, ldab, (double*)d_dev, (double*)e_dev, work_dev, work_bytes, s);
+    else
+        rc = gb2bd_typed<float>(n, nb, (float*)band_dev, ldab, (float*)d_dev, (float*)e_dev, work_dev, work_bytes, s);
     prof_end(s);
     return rc;
 }

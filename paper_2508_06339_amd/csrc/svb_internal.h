@@ -78,11 +78,18 @@ int run_chase(int64_t n, int nb, C* band, int64_t ldab, C* d, C* e,
               void* work, size_t work_bytes, hipStream_t s);
 size_t chase_workspace_bytes(int64_t n, int nb);
 template <typename C>
-void launch_extract_bidiag(const C* band, int64_t ldab, int64_t n, int b, C* d, C* e, const int* ctrl, hipStream_t s);
+void launch_extract_bidiag(const C* band, int64_t ldab, int64_t n, int b, C* d, C* e, const int* ctrl,
+                           const int* ctrl2, hipStream_t s);
 // narrow band (8 super-diagonals) -> bidiagonal inside LDS windows; entry (i,j) at band[(i-j+ku) + j*ldab]
 template <typename C>
 int run_chase_narrow(int64_t n, C* band, int64_t ldab, int64_t ku, int* ctrl, hipStream_t s);
 size_t chase_narrow_workspace_bytes(int64_t n);
+// band of nb super-diagonals -> band of 8 (blocked chase, same storage); false / SVB_ERR_UNSUPPORTED
+// where two nb x nb blocks do not fit in LDS
+bool band_reduce_supported(int nb, size_t elem_size);
+template <typename C>
+int run_band_reduce(int64_t n, int nb, C* band, int64_t ldab, int* ctrl, hipStream_t s);
+size_t band_reduce_workspace_bytes(int64_t n);
 
 // ---- stage 3 (host) -----------------------------------------------------------
 int host_bdsvals(int64_t n, const double* d, const double* e, double* sigma);

@@ -120,7 +120,9 @@ def test_stage1_band_preserves_singular_values():
 @pytest.mark.parametrize("dtype,n,nb", [("f64", 200, 32), ("f32", 333, 64), ("f64", 130, 128), ("f32", 700, 128),
                                          ("f64", 1000, 64), ("f64", 3, 32), ("f64", 2, 32),
                                          ("f64", 9, 8), ("f64", 130, 8), ("f32", 1000, 8), ("f64", 1337, 8),
-                                         ("f32", 5000, 8)])
+                                         ("f32", 5000, 8),
+                                         ("f64", 777, 32), ("f32", 2000, 32), ("f32", 1500, 64), ("f64", 64, 64),
+                                         ("f32", 3001, 128), ("f32", 129, 128), ("f64", 41, 32)])
 def test_stage2_on_random_band(dtype, n, nb):
     # random upper band input: Frobenius norm kept, bdsvals(d, e) = oracle(band as dense)
     npdt = workloads.NP_DTYPE[dtype]
@@ -184,6 +186,14 @@ def test_stage2_expired_wait_is_reported(monkeypatch):
     monkeypatch.delenv("SVB_CHASE_SPIN")
     s = _gpu_sigma(a, 32)
     _check(s, oracle.svdvals(a), 256, "f64")
+
+
+@pytest.mark.parametrize("n,nb", [(256, 32), (512, 64)])
+def test_stage2_one_phase_pipelined_variant(monkeypatch, n, nb):
+    # the one-phase pipelined chase (one sweep per workgroup), kept beside the two-phase path
+    monkeypatch.setenv("SVB_CHASE_IMPL", "1")
+    a, info = workloads.make("c1", n=n, nb=nb)
+    _check(_gpu_sigma(a, nb), oracle.svdvals(a), n, "f64")
 
 
 def test_stage2_wavefront_variant(monkeypatch):
