@@ -50,7 +50,13 @@ __device__ __forceinline__ void lds_block_sync()
 
 // Reciprocal with the hardware instruction (1 ulp) plus, for f64, one Newton step: the
 // reflector scalars sit on the serial path of every step.
-__device__ __forceinline__ float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
+__device__ __forceinline__ float fast_rcp(float x)
+{
+    // hardware reciprocal (1 ulp, biased) refined by one Newton step: a biased tau or scale
+    // makes every reflector slightly non-orthogonal in the same direction, which adds up
+    const float r = __builtin_amdgcn_rcpf(x);
+    return fmaf(r, fmaf(-x, r, 1.0f), r);
+}
 __device__ __forceinline__ double fast_rcp(double x)
 {
     double r = __builtin_amdgcn_rcp(x);
@@ -230,7 +236,7 @@ __global__ __launch_bounds__(NW * 16) void chase_narrow_kernel(C* __restrict__ b
                 }
                 __syncthreads();
                 failed = failed || sh_fail != 0;
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+                // no cache invalidate: every band access is a device-scope atomic
             }
         };
         auto load_chunk_direct = [&](int64_t k) {
@@ -299,7 +305,9 @@ __global__ __launch_bounds__(NW * 16) void chase_narrow_kernel(C* __restrict__ b
             if (f >= 0 && f < nchunks) {
                 flush_chunk(f);
                 next_flush = f + 1;
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+                // the stores are device-scope atomics: once acknowledged (vmcnt = 0) they are
+                // visible to every workgroup, no cache write-back is needed
+                __builtin_amdgcn_s_waitcnt(0x0f70);
                 __syncthreads();
                 if (tid == 0)
                     __hip_atomic_store(&flushed[b], (int)min(i0 + (f + 1) * CH, (int64_t)kAllFlushed - 1),

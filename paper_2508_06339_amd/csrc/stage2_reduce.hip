@@ -18,9 +18,10 @@
 // from a ticket counter, a progress counter per sweep, bounded waits (as in stage2_chase.hip).
 //
 // Per step the workgroup holds the upper block U (rows c0-B .., the previous step's A3) and Z
-// stacked in LDS (2B x B); A3 is prefetched into registers at the start of the step and the
-// next step's Z in the middle of it, and they take the place of U and Z once those have been
-// written back, so every block is read once and written once per sweep.
+// stacked in LDS (2B x B); A3 is requested at the start of the step and the next step's Z in
+// the middle of it, and they take the place of U and Z once those have been written back, so
+// every block is read once and written once per sweep.  One wave factors the panels while the
+// others do that traffic.
 //
 // Packed band: entry (i,j) at band[(i - j + ku) + j*ldab], ku = 2B-1, ldab >= 3B.
 #include "svb_internal.h"
@@ -30,6 +31,26 @@ namespace svb {
 namespace {
 
 constexpr int kSweepDone = 0x7fffffff;
+
+// Workgroup barrier that orders LDS traffic only: s_waitcnt lgkmcnt(0) (gfx9 encoding:
+// vmcnt = 63, expcnt = 7, lgkmcnt = 0), then s_barrier.  __syncthreads() would also wait for
+// every outstanding global load and store, i.e. for the block prefetches that are meant to
+// stay in flight across the phases of a step; visibility of global data between workgroups
+// is handled separately (stores_done below, fences at the ends of a sweep).
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_s_waitcnt(0xc07f);
+    __builtin_amdgcn_s_barrier();
+}
+// Every band access of this kernel is a device-scope atomic (written through to, and read
+// from, the level all compute dies share), so publishing a step needs no cache write-back and
+// consuming one no invalidate: the writer only waits until its stores have been acknowledged
+// (s_waitcnt vmcnt(0)) before the barrier that precedes the progress store, and the reader
+// issues its loads after the barrier that follows the progress load.
+__device__ __forceinline__ void stores_done()
+{
+    __builtin_amdgcn_s_waitcnt(0x0f70);
+}
 
 template <typename C> __device__ __forceinline__ C rgld(const C* p)
 {
@@ -76,31 +97,45 @@ __device__ __forceinline__ double lane_value(double v, int lane)
     const int hi = __builtin_amdgcn_readlane((int)(b >> 32), lane);
     return __builtin_bit_cast(double, ((long long)hi << 32) | (long long)(unsigned)lo);
 }
-// lane 15 of the previous row of 16 (CTRL 0x142) / lane 31 (CTRL 0x143) for the rows in ROWS, 0 elsewhere
-template <int CTRL, int ROWS> __device__ __forceinline__ float dpp_bcast(float v)
+constexpr int kDppRor8 = 0x128;       // lane i <-> i^8 inside rows of 16 (rotate by 8)
+
+// Sums of eight per-lane values over the 64 lanes of a wave, as wave-uniform scalars.
+// The first three stages halve the number of values while doubling the lanes summed
+// (each lane keeps the half selected by one of its index bits and hands the other half to
+// its partner: partners i^7 with bit 2, i^1 with bit 0, i^2 with bit 1), so that after them
+// lane i holds, summed over its group of eight lanes, the value with index
+// 4*bit1(i) + 2*bit0(i) + bit2(i); two more stages sum over the row of 16 and over the four rows.
+template <typename C> __device__ __forceinline__ void wave_sum8(const C (&a)[8], C (&out)[8])
 {
-    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROWS, 0xF, false));
-}
-template <int CTRL, int ROWS> __device__ __forceinline__ double dpp_bcast(double v)
-{
-    const long long b = __builtin_bit_cast(long long, v);
-    const int lo = __builtin_amdgcn_update_dpp(0, (int)(b & 0xffffffffll), CTRL, ROWS, 0xF, false);
-    const int hi = __builtin_amdgcn_update_dpp(0, (int)(b >> 32), CTRL, ROWS, 0xF, false);
-    return __builtin_bit_cast(double, ((long long)hi << 32) | (long long)(unsigned)lo);
-}
-// sum over the 64 lanes of a wave as a wave-uniform scalar: rows of 16 first, then row 0 into
-// row 1 and row 2 into row 3, then rows 0+1 into rows 2 and 3; lane 63 holds the total
-template <typename C> __device__ __forceinline__ C wave_sum(C v)
-{
-    v = quad_allsum(v);
-    v += dpp_get<kDppHalfMirror>(v);
-    v += dpp_get<kDppMirror>(v);
-    v += dpp_bcast<0x142, 0xA>(v);
-    v += dpp_bcast<0x143, 0xC>(v);
-    return lane_value(v, 63);
+    const int lane = threadIdx.x & (kWave - 1);
+    const bool b0 = lane & 1, b1 = lane & 2, b2 = lane & 4;
+    C b[4], c[2];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const C keep = b2 ? a[2 * j + 1] : a[2 * j], send = b2 ? a[2 * j] : a[2 * j + 1];
+        b[j] = keep + dpp_get<kDppHalfMirror>(send);
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const C keep = b0 ? b[2 * j + 1] : b[2 * j], send = b0 ? b[2 * j] : b[2 * j + 1];
+        c[j] = keep + dpp_get<kDppXor1>(send);
+    }
+    const C keep = b1 ? c[1] : c[0], send = b1 ? c[0] : c[1];
+    C v = keep + dpp_get<kDppXor2>(send);
+    v += dpp_get<kDppRor8>(v);
+    v += __shfl_xor(v, 16, kWave);
+    v += __shfl_xor(v, 32, kWave);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) out[i] = lane_value(v, ((i >> 1) & 1) + 2 * ((i >> 2) & 1) + 4 * (i & 1));
 }
 
-__device__ __forceinline__ float rrcp(float x) { return __builtin_amdgcn_rcpf(x); }
+__device__ __forceinline__ float rrcp(float x)
+{
+    // hardware reciprocal (1 ulp, biased) refined by one Newton step: a biased tau or scale
+    // makes every reflector slightly non-orthogonal in the same direction, which adds up
+    const float r = __builtin_amdgcn_rcpf(x);
+    return fmaf(r, fmaf(-x, r, 1.0f), r);
+}
 __device__ __forceinline__ double rrcp(double x)
 {
     double r = __builtin_amdgcn_rcp(x);
@@ -139,7 +174,7 @@ template <int D> __device__ __forceinline__ void load_v(const double* v, double 
 // (Vs[vidx(e) + k]) and Ts the D x D upper triangular T of the compact-WY form
 // H_0 H_1 .. H_{D-1} = I - V T V^T, row-major.  One D-vector reduction over the wave per
 // reflector yields its norm, the products with the lines below and the products v_j^T v_k
-// that T needs; the sums are wave-uniform scalars.
+// that T needs; the sums are wave-uniform scalars.  D = 8.
 template <typename C, int B, int D>
 __device__ __forceinline__ void panel_wave(C* P, int sk, int se, C* Vs, C* Ts)
 {
@@ -157,7 +192,7 @@ __device__ __forceinline__ void panel_wave(C* P, int sk, int se, C* Vs, C* Ts)
     C trow[D];
 #pragma unroll
     for (int k = 0; k < D; ++k) {
-        C p[D], colk[D];
+        C part[D], p[D], colk[D];
 #pragma unroll
         for (int j = 0; j < D; ++j) {
             C acc = 0;
@@ -166,9 +201,10 @@ __device__ __forceinline__ void panel_wave(C* P, int sk, int se, C* Vs, C* Ts)
                 const int e = lane + kWave * q;
                 acc += (e > k) ? x[j][q] * x[k][q] : (C)0;
             }
-            p[j] = wave_sum(acc);
+            part[j] = acc;
             colk[j] = lane_value(x[j][0], k);   // element k of every line
         }
+        wave_sum8(part, p);
         const C alpha = colk[k], ss = p[k];
         C beta, inv, tau;
         if (ss == (C)0) {
@@ -269,165 +305,243 @@ __device__ __forceinline__ void apply_line(C* base, int es, bool valid, const C*
     }
 }
 
+// threads of the band reduction kernel: 8*B apply threads (four per line of a 2B-line pass),
+// plus one extra wave for the panels where that still fits in a workgroup.  Blocks are moved
+// by "traffic" waves, each lane keeping one block row: a wave covers 64 consecutive rows of
+// CPG columns at a time and steps through the columns with a fixed stride, so that its
+// addresses are a scalar base, advanced by a scalar per step, plus a fixed lane offset.
+template <int B> struct ReduceShape {
+    static constexpr bool EXTRA = 8 * B + kWave <= 1024;
+    static constexpr int NT = EXTRA ? 8 * B + kWave : 8 * B;
+    static constexpr int NWV = NT / kWave;
+    static constexpr int PWV = EXTRA ? NWV - 1 : 0;               // the panel wave
+    static constexpr int GPC = B >= kWave ? B / kWave : 1;        // 64-row groups per block column
+    static constexpr int CPG = B >= kWave ? 1 : kWave / B;        // block columns per wave access
+    static constexpr int NTW = (NWV - 1) / GPC * GPC;             // waves that move blocks
+    static constexpr int JS = NTW / GPC * CPG;                    // column step of a traffic wave
+    static constexpr int PER = (B + JS - 1) / JS;                 // accesses per traffic wave and block
+};
+
 template <typename C, int B, int D>
-__global__ __launch_bounds__(8 * B) void band_reduce_kernel(C* __restrict__ band, int64_t ldab, int64_t n,
-                                                            int* __restrict__ ctrl, int* __restrict__ progress,
-                                                            int spin_limit)
+__global__ __launch_bounds__(ReduceShape<B>::NT) void band_reduce_kernel(C* __restrict__ band, int64_t ldab, int64_t n,
+                                                                        int* __restrict__ ctrl,
+                                                                        int* __restrict__ progress, int spin_limit)
 {
-    constexpr int NT = 8 * B, LD = 2 * B + 1, PER = B / 8;
+    // The panel wave draws the sweep, waits for the predecessor, factors the two panels of a
+    // step and publishes progress.  The traffic waves move the blocks between device memory
+    // and LDS.  The panel wave's work overlaps the traffic: the right panel of step t with the
+    // write-back of Z of step t-1, the left panel with the write-back of U.
+    using SH = ReduceShape<B>;
+    constexpr int LD = 2 * B + 1, PER = SH::PER, JS = SH::JS;
     extern __shared__ __align__(16) unsigned char smem_raw[];
     C* S = reinterpret_cast<C*>(smem_raw);        // rows c0-B .. c0+B-1, columns c0 .. c0+B-1: S[row + col*LD]
     C* Vs = S + ((B * LD + 3) & ~3);              // (B + 4) * D
     C* Ts = Vs + (B + 4) * D;                     // D * D
     __shared__ int sh_s, sh_fail;
-    const int tid = threadIdx.x;
-    const int ii = tid % B, jj0 = tid / B;        // this thread's row and first column inside a block (column step 8)
-    const int line = (tid >> 6) * 16 + ((tid & 63) >> 2);   // line of the apply phases
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);       // wave-uniform: scalar branches below
+    const bool pw = wv == SH::PWV;
+    const bool lead = tid == SH::PWV * kWave;                      // first lane of the panel wave
+    const int tw = SH::EXTRA ? wv : wv - 1;                        // index among the traffic waves
+    const bool traffic = !pw && tw < SH::NTW;
+    const bool applies = tid < 8 * B;
+    const int line = (tid >> 6) * 16 + (lane >> 2);                // line of the apply phases
+    // this lane's block row and first block column
+    const int ii = (tw % SH::GPC) * kWave + (B >= kWave ? lane : lane % B);
+    const int jj0 = (tw / SH::GPC) * SH::CPG + (B >= kWave ? 0 : lane / B);
+    const int ldm1 = (int)(ldab - 1);
     const int64_t ku = 2 * (int64_t)B - 1;
-#define BAND(r_, c_) band[((r_) - (c_) + ku) + (c_) * ldab]
 #ifdef SVB_CHASE_TIMING
     unsigned long long tacc[8] = {0, 0, 0, 0, 0, 0, 0, 0}, tlast = 0, nstep_acc = 0;
-#define RMARK(slot_) do { if (tid == 0) { unsigned long long now_ = wall_clock64(); tacc[slot_] += now_ - tlast; tlast = now_; } } while (0)
+#define RMARK(slot_) do { if (lead) { unsigned long long now_ = wall_clock64(); tacc[slot_] += now_ - tlast; tlast = now_; } } while (0)
 #else
 #define RMARK(slot_) do { } while (0)
 #endif
     const int64_t nsweeps = (n - 1) / D;
 
-    // Every thread-0-only section is followed by a barrier before the next one (no divergent
+    // A B x B block of the band whose first element is entry (r0, cb): this lane's first
+    // element of it, and the numbers of its rows and columns that lie inside the matrix.
+    struct Blk { C* p; int nrow, ncol; };
+    auto block_at = [&](int64_t r0, int64_t cb) -> Blk {
+        Blk k;
+        k.p = band + ((r0 - cb + ku) + cb * ldab) + (ii + (int64_t)jj0 * ldm1);
+        k.nrow = (int)max((int64_t)0, min((int64_t)B, n - r0));
+        k.ncol = (int)max((int64_t)0, min((int64_t)B, n - cb));
+        return k;
+    };
+    // access q of a block: element (ii, jj0 + q*JS), at k.p + q*JS*ldm1 in the band and at
+    // lds0 + q*JS*LD in LDS; loads of elements outside the matrix read the band's first entry
+    // and are masked where the value is consumed (masking at once would wait for the load)
+    auto inside = [&](const Blk& k, int q) -> bool { return ii < k.nrow && jj0 + q * JS < k.ncol; };
+    auto gload = [&](const Blk& k, int q, bool also) -> C {
+        const C* p = (inside(k, q) && also) ? k.p + (int64_t)(q * JS) * ldm1 : band;
+        return rgld(p);
+    };
+    auto gstore = [&](const Blk& k, int q, C v) { rgst(k.p + (int64_t)(q * JS) * ldm1, v); };
+    // waits (one lane) until sweep s-1 has finished `need` steps; an expired wait sets sh_fail
+    auto wait_for = [&](int64_t s, int need) {
+        if (lead && s > 0) {
+            int spins = 0;
+            while (__hip_atomic_load(&progress[s - 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < need) {
+                if (++spins > spin_limit) {
+                    atomicExch(&ctrl[1], 1);
+                    sh_fail = 1;
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(1);
+            }
+        }
+    };
+
+    // Every single-lane section is followed by a barrier before the next one (no divergent
     // region spans a loop back-edge).
     for (;;) {
-        if (tid == 0) {
+        if (lead) {
             sh_s = atomicAdd(&ctrl[0], 1);
             sh_fail = __hip_atomic_load(&ctrl[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         __syncthreads();
         const int64_t s = sh_s;
-        bool failed = sh_fail != 0;
         __syncthreads();
         if (s >= nsweeps) break;
         const int64_t c00 = (s + 1) * D;
         const int nsteps = (int)((n - 1 - c00) / B) + 1;
+#ifdef SVB_CHASE_TIMING
+        if (lead) tlast = wall_clock64();
+#endif
+        // ---- prologue: the sweep's own D rows and the first diagonal block, straight into LDS
+        wait_for(s, 3);
+        __syncthreads();
+        bool failed = sh_fail != 0;
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        C pre[PER];   // traffic waves: A3 of the step, then Z of the next one
+        if (!failed && traffic) {
+            C u0[PER];
+            const Blk ub = block_at(c00 - B, c00), zb = block_at(c00, c00);
+            const int lds0 = ii + jj0 * LD;
+#pragma unroll
+            for (int q = 0; q < PER; ++q) {
+                u0[q] = gload(ub, q, ii >= B - D);
+                pre[q] = gload(zb, q, true);
+            }
+#pragma unroll
+            for (int q = 0; q < PER; ++q) {
+                if (jj0 + q * JS < B) {
+                    S[lds0 + q * JS * LD] = (inside(ub, q) && ii >= B - D) ? u0[q] : (C)0;
+                    S[B + lds0 + q * JS * LD] = inside(zb, q) ? pre[q] : (C)0;
+                }
+            }
+        }
+        __syncthreads();
+        RMARK(7);
         for (int t = 0; t < nsteps && !failed; ++t) {
             const int64_t c0 = c00 + (int64_t)t * B;
+            const int xoff = (t == 0) ? B - D : 0;
+            // opaque per-step copy: without it every LDS index below is hoisted out of the step
+            // loop and held in (spilled) registers
+            int lds0 = ii + jj0 * LD;
+            asm volatile("" : "+v"(lds0));
 #ifdef SVB_CHASE_TIMING
-            if (tid == 0) { tlast = wall_clock64(); ++nstep_acc; }
+            if (lead) { tlast = wall_clock64(); ++nstep_acc; }
 #endif
-            if (s > 0) {
-                if (tid == 0) {
-                    const int need = t + 3;   // a finished sweep reports kSweepDone
-                    int spins = 0;
-                    while (__hip_atomic_load(&progress[s - 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < need) {
-                        if (++spins > spin_limit) {
-                            atomicExch(&ctrl[1], 1);
-                            sh_fail = 1;
-                            break;
-                        }
-                        __builtin_amdgcn_s_sleep(1);
+            // ---- S1: right panel (LQ of X)  ||  Z of the previous step back, this step's Z in
+            if (pw) {
+                panel_wave<C, B, D>(S + xoff, 1, LD, Vs, Ts);
+            } else if (traffic && t > 0) {
+                // two passes: LDS first (one wait for the prefetch), then all stores back to back
+                // (loads and stores complete out of order with each other, so a store between
+                // two uses of prefetched values would be waited for every time)
+                const Blk zp = block_at(c0 - B, c0 - B), zc = block_at(c0, c0);
+#pragma unroll
+                for (int q = 0; q < PER; ++q) {
+                    if (jj0 + q * JS < B) {
+                        const int li = B + lds0 + q * JS * LD;
+                        const C old = S[li];
+                        S[li] = inside(zc, q) ? pre[q] : (C)0;
+                        pre[q] = old;
                     }
                 }
-                __syncthreads();
-                failed = sh_fail != 0;
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+#pragma unroll
+                for (int q = 0; q < PER; ++q)
+                    if (inside(zp, q)) gstore(zp, q, pre[q]);
+                stores_done();
             }
             RMARK(0);
-            if (!failed) {
-                const int xoff = (t == 0) ? B - D : 0;
-                C pre[PER];   // A3 of this step, then Z of the next one
-                if (t == 0) {
-                    // the sweep's own D rows and the first diagonal block, straight into LDS
-                    C u0[PER], z0[PER];
+            lds_barrier();
+            RMARK(1);
+            // ---- S2: publish the previous step, wait for the predecessor's step t+2
+            if (lead && t > 0) __hip_atomic_store(&progress[s], t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            wait_for(s, t + 3);
+            lds_barrier();
+            failed = sh_fail != 0;
+            RMARK(2);
+            if (failed) break;
+            // ---- S3: A3 requested; block reflector onto the rows below X
+            if (traffic) {
+                const Blk a3 = block_at(c0, c0 + B);
 #pragma unroll
-                    for (int q = 0; q < PER; ++q) {
-                        const int jj = jj0 + 8 * q;
-                        const int64_t col = c0 + jj;
-                        u0[q] = (ii >= B - D && col < n) ? rgld(&BAND(c0 - B + ii, col)) : (C)0;
-                        z0[q] = (c0 + ii < n && col < n) ? rgld(&BAND(c0 + ii, col)) : (C)0;
-                    }
-#pragma unroll
-                    for (int q = 0; q < PER; ++q) {
-                        const int jj = jj0 + 8 * q;
-                        S[ii + jj * LD] = u0[q];
-                        S[B + ii + jj * LD] = z0[q];
-                    }
-                }
-                // A3 of this step: requested now, used after the right half
-#pragma unroll
-                for (int q = 0; q < PER; ++q) {
-                    const int jj = jj0 + 8 * q;
-                    const int64_t col = c0 + B + jj;
-                    pre[q] = (c0 + ii < n && col < n) ? rgld(&BAND(c0 + ii, col)) : (C)0;
-                }
-                __syncthreads();
-                RMARK(1);
-                // ---- right half: LQ of X, block reflector onto the rows below --------------
-                if (tid < kWave) panel_wave<C, B, D>(S + xoff, 1, LD, Vs, Ts);
-                __syncthreads();
-                RMARK(2);
-                {
-                    const int row = xoff + D + line;
-                    apply_line<C, B, D>(S + row, LD, row < 2 * B, Vs, Ts);
-                }
-                __syncthreads();
-                RMARK(3);
-                // U is final for this sweep: write it back, A3 takes its place
-#pragma unroll
-                for (int q = 0; q < PER; ++q) {
-                    const int jj = jj0 + 8 * q;
-                    const int64_t col = c0 + jj;
-                    if (ii >= xoff && col < n) rgst(&BAND(c0 - B + ii, col), S[ii + jj * LD]);
-                    S[ii + jj * LD] = pre[q];
-                }
-                // Z of the next step: requested now, used after the left half
-#pragma unroll
-                for (int q = 0; q < PER; ++q) {
-                    const int jj = jj0 + 8 * q;
-                    const int64_t col = c0 + B + jj;
-                    pre[q] = (c0 + B + ii < n && col < n) ? rgld(&BAND(c0 + B + ii, col)) : (C)0;
-                }
-                __syncthreads();
-                RMARK(4);
-                // ---- left half: QR of Z's first D columns, block reflector onto Z and A3 ------
-                if (tid < kWave) panel_wave<C, B, D>(S + B, LD, 1, Vs, Ts);
-                __syncthreads();
-                RMARK(5);
-                {
-                    const bool valid = line < 2 * B - D;
-                    C* base = (line < B - D) ? S + B + (D + line) * LD : S + (line - (B - D)) * LD;
-                    apply_line<C, B, D>(base, 1, valid, Vs, Ts);
-                }
-                __syncthreads();
-                RMARK(6);
-                // Z is final for this sweep; the next step's Z takes its place
-#pragma unroll
-                for (int q = 0; q < PER; ++q) {
-                    const int jj = jj0 + 8 * q;
-                    const int64_t col = c0 + jj;
-                    if (c0 + ii < n && col < n) rgst(&BAND(c0 + ii, col), S[B + ii + jj * LD]);
-                    S[B + ii + jj * LD] = pre[q];
-                }
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+                for (int q = 0; q < PER; ++q) pre[q] = gload(a3, q, true);
             }
-            __syncthreads();
-            if (tid == 0)
-                __hip_atomic_store(&progress[s], (failed || t == nsteps - 1) ? kSweepDone : t + 1, __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_AGENT);
-            __syncthreads();
-            RMARK(7);
+            if (applies) {
+                const int row = xoff + D + line;
+                apply_line<C, B, D>(S + row, LD, row < 2 * B, Vs, Ts);
+            }
+            lds_barrier();
+            RMARK(3);
+            // ---- S4: left panel (QR of Z's first D columns)  ||  U back, A3 in, next Z requested
+            if (pw) {
+                panel_wave<C, B, D>(S + B, LD, 1, Vs, Ts);
+            } else if (traffic) {
+                const Blk ub = block_at(c0 - B, c0), zn = block_at(c0 + B, c0 + B), a3 = block_at(c0, c0 + B);
+#pragma unroll
+                for (int q = 0; q < PER; ++q) {
+                    if (jj0 + q * JS < B) {
+                        const int li = lds0 + q * JS * LD;
+                        const C old = S[li];
+                        S[li] = inside(a3, q) ? pre[q] : (C)0;
+                        pre[q] = old;
+                    }
+                }
+#pragma unroll
+                for (int q = 0; q < PER; ++q)
+                    if (inside(ub, q) && ii >= xoff) gstore(ub, q, pre[q]);
+#pragma unroll
+                for (int q = 0; q < PER; ++q) pre[q] = gload(zn, q, true);
+            }
+            RMARK(4);
+            lds_barrier();
+            RMARK(5);
+            // ---- S5: block reflector onto the other columns of Z and onto A3
+            if (applies) {
+                const bool valid = line < 2 * B - D;
+                C* base = (line < B - D) ? S + B + (D + line) * LD : S + (line - (B - D)) * LD;
+                apply_line<C, B, D>(base, 1, valid, Vs, Ts);
+            }
+            lds_barrier();
+            RMARK(6);
         }
-        if (failed) {
-            if (tid == 0) __hip_atomic_store(&progress[s], kSweepDone, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        // ---- epilogue: the last step's Z back (nothing is right of it)
+        if (!failed && traffic) {
+            const int64_t c0 = c00 + (int64_t)(nsteps - 1) * B;
+            const Blk zl = block_at(c0, c0);
+            const int lds0 = ii + jj0 * LD;
+#pragma unroll
+            for (int q = 0; q < PER; ++q)
+                if (inside(zl, q)) gstore(zl, q, S[B + lds0 + q * JS * LD]);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
         }
+        __syncthreads();
+        if (lead) __hip_atomic_store(&progress[s], kSweepDone, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __syncthreads();
     }
 #ifdef SVB_CHASE_TIMING
-    if (tid == 0) {
+    if (lead) {
         unsigned long long* acc = reinterpret_cast<unsigned long long*>(ctrl + 8);
         for (int q = 0; q < 8; ++q) atomicAdd(&acc[q], tacc[q]);
         atomicAdd(&acc[8], nstep_acc);
     }
 #endif
 #undef RMARK
-#undef BAND
 }
 
 __global__ __launch_bounds__(256) void reduce_clear_kernel(int* __restrict__ p, int64_t count)
@@ -455,7 +569,7 @@ int launch_band_reduce(int64_t n, C* band, int64_t ldab, int* ctrl, hipStream_t 
     if (nsweeps <= 0) return SVB_OK;
     const int grid = (int)min((int64_t)env_int("SVB_REDUCE_GRID", 256), nsweeps);
     const int spin_limit = env_int("SVB_CHASE_SPIN", 1 << 20);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(8 * B), smem, s, band, ldab, n, ctrl, ctrl + 64, spin_limit);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(ReduceShape<B>::NT), smem, s, band, ldab, n, ctrl, ctrl + 64, spin_limit);
     return hipGetLastError() == hipSuccess ? SVB_OK : SVB_ERR_DEVICE;
 }
 
