@@ -195,7 +195,8 @@ __global__ __launch_bounds__(NT) void panel_qr_kernel(C* __restrict__ P, int64_t
 //   - every thread derives beta, tau and updates its rows (Algorithm 3's
 //     rho / rho' step); columns left of k record v_c^T v_k for the T factor.
 // Two barriers per reflector; the reflector tails stay unscaled in registers
-// (each column remembers its scale) until they are written out.
+// (each column remembers its scale) until they are written out.  Reflectors are
+// processed in blocks of 8 whose pivot rows sit at fixed register positions.
 // Afterwards T is built in LDS from the recorded inner products (the LAPACK
 // larft recurrence, rows in parallel) and written to Tws for the Y = V T product.
 template <typename C, int NB, int RPT, int NT>
@@ -231,68 +232,103 @@ __global__ __launch_bounds__(NT) void panel_qr_reg_kernel(C* __restrict__ P, int
     }
     C my_inv = 0;
 
-    for (int k = 0; k < NB; ++k) {
-        const int buf = k & 1, rgk = k / RPT, kk = k % RPT;
+    // Reflectors are taken KB at a time.  Inside a block the pivot rows are registers
+    // a[0] .. a[KB-1] of the row group that owns them (compile-time indices: a run-time
+    // register index would cost a select per register and reflector); after the block those
+    // KB rows are final, are written out, and the group's registers move down by KB.  The
+    // pivot column is exchanged in register order (xs[row0 + i] belongs to a[i]), so the
+    // moving frame of the pivot group never shows in an LDS index.
+    constexpr int KB = 8;
+    static_assert(RPT % KB == 0 && NB % KB == 0, "block of reflectors must divide the tile");
+    for (int kb = 0; kb < NB / KB; ++kb) {
+        const int rgk = (kb * KB) / RPT;          // row group that owns this block's pivot rows
+#pragma unroll
+        for (int ki = 0; ki < KB; ++ki) {
+            const int k = kb * KB + ki;
+            const int buf = ki & 1;
+            if (rg == rgk) rowk[buf * NB + c] = a[ki];
+            if (c == k) {
+                if (rg == rgk) {
+#pragma unroll
+                    for (int r = 0; r < RPT; ++r) xs[buf * HMAX + row0 + r] = (r > ki) ? a[r] : (C)0;
+                } else if (rg > rgk) {
+#pragma unroll
+                    for (int r = 0; r < RPT; ++r) xs[buf * HMAX + row0 + r] = a[r];
+                }
+            }
+            __syncthreads();
+            const bool below = rg >= rgk;
+            C p = 0;
+            if (below) {
+#pragma unroll
+                for (int r = 0; r < RPT; ++r) p += xs[buf * HMAX + row0 + r] * a[r];
+            }
+            part[rg * NB + c] = p;
+            __syncthreads();
+            C D = 0, ss = 0;
+#pragma unroll
+            for (int q = 0; q < NRG; ++q) {
+                D += part[q * NB + c];
+                ss += part[q * NB + k];
+            }
+            const C alpha = rowk[buf * NB + k], akc = rowk[buf * NB + c];
+            C tau, beta, inv;
+            if (ss == (C)0) {
+                tau = 0; beta = alpha; inv = 0;
+            } else {
+                const C nrm = sqrt(alpha * alpha + ss);
+                beta = alpha >= (C)0 ? -nrm : nrm;
+                tau = (beta - alpha) / beta;
+                inv = (C)1 / (alpha - beta);
+            }
+            const C w = akc + inv * D;   // v_k^T (column c)
+            const C f = tau * w;
+            if (rg == 0) {
+                if (c < k) Gs[c + k * NB] = my_inv * w;   // v_c^T v_k (v_c's tail is stored unscaled)
+                if (c == k) taus[k] = tau;
+            }
+            if (c == k) my_inv = inv;
+            if (rg == rgk) a[ki] = (c > k) ? akc - f : ((c == k) ? beta : akc);
+            if (c > k && below && tau != (C)0) {
+                const C coef = f * inv;
+                // the pivot column was published with zeros at and above the pivot row
+#pragma unroll
+                for (int r = 0; r < RPT; ++r) a[r] -= coef * xs[buf * HMAX + row0 + r];
+            }
+        }
+        // rows kb*KB .. kb*KB+KB-1 are final: R part to the next level, V part (scaled tails,
+        // unit diagonal, zeros above) in place; then the pivot group's registers move down
         if (rg == rgk) {
-            C v = a[0];
 #pragma unroll
-            for (int r = 1; r < RPT; ++r) v = (r == kk) ? a[r] : v;
-            rowk[buf * NB + c] = v;
-        }
-        if (c == k) {
+            for (int i = 0; i < KB; ++i) {
+                const int row = kb * KB + i;
+                if (row < h) {
+                    Pnext[((int64_t)d * NB + row) + (int64_t)c * ldnext] = (row <= c) ? a[i] : (C)0;
+                    Pd[row + (int64_t)c * ldp] = (row > c) ? a[i] * my_inv : ((row == c) ? (C)1 : (C)0);
+                }
+            }
 #pragma unroll
-            for (int r = 0; r < RPT; ++r) xs[buf * HMAX + row0 + r] = (row0 + r > k) ? a[r] : (C)0;
-        }
-        __syncthreads();
-        const bool below = row0 + RPT - 1 > k;
-        C p = 0;
-        if (below) {
+            for (int r = 0; r < RPT - KB; ++r) a[r] = a[r + KB];
 #pragma unroll
-            for (int r = 0; r < RPT; ++r) p += xs[buf * HMAX + row0 + r] * a[r];
-        }
-        part[rg * NB + c] = p;
-        __syncthreads();
-        C D = 0, ss = 0;
-#pragma unroll
-        for (int q = 0; q < NRG; ++q) {
-            D += part[q * NB + c];
-            ss += part[q * NB + k];
-        }
-        const C alpha = rowk[buf * NB + k], akc = rowk[buf * NB + c];
-        C tau, beta, inv;
-        if (ss == (C)0) {
-            tau = 0; beta = alpha; inv = 0;
-        } else {
-            const C nrm = sqrt(alpha * alpha + ss);
-            beta = alpha >= (C)0 ? -nrm : nrm;
-            tau = (beta - alpha) / beta;
-            inv = (C)1 / (alpha - beta);
-        }
-        const C w = akc + inv * D;   // v_k^T (column c)
-        const C f = tau * w;
-        if (rg == 0) {
-            if (c < k) Gs[c + k * NB] = my_inv * w;   // v_c^T v_k (v_c's tail is stored unscaled)
-            if (c == k) taus[k] = tau;
-        }
-        if (c == k) my_inv = inv;
-        if (rg == rgk) {
-            const C nv = (c > k) ? akc - f : ((c == k) ? beta : akc);
-#pragma unroll
-            for (int r = 0; r < RPT; ++r) a[r] = (r == kk) ? nv : a[r];
-        }
-        if (c > k && below && tau != (C)0) {
-            const C coef = f * inv;
-#pragma unroll
-            for (int r = 0; r < RPT; ++r) a[r] -= coef * xs[buf * HMAX + row0 + r];
+            for (int r = RPT - KB; r < RPT; ++r) a[r] = 0;
         }
     }
-    // R -> next level's panel; explicit V (unit diagonal, zeros above, scaled tails) in place
+    // what is left in registers lies below the triangle: explicit V
+    {
+        constexpr int RGL = (NB - 1) / RPT;                 // last pivot group
+        constexpr int LEFT = RPT - (NB - RGL * RPT);        // rows it still holds
+        if (rg == RGL) {
 #pragma unroll
-    for (int r = 0; r < RPT; ++r) {
-        const int row = row0 + r;
-        if (row < h) {
-            if (row < NB) Pnext[((int64_t)d * NB + row) + (int64_t)c * ldnext] = (row <= c) ? a[r] : (C)0;
-            Pd[row + (int64_t)c * ldp] = (row > c) ? a[r] * my_inv : ((row == c) ? (C)1 : (C)0);
+            for (int r = 0; r < LEFT; ++r) {
+                const int row = NB + r;
+                if (row < h) Pd[row + (int64_t)c * ldp] = a[r] * my_inv;
+            }
+        } else if (rg > RGL) {
+#pragma unroll
+            for (int r = 0; r < RPT; ++r) {
+                const int row = row0 + r;
+                if (row < h) Pd[row + (int64_t)c * ldp] = a[r] * my_inv;
+            }
         }
     }
     __syncthreads();
