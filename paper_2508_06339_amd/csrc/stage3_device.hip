@@ -9,7 +9,8 @@
 //   t_1 = -x^2,  D_j = d_j^2 + t_j,  t_{j+1} = -x^2 + e_j^2 * t_j / D_j,
 // the number of negative D_j (the differential stationary qd form of the Sturm
 // sequence: one division per row, n rows).  Squares are taken after scaling by
-// the largest entry, always in fp64.
+// the largest entry, always in fp64.  A first kernel counts at 1024 shared points of
+// [0, bound]; every singular value then starts its bisection from the cell it falls in.
 #include "svb_internal.h"
 
 namespace svb {
@@ -64,51 +65,111 @@ __global__ __launch_bounds__(kPrepThreads) void bd_prep_kernel(const C* __restri
     }
 }
 
-template <typename C>
-__global__ __launch_bounds__(64) void bd_bisect_kernel(const double* __restrict__ ws, int64_t n,
-                                                        C* __restrict__ sigma, double rel_tol)
+constexpr int kGrid = 1024;   // points of the shared first partition of [0, bound]
+
+__device__ __forceinline__ double lane_value(double v, int lane)
 {
-    const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;  // ascending index
-    const double scale = ws[0], hi0 = ws[1];
-    const double* __restrict__ d2 = ws + 8;
-    const double* __restrict__ e2 = d2 + n;
-    if (k >= n) return;
-    if (scale != scale) {  // non-finite input: poison the output, the caller maps it to a status
-        sigma[n - 1 - k] = (C)NAN;
-        return;
-    }
+    const long long b = __builtin_bit_cast(long long, v);
+    const int lo = __builtin_amdgcn_readlane((int)(b & 0xffffffffll), lane);
+    const int hi = __builtin_amdgcn_readlane((int)(b >> 32), lane);
+    return __builtin_bit_cast(double, ((long long)hi << 32) | (long long)(unsigned)lo);
+}
+
+// Number of singular values below x (x2 = x^2, one value per lane) by the recurrence in the
+// header.  All 64 lanes of the wave walk the same rows, so the rows are fetched 64 at a time,
+// one per lane, and handed round as wave-uniform scalars: no memory access sits on the
+// dependent chain of the recurrence.  Rows past n are padded so that they never count.
+__device__ __forceinline__ int64_t sturm_count(const double* __restrict__ d2, const double* __restrict__ e2,
+                                               int64_t n, double x2)
+{
+    const int lane = threadIdx.x & (kWave - 1);
     const double pivmin = 1e-300;
-    double lo = 0.0, hi = hi0;
-    for (int it = 0; it < 200; ++it) {
-        const double mid = 0.5 * (lo + hi);
-        if (!(hi - lo > rel_tol * hi + 1e-38 * hi0) || !(mid > lo && mid < hi)) break;
-        const double x2 = mid * mid;
-        double t = -x2;
-        int64_t cnt = 0;
-        for (int64_t j = 0; j < n; ++j) {
-            double D = d2[j] + t;
+    double t = -x2;
+    int64_t cnt = 0;
+    double dn = lane < n ? d2[lane] : 1e300, en = lane < n ? e2[lane] : 0.0;
+    for (int64_t j0 = 0; j0 < n; j0 += kWave) {
+        const double dj = dn, ej = en;
+        const int64_t jn = j0 + kWave + lane;
+        dn = jn < n ? d2[jn] : 1e300;
+        en = jn < n ? e2[jn] : 0.0;
+#pragma unroll
+        for (int jj = 0; jj < kWave; ++jj) {
+            const double dd = lane_value(dj, jj), ee = lane_value(ej, jj);
+            double D = dd + t;
             if (fabs(D) < pivmin) D = -pivmin;
             cnt += D < 0.0 ? 1 : 0;
             double r = __builtin_amdgcn_rcp(D);      // reciprocal + one Newton step instead of a full division
             r = fma(r, fma(-D, r, 1.0), r);
-            t = e2[j] * (t * r) - x2;
+            t = ee * (t * r) - x2;
         }
-        if (cnt >= k + 1) hi = mid;
-        else lo = mid;
     }
-    sigma[n - 1 - k] = (C)(0.5 * (lo + hi) * scale);
+    return cnt;
+}
+
+// counts at the points x_i = bound * i / kGrid, i = 1 .. kGrid - 1 (x_0 counts 0, x_kGrid counts n)
+__global__ __launch_bounds__(64) void bd_grid_kernel(const double* __restrict__ ws, int64_t n, int* __restrict__ gcnt)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;   // 0 .. kGrid-1, all lanes stay active
+    const double scale = ws[0], hi0 = ws[1];
+    const double* __restrict__ d2 = ws + 8;
+    const double* __restrict__ e2 = d2 + n;
+    int64_t c = 0;
+    if (scale == scale) {
+        const double x = hi0 * ((double)i / kGrid);
+        c = sturm_count(d2, e2, n, x * x);
+    }
+    gcnt[i] = i == 0 ? 0 : (int)min(c, n);
+    if (i == 0) gcnt[kGrid] = (int)n;
+}
+
+template <typename C>
+__global__ __launch_bounds__(64) void bd_bisect_kernel(const double* __restrict__ ws, int64_t n,
+                                                        C* __restrict__ sigma, double rel_tol,
+                                                        const int* __restrict__ gcnt)
+{
+    const int64_t kraw = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;  // ascending index
+    const int64_t k = min(kraw, n - 1);   // surplus lanes repeat the last value: the wave stays whole
+    const double scale = ws[0], hi0 = ws[1];
+    const double* __restrict__ d2 = ws + 8;
+    const double* __restrict__ e2 = d2 + n;
+    if (scale != scale) {  // non-finite input: poison the output, the caller maps it to a status
+        if (kraw < n) sigma[n - 1 - k] = (C)NAN;
+        return;
+    }
+    // first interval from the shared partition: gcnt[a] < k+1 <= gcnt[b] with b = a+1
+    int a = 0, b = kGrid;
+    while (b - a > 1) {
+        const int m = (a + b) >> 1;
+        if (gcnt[m] >= k + 1) b = m;
+        else a = m;
+    }
+    double lo = hi0 * ((double)a / kGrid), hi = b == kGrid ? hi0 : hi0 * ((double)b / kGrid);
+    for (int it = 0; it < 200; ++it) {
+        const double mid = 0.5 * (lo + hi);
+        const bool open = (hi - lo > rel_tol * hi + 1e-38 * hi0) && (mid > lo && mid < hi);
+        if (!__any(open)) break;            // wave-uniform exit: the row hand-over needs every lane
+        const int64_t cnt = sturm_count(d2, e2, n, mid * mid);
+        if (open) {
+            if (cnt >= k + 1) hi = mid;
+            else lo = mid;
+        }
+    }
+    if (kraw < n) sigma[n - 1 - k] = (C)(0.5 * (lo + hi) * scale);
 }
 
 }  // namespace
 
-size_t bdsvals_dev_workspace_bytes(int64_t n) { return (size_t)(8 + 2 * n) * sizeof(double); }
+// doubles: scale, bound, 6 spare, d^2, e^2; then the counts at the partition points
+size_t bdsvals_dev_workspace_bytes(int64_t n) { return (size_t)(8 + 2 * n) * sizeof(double) + (size_t)(kGrid + 8) * sizeof(int); }
 
 template <typename C>
 int run_bdsvals_dev(int64_t n, const C* d, const C* e, C* sigma, void* work, double rel_tol, hipStream_t s)
 {
     double* ws = static_cast<double*>(work);
     hipLaunchKernelGGL((bd_prep_kernel<C>), dim3(1), dim3(kPrepThreads), 0, s, d, e, n, ws);
-    hipLaunchKernelGGL((bd_bisect_kernel<C>), dim3((unsigned)((n + 63) / 64)), dim3(64), 0, s, ws, n, sigma, rel_tol);
+    int* gcnt = reinterpret_cast<int*>(ws + 8 + 2 * n);
+    hipLaunchKernelGGL(bd_grid_kernel, dim3(kGrid / 64), dim3(64), 0, s, ws, n, gcnt);
+    hipLaunchKernelGGL((bd_bisect_kernel<C>), dim3((unsigned)((n + 63) / 64)), dim3(64), 0, s, ws, n, sigma, rel_tol, gcnt);
     return hipGetLastError() == hipSuccess ? SVB_OK : SVB_ERR_DEVICE;
 }
 
