@@ -131,7 +131,7 @@ def main():
         t, st = one_step()
         times.append(t)
         stages.append(st)
-    prof = {k: svb.svb_profile_get(i) for i, k in enumerate(["panel", "k1", "k2", "chase"])}
+    prof = {k: svb.svb_profile_get(i) for i, k in enumerate(["panel", "k1", "k2", "chase", "fused"])}
     svb.svb_profile_enable(False)
 
     total = float(np.sum(times))
@@ -150,7 +150,7 @@ def main():
     check["rel_frobenius_defect"] = abs(float(np.sum(s * s)) - fro2) / fro2
 
     # roofline of the dominant kernel (the one with the largest summed duration)
-    dom = max(("k1", "k2"), key=lambda k: prof[k]["seconds"])
+    dom = max(("k1", "k2", "fused"), key=lambda k: prof[k]["seconds"])
     pk = prof[dom]
     ach = pk["flops"] / pk["seconds"] / 1e12 if pk["seconds"] > 0 else 0.0
     peak = PEAK_TFLOPS[dtype]
@@ -161,9 +161,10 @@ def main():
     tfile = os.path.join(ROOT, "profiles", f"hbm_traffic_{args.config}_{n}_{dtype}_nb{nb}.json")
     if os.path.exists(tfile):
         tr = json.load(open(tfile))
-        rd = sum(v["read_GB"] for k, v in tr.items() if k.startswith(dom + "_mfma"))
-        wr = sum(v["write_GB"] for k, v in tr.items() if k.startswith(dom + "_mfma"))
-        nl = sum(v["launches"] for k, v in tr.items() if k.startswith(dom + "_mfma"))
+        kname = {"k1": "k1_mfma", "k2": "k2_mfma", "fused": "update_fused_kernel"}[dom]
+        rd = sum(v["read_GB"] for k, v in tr.items() if k.startswith(kname))
+        wr = sum(v["write_GB"] for k, v in tr.items() if k.startswith(kname))
+        nl = sum(v["launches"] for k, v in tr.items() if k.startswith(kname))
         if nl:
             roofline["traffic"] = (rd + wr) * 1e9 / nl
             roofline["traffic_unit"] = "HBM bytes per launch (FETCH_SIZE + WRITE_SIZE, calibrated)"
@@ -175,7 +176,7 @@ def main():
             roofline_stage2_traffic = None
     else:
         roofline_stage2_traffic = None
-    upd_s = prof["k1"]["seconds"] + prof["k2"]["seconds"]
+    upd_s = prof["k1"]["seconds"] + prof["k2"]["seconds"] + prof["fused"]["seconds"]
     ch = prof["chase"]
     ch_gbs = ch["bytes"] / ch["seconds"] / 1e9 if ch["seconds"] > 0 else 0.0
     roofline_stage2 = dict(kernel="chase", bound="hbm", achieved=ch_gbs, peak=PEAK_HBM_GBS, unit="GB/s",

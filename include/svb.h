@@ -152,13 +152,15 @@ int svb_last_timings(double* t_stage1, double* t_stage2, double* t_stage3);
  * stream) sums the elapsed times.  Off by default; costs two event records
  * per launch when on.
  *   kind: SVB_PROF_PANEL (gather + domain QR + R scatter), SVB_PROF_K1
- *   (W = Y^T C), SVB_PROF_K2 (C -= V W), SVB_PROF_CHASE (stage 2).
+ *   (W = Y^T C), SVB_PROF_K2 (C -= V W), SVB_PROF_FUSED (both products in one
+ *   pass over the trailing matrix, the default), SVB_PROF_CHASE (stage 2).
  *   seconds / launches / flops / bytes [host] out, any may be NULL: totals
  *   since the last svb_profile_enable(1); flops and bytes are the algorithmic
  *   counts of the launches (2*rows*nb*cols per product; 3*n^2*nb*size for the
  *   chase), not hardware counters.
  */
-enum { SVB_PROF_PANEL = 0, SVB_PROF_K1 = 1, SVB_PROF_K2 = 2, SVB_PROF_CHASE = 3, SVB_PROF_KINDS = 4 };
+enum { SVB_PROF_PANEL = 0, SVB_PROF_K1 = 1, SVB_PROF_K2 = 2, SVB_PROF_CHASE = 3, SVB_PROF_FUSED = 4,
+       SVB_PROF_KINDS = 5 };
 int svb_profile_enable(int on);
 int svb_profile_collect(void);
 int svb_profile_get(int kind, double* seconds, int64_t* launches, double* flops, double* bytes);

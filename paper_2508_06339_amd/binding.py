@@ -152,7 +152,7 @@ def svb_last_timings():
     return tuple(x.value for x in t)
 
 
-SVB_PROF_PANEL, SVB_PROF_K1, SVB_PROF_K2, SVB_PROF_CHASE = 0, 1, 2, 3
+SVB_PROF_PANEL, SVB_PROF_K1, SVB_PROF_K2, SVB_PROF_CHASE, SVB_PROF_FUSED = 0, 1, 2, 3, 4
 
 
 def svb_profile_enable(on: bool) -> int:

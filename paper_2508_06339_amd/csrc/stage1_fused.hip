@@ -1,0 +1,297 @@
+// Stage 1, trailing-matrix update in one pass (paper Section 3.1 Algorithm 1
+// lines 3/6; Section 3.2 "Trailing Submatrix Update", Algorithm 5: the fused
+// TSMQR keeps the tile-row columns a thread owns in registers while it walks
+// down the reflector tiles, so that every matrix entry is read once and
+// written once).
+//
+// Same idea, with the domain's reflectors in compact-WY form (Y = V T) and the
+// products on MFMA: a workgroup owns the block C_d[:, strip] (all rows of one
+// panel domain, 64 columns of the trailing matrix), each of its 4 waves keeps
+// 16 of those columns in accumulator registers for the whole kernel:
+//     W  = Y_d^T C      (contraction over the rows: C's registers are the B operand)
+//     C -= V_d W        (W's registers are the B operand, C's the accumulators)
+// Y_d and V_d stream through LDS in 32-row slices shared by the 4 waves
+// (double buffered, one barrier per slice).  The trailing matrix is read once
+// and written once per tree level; W never leaves the registers.
+//
+// Trailing-matrix element (p, q) lives at Cb[p*sp + q*sq]; p runs along the
+// panel direction.  QR sweep: (sp, sq) = (1, lda); LQ sweep: (lda, 1).
+#include "svb_internal.h"
+#include "mfma_frag.h"
+#include "mfma_gemm.h"
+
+namespace svb {
+
+namespace {
+
+// ---- the four matrix entries a lane holds of one 16 x 16 tile: rows p0 + roff(r, gq), column q
+template <typename T, typename C, bool LQ>
+__device__ __forceinline__ typename Frag<C>::acc_t frag_load(const T* __restrict__ Cb, int64_t lda,
+                                                             int64_t p0, int64_t q, int gq)
+{
+    using F = Frag<C>;
+    typename F::acc_t c;
+    if constexpr (!LQ && F::kContig) {
+        C o[4];
+        VecIO<C, T>::ld(&Cb[(p0 + 4 * gq) + q * lda], o);
+        c[0] = o[0]; c[1] = o[1]; c[2] = o[2]; c[3] = o[3];
+    } else {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int64_t p = p0 + F::roff(r, gq);
+            c[r] = ld_as<C, T>(LQ ? &Cb[p * lda + q] : &Cb[p + q * lda]);
+        }
+    }
+    return c;
+}
+
+template <typename T, typename C, bool LQ>
+__device__ __forceinline__ void frag_store(T* __restrict__ Cb, int64_t lda, int64_t p0, int64_t q, int gq,
+                                           const typename Frag<C>::acc_t& c)
+{
+    using F = Frag<C>;
+    if constexpr (!LQ && F::kContig) {
+        const C o[4] = {c[0], c[1], c[2], c[3]};
+        VecIO<C, T>::st(&Cb[(p0 + 4 * gq) + q * lda], o);
+    } else {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int64_t p = p0 + F::roff(r, gq);
+            st_as<T, C>(LQ ? &Cb[p * lda + q] : &Cb[p + q * lda], c[r]);
+        }
+    }
+}
+
+template <typename C, int NB> struct FusedGeom {
+    static constexpr int RC = 32;                         // rows of Y / V per LDS slice
+    static constexpr int NV = Frag<C>::NV;
+    static constexpr int MT = NB / 16;                    // 16-row tiles of W
+    // row lengths chosen so that the operand fetches (16 lanes on 16 different rows) fall on
+    // different LDS banks
+    static constexpr int LDR = sizeof(C) == 4 ? RC + 4 : RC + 1;   // Y slice: [column][row]
+    static constexpr int LDC = sizeof(C) == 4 ? NB + 4 : NB + 1;   // V slice: [row][column]
+    static constexpr int BUF = NB * LDR > RC * LDC ? NB * LDR : RC * LDC;
+    static constexpr int NLD = RC * NB / NV / 256;        // 16-byte vectors per thread and slice
+    static_assert(NLD >= 1, "slice too small for 256 threads");
+    static constexpr size_t kSmemBytes = 2 * (size_t)BUF * sizeof(C);
+};
+
+}  // namespace
+
+// HT: 16-row tiles a wave holds (HT * 16 = rows of the largest domain).
+// Two workgroups per compute unit (one loads or stores its block while the other computes)
+// wherever the block and W fit in 256 registers per lane.
+template <typename T, typename C, int NB, int HT, bool LQ>
+__global__ __launch_bounds__(256, (sizeof(C) == 8 && NB == 128) ? 1 : 2) void update_fused_kernel(T* __restrict__ Cb, int64_t lda, int64_t qlen,
+                                                           const C* __restrict__ V, const C* __restrict__ Y,
+                                                           int64_t ldp, int chunks, int g, int64_t stride,
+                                                           int strips, int total)
+{
+    using F = Frag<C>;
+    using G = FusedGeom<C, NB>;
+    typedef typename F::acc_t acc_t;
+    constexpr int RC = G::RC, NV = G::NV, MT = G::MT, LDR = G::LDR, LDC = G::LDC, BUF = G::BUF, NLD = G::NLD;
+    constexpr int NCK = HT * 16 / RC;   // slices per product for a full domain
+    constexpr int VPC = RC / NV;        // vectors per slice column
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    C* smem = reinterpret_cast<C*>(smem_raw);
+
+    // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2): give every
+    // XCD a contiguous range of tiles, so that the workgroups sharing a domain's V and Y
+    // mostly share an L2 as well.
+    const int per = (total + 7) / 8;
+    const int tile = (int)(blockIdx.x % 8) * per + (int)(blockIdx.x / 8);
+    if (tile >= total) return;
+    const int d = tile / strips, strip = tile % strips;
+
+    const int nch = min(g, chunks - d * g);
+    const int ntile = nch * NB / 16;   // 16-row tiles of this domain
+    const int nck = nch * NB / RC;     // slices of this domain
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int i = lane & 15, gq = lane >> 4;
+    const int64_t q = (int64_t)strip * 64 + wave * 16 + i;
+    const bool active = (int64_t)strip * 64 + wave * 16 < qlen;   // qlen is a multiple of 16
+    const int64_t prow0 = (int64_t)d * g * NB;                    // first row of the domain in V / Y
+
+    // global p index of tile t: chunk (16t / NB) of the domain, offset (16t % NB) inside it
+    auto tile_p = [&](int t) -> int64_t {
+        return ((int64_t)d * g + (16 * t) / NB) * stride + (16 * t) % NB;
+    };
+
+    acc_t c[HT];
+#pragma unroll
+    for (int t = 0; t < HT; ++t) {
+        if (active && t < ntile) c[t] = frag_load<T, C, LQ>(Cb, lda, tile_p(t), q, gq);
+        else
+#pragma unroll
+            for (int r = 0; r < 4; ++r) c[t][r] = 0;
+    }
+    acc_t w[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) w[mt][r] = 0;
+
+    // ---- slices of Y and V: global -> registers -> LDS
+    C sreg[NLD][NV];
+    auto slice_ld = [&](const C* __restrict__ src, int ck) {
+#pragma unroll
+        for (int e = 0; e < NLD; ++e) {
+            const int idx = tid + e * 256;
+            const int rv = idx % VPC, col = idx / VPC;
+            VecIO<C, C>::ld(&src[(prow0 + (int64_t)ck * RC + rv * NV) + (int64_t)col * ldp], sreg[e]);
+        }
+    };
+    auto slice_st_y = [&](C* buf) {   // [column][row]
+#pragma unroll
+        for (int e = 0; e < NLD; ++e) {
+            const int idx = tid + e * 256;
+            const int rv = idx % VPC, col = idx / VPC;
+            if constexpr (sizeof(C) == 4) {
+                VecIO<C, C>::st(&buf[col * LDR + rv * NV], sreg[e]);
+            } else {
+#pragma unroll
+                for (int j = 0; j < NV; ++j) buf[col * LDR + rv * NV + j] = sreg[e][j];
+            }
+        }
+    };
+    auto slice_st_v = [&](C* buf) {   // [row][column]
+#pragma unroll
+        for (int e = 0; e < NLD; ++e) {
+            const int idx = tid + e * 256;
+            const int rv = idx % VPC, col = idx / VPC;
+#pragma unroll
+            for (int j = 0; j < NV; ++j) buf[(rv * NV + j) * LDC + col] = sreg[e][j];
+        }
+    };
+
+    int cur = 0;
+    slice_ld(Y, 0);
+    slice_st_y(smem);
+    __syncthreads();
+#pragma unroll
+    for (int s = 0; s < 2 * NCK; ++s) {
+        const bool isV = s >= NCK;
+        const int ck = isV ? s - NCK : s;
+        if (ck < nck) {
+            const bool last = ck + 1 == nck;
+            const bool have_next = !(isV && last);
+            const bool nextV = isV || last;
+            if (have_next) slice_ld(nextV ? V : Y, last ? 0 : ck + 1);
+            const C* buf = smem + cur * BUF;
+            if (active) {
+                if (!isV) {
+                    // W += Y_slice^T C_slice
+#pragma unroll
+                    for (int tt = 0; tt < RC / 16; ++tt) {
+                        const int t = ck * (RC / 16) + tt;
+                        // four tiles of W at a time: consecutive MFMAs are independent
+                        constexpr int MG = MT < 4 ? MT : 4;
+#pragma unroll
+                        for (int m0 = 0; m0 < MT; m0 += MG) {
+                            C a[MG][4];
+#pragma unroll
+                            for (int m = 0; m < MG; ++m) F::ld4(&buf[(16 * (m0 + m) + i) * LDR + 16 * tt], gq, a[m]);
+#pragma unroll
+                            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                                for (int m = 0; m < MG; ++m) w[m0 + m] = F::mma(a[m][r], c[t][r], w[m0 + m]);
+                        }
+                    }
+                    if (last) {
+#pragma unroll
+                        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) w[mt][r] = -w[mt][r];
+                    }
+                } else {
+                    // C_slice += V_slice (-W)
+                    static_assert(RC / 16 == 2, "two tiles per slice");
+                    const int t0 = ck * 2, t1 = ck * 2 + 1;
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt) {
+                        C a0[4], a1[4];
+                        F::ld4(&buf[i * LDC + 16 * mt], gq, a0);
+                        F::ld4(&buf[(16 + i) * LDC + 16 * mt], gq, a1);
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            c[t0] = F::mma(a0[r], w[mt][r], c[t0]);
+                            c[t1] = F::mma(a1[r], w[mt][r], c[t1]);
+                        }
+                    }
+                }
+            }
+            if (have_next) {
+                C* nbuf = smem + (cur ^ 1) * BUF;
+                if (nextV) slice_st_v(nbuf);
+                else slice_st_y(nbuf);
+            }
+            __syncthreads();
+            cur ^= 1;
+        }
+    }
+
+    if (active) {
+#pragma unroll
+        for (int t = 0; t < HT; ++t)
+            if (t < ntile) frag_store<T, C, LQ>(Cb, lda, tile_p(t), q, gq, c[t]);
+    }
+}
+
+template <typename T, typename C, int NB, int HT, bool LQ>
+static void launch_fused(T* Cb, int64_t lda, int64_t qlen, const C* V, const C* Y, int64_t ldp, int chunks,
+                         int g, int64_t stride, bool credited, hipStream_t s)
+{
+    using G = FusedGeom<C, NB>;
+    auto kern = update_fused_kernel<T, C, NB, HT, LQ>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  (int)G::kSmemBytes);
+        attr_set = true;
+    }
+    const int domains = (chunks + g - 1) / g;
+    const int strips = (int)((qlen + 63) / 64);
+    const int total = domains * strips;
+    const int per = (total + 7) / 8;
+    // both products: 2 * rows * NB * cols flops each; the block is read once and written once
+    const double fl = credited ? 4.0 * chunks * NB * (double)NB * (double)qlen : 0.0;
+    const double by = credited ? 2.0 * chunks * NB * (double)qlen * sizeof(T) : 0.0;
+    prof_begin(SVB_PROF_FUSED, s, fl, by);
+    hipLaunchKernelGGL(kern, dim3((unsigned)(per * 8)), dim3(256), G::kSmemBytes, s, Cb, lda, qlen, V, Y, ldp,
+                       chunks, g, stride, strips, total);
+    prof_end(s);
+}
+
+template <typename C> constexpr int fused_tiles() { return sizeof(C) == 4 ? 32 : 16; }
+
+// rows of the largest domain the one-pass kernel holds in registers
+template <typename C> int fused_update_rows() { return fused_tiles<C>() * 16; }
+template int fused_update_rows<float>();
+template int fused_update_rows<double>();
+
+template <typename T, typename C>
+void launch_update_fused(int nb, bool lq, T* Cb, int64_t lda, int64_t qlen, const C* V, const C* Y,
+                         int64_t ldp, int chunks, int g, int64_t stride, bool credited, hipStream_t s)
+{
+    if (qlen <= 0) return;
+    constexpr int HT = fused_tiles<C>();
+#define SVB_FUSED_CASE(NBV)                                                                                   \
+    case NBV:                                                                                                 \
+        if (lq) launch_fused<T, C, NBV, HT, true>(Cb, lda, qlen, V, Y, ldp, chunks, g, stride, credited, s);  \
+        else launch_fused<T, C, NBV, HT, false>(Cb, lda, qlen, V, Y, ldp, chunks, g, stride, credited, s);    \
+        break;
+    switch (nb) {
+        SVB_FUSED_CASE(32)
+        SVB_FUSED_CASE(64)
+        SVB_FUSED_CASE(128)
+    default: break;
+    }
+#undef SVB_FUSED_CASE
+}
+
+template void launch_update_fused<float, float>(int, bool, float*, int64_t, int64_t, const float*, const float*, int64_t, int, int, int64_t, bool, hipStream_t);
+template void launch_update_fused<__half, float>(int, bool, __half*, int64_t, int64_t, const float*, const float*, int64_t, int, int, int64_t, bool, hipStream_t);
+template void launch_update_fused<double, double>(int, bool, double*, int64_t, int64_t, const double*, const double*, int64_t, int, int, int64_t, bool, hipStream_t);
+
+}  // namespace svb

@@ -228,8 +228,11 @@ int ge2gb_impl(int64_t n, T* A, int64_t lda, int nb, C* band, int64_t ldab, unsi
 {
     int* err = reinterpret_cast<int*>(work + cv.off_err);
     const int g = domain_chunks(sizeof(C) == 8 ? SVB_F64 : SVB_F32, nb);
-    const int impl = env_int("SVB_UPDATE_IMPL", 1);
-    const bool la = impl != 0 && env_int("SVB_LOOKAHEAD", 1) != 0 && g_la.init();
+    // update: 2 = one pass over the trailing matrix per tree level (default, when the domain fits
+    // the kernel's registers), 1 = two MFMA kernels with look-ahead, 0 = plain FMA kernels
+    int impl = env_int("SVB_UPDATE_IMPL", 2);
+    if (impl == 2 && g * nb > fused_update_rows<C>()) impl = 1;
+    const bool la = impl == 1 && env_int("SVB_LOOKAHEAD", 1) != 0 && g_la.init();
     const int64_t N = n / nb;
     Level lv[kMaxLevels];
     int64_t woff[kMaxLevels];
@@ -281,6 +284,11 @@ int ge2gb_impl(int64_t n, T* A, int64_t lda, int nb, C* band, int64_t ldab, unsi
                     any_rest = any_rest || lv[L].chunks > lv[L].domains;
                 }
                 const bool defer = la && any_rest;
+                if (impl == 2) {
+                    for (int L = 0; L < nl; ++L)
+                        launch_update_fused<T, C>(nb, lq, Cb, lda, qlen, Vb + lv[L].poff, Yb + lv[L].poff,
+                                                  lv[L].ldp, lv[L].chunks, g, lv[L].stride, L == 0, s);
+                } else
                 for (int L = 0; L < nl; ++L)
                     launch_update<T, C>(nb, lq, Cb, lda, qlen, Vb + lv[L].poff, Yb + lv[L].poff, lv[L].ldp,
                                         lv[L].chunks, g, lv[L].stride, Wb + woff[L], impl, L == 0, defer ? 1 : 0, s);
