@@ -24,44 +24,6 @@ namespace svb {
 
 namespace {
 
-// ---- the four matrix entries a lane holds of one 16 x 16 tile: rows p0 + roff(r, gq), column q
-template <typename T, typename C, bool LQ>
-__device__ __forceinline__ typename Frag<C>::acc_t frag_load(const T* __restrict__ Cb, int64_t lda,
-                                                             int64_t p0, int64_t q, int gq)
-{
-    using F = Frag<C>;
-    typename F::acc_t c;
-    if constexpr (!LQ && F::kContig) {
-        C o[4];
-        VecIO<C, T>::ld(&Cb[(p0 + 4 * gq) + q * lda], o);
-        c[0] = o[0]; c[1] = o[1]; c[2] = o[2]; c[3] = o[3];
-    } else {
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int64_t p = p0 + F::roff(r, gq);
-            c[r] = ld_as<C, T>(LQ ? &Cb[p * lda + q] : &Cb[p + q * lda]);
-        }
-    }
-    return c;
-}
-
-template <typename T, typename C, bool LQ>
-__device__ __forceinline__ void frag_store(T* __restrict__ Cb, int64_t lda, int64_t p0, int64_t q, int gq,
-                                           const typename Frag<C>::acc_t& c)
-{
-    using F = Frag<C>;
-    if constexpr (!LQ && F::kContig) {
-        const C o[4] = {c[0], c[1], c[2], c[3]};
-        VecIO<C, T>::st(&Cb[(p0 + 4 * gq) + q * lda], o);
-    } else {
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int64_t p = p0 + F::roff(r, gq);
-            st_as<T, C>(LQ ? &Cb[p * lda + q] : &Cb[p + q * lda], c[r]);
-        }
-    }
-}
-
 template <typename C, int NB> struct FusedGeom {
     static constexpr int RC = 32;                         // rows of Y / V per LDS slice
     static constexpr int NV = Frag<C>::NV;

@@ -438,11 +438,14 @@ template <typename C>
 void launch_panel_qr(int nb, C* P, int64_t ldp, C* Y, C* Tws, int chunks, int g,
                      C* Pnext, int64_t ldnext, int* /*err*/, hipStream_t s)
 {
-    static const int impl = env_int("SVB_PANEL_IMPL", 1);
-    // register-resident kernel + MFMA Y product when the domain fits (and 128-row Y tiles
-    // never straddle two domains); otherwise the plain kernel below
-    if (impl != 0 && panel_reg_rows<C>(nb) >= g * nb && (g * nb) % 128 == 0) {
-        PanelRegDispatch<C>::run(nb, P, ldp, Tws, chunks, g, Pnext, ldnext, s);
+    static const int impl = env_int("SVB_PANEL_IMPL", 2);
+    // blocked register-resident kernel (2, default) or the reflector-at-a-time register kernel (1),
+    // each followed by the MFMA Y product, when the domain fits (and 128-row Y tiles never
+    // straddle two domains); otherwise the plain kernel below
+    const bool blk = impl == 2 && panel_blk_rows<C>() >= g * nb;
+    if ((blk || (impl != 0 && panel_reg_rows<C>(nb) >= g * nb)) && (g * nb) % 128 == 0) {
+        if (blk) launch_panel_blk<C>(nb, P, ldp, Tws, chunks, g, Pnext, ldnext, s);
+        else PanelRegDispatch<C>::run(nb, P, ldp, Tws, chunks, g, Pnext, ldnext, s);
         const int64_t rows = (int64_t)chunks * nb;
         if (nb == 32) launch_panel_y<C, 32>(P, Y, Tws, ldp, rows, g, s);
         else if (nb == 64) launch_panel_y<C, 64>(P, Y, Tws, ldp, rows, g, s);

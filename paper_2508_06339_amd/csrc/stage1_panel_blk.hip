@@ -1,0 +1,380 @@
+// Stage 1, panel factorisation of one domain, blocked (paper Section 3.2
+// "Panel Factorization", Algorithm 3; Section 3.1 Algorithm 1 lines 2/4).
+//
+// The paper's GEQRT/TSQRT keep the tile in registers and apply every reflector
+// to every column with scalar FMAs.  Here the domain (H = 16*HT rows, NB
+// columns) also lives in registers, but in MFMA accumulator layout: wave w
+// holds columns 16w .. 16w+15.  The columns are factored 16 at a time:
+//   1. the owning wave hands its 16 columns to LDS;
+//   2. all threads factor that 16-column block with Householder reflectors
+//      (Algorithm 3's loop, the column split over row groups, two barriers per
+//      reflector) -- the only part that works reflector by reflector;
+//   3. the block's reflectors are applied to the columns right of it as ONE
+//      block reflector on MFMA:  C_w -= V_b (T_b^T (V_b^T C_w));
+//   4. the waves left of the block (whose registers now hold their own V)
+//      form V_w^T V_b the same way, from which the domain's compact-WY factor
+//      T grows by one block column:  T[0:b, b] = -T[0:b, 0:b] (V^T V_b) T_b.
+// Outputs as for the other panel kernels: V explicit in place, R into the next
+// level's panel, T for the Y = V T product.
+//
+// Reflector convention: H = I - tau v v^T, v_k = 1, beta = -sign(alpha)*norm,
+// tau = (beta - alpha)/beta (Algorithm 3's 2x^2/(x^2+|tail|^2)); a zero tail
+// gives tau = 0 instead of the paper's 10*eps rule.
+#include "svb_internal.h"
+#include "mfma_frag.h"
+
+namespace svb {
+
+namespace {
+
+template <typename C, int NB, int HT> struct PanelBlkGeom {
+    static constexpr int NW = NB / 16, NT = NW * 64, H = HT * 16;
+    static constexpr int RPT = (H / (4 * NW)) < 16 ? 16 : H / (4 * NW);   // rows per thread in step 2
+    static constexpr int NRGU = H / RPT;                                  // row groups in use
+    static constexpr int PAD = sizeof(C) == 4 ? 4 : 1;   // keeps 16 lanes on 16 rows off each other's banks
+    static constexpr int LDB = H + PAD;                  // block columns: [column][row]
+    static constexpr int LDT = 16 + PAD;                 // 16 x 16 blocks
+    static constexpr int LDZ = NB + PAD;
+    static constexpr int NBLK = NW * (NW + 1) / 2;       // blocks of the upper block triangle of T
+    // LDS carve, in elements
+    static constexpr int oBs = 0;
+    static constexpr int oTs = oBs + 16 * LDB;           // T, block (bi, bj) row-major at blk(bi, bj) * 16 * LDT
+    static constexpr int oZs = oTs + NBLK * 16 * LDT;    // Z = (V_w^T V_b) T_b, [column][row]
+    static constexpr int oXs = oZs + 16 * LDZ;           // pivot column, two buffers
+    static constexpr int oPart = oXs + 2 * H;            // partial inner products, [wave][column]
+    static constexpr int oRowk = oPart + NW * 16;        // pivot row, two buffers
+    static constexpr int oGs = oRowk + 2 * 16;           // v_c^T v_k inside the block
+    static constexpr int oRs = oGs + 16 * 16;            // R block, [column][row]
+    static constexpr int oTb = oRs + 16 * LDT;           // T_b, [column][row]
+    static constexpr int oTl = oTb + 16 * LDT;           // T_b, [row][column]
+    static constexpr int oTau = oTl + 16 * LDT;
+    static constexpr int kElems = oTau + 16;
+    static constexpr size_t kSmemBytes = (size_t)kElems * sizeof(C);
+    static_assert(RPT % 4 == 0 && NRGU <= 4 * NW, "row split");
+    static_assert(kSmemBytes <= 160 * 1024, "LDS");
+};
+
+__device__ __forceinline__ int tblk(int bi, int bj) { return bj * (bj + 1) / 2 + bi; }
+
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+}  // namespace
+
+template <typename C, int NB, int HT>
+__global__ __launch_bounds__(NB * 4) void panel_qr_blk_kernel(C* __restrict__ P, int64_t ldp,
+                                                              C* __restrict__ Tws, int chunks, int g,
+                                                              C* __restrict__ Pnext, int64_t ldnext)
+{
+    using F = Frag<C>;
+    using G = PanelBlkGeom<C, NB, HT>;
+    typedef typename F::acc_t acc_t;
+    constexpr int NW = G::NW, NT = G::NT, H = G::H, RPT = G::RPT, NRGU = G::NRGU;
+    constexpr int LDB = G::LDB, LDT = G::LDT, LDZ = G::LDZ;
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    C* sm = reinterpret_cast<C*>(smem_raw);
+    C* Bs = sm + G::oBs;
+    C* Ts = sm + G::oTs;
+    C* Zs = sm + G::oZs;
+    C* xs = sm + G::oXs;
+    C* part = sm + G::oPart;
+    C* rowk = sm + G::oRowk;
+    C* Gs = sm + G::oGs;
+    C* Rs = sm + G::oRs;
+    C* Tb = sm + G::oTb;
+    C* Tl = sm + G::oTl;
+    C* taus = sm + G::oTau;
+
+    const int d = blockIdx.x;
+    const int nch = min(g, chunks - d * g);
+    const int ntile = nch * NB / 16;              // 16-row tiles that exist (the rest reads as zero)
+    C* Pd = P + (int64_t)d * g * NB;
+    C* Td = Tws + (int64_t)d * NB * NB;
+    C* Rd = Pnext + (int64_t)d * NB;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int i = lane & 15, gq = lane >> 4;      // MFMA fragment coordinates
+    const int pc = tid & 15, prg = tid >> 4;      // step 2: column of the block, row group
+    const int64_t mycol = 16 * wave + i;
+
+    acc_t c[HT];
+#pragma unroll
+    for (int t = 0; t < HT; ++t) {
+        if (t < ntile) c[t] = frag_load<C, C, false>(Pd, ldp, 16 * t, mycol, gq);
+        else
+#pragma unroll
+            for (int r = 0; r < 4; ++r) c[t][r] = 0;
+    }
+    for (int idx = tid; idx < G::NBLK * 16 * LDT; idx += NT) Ts[idx] = 0;
+
+    for (int b = 0; b < NW; ++b) {
+        // ---- 1. the owner's columns (rows 16b ..) to LDS
+        if (wave == b) {
+#pragma unroll
+            for (int t = 0; t < HT; ++t)
+                if (t >= b) {
+                    const C o[4] = {c[t][0], c[t][1], c[t][2], c[t][3]};
+                    F::st4(&Bs[i * LDB + 16 * t], gq, o);
+                }
+        }
+        __syncthreads();
+
+        // ---- 2. Householder QR of the block: thread (pc, prg) holds rows 16b + prg*RPT + r of column pc
+        const int rbase = 16 * b + prg * RPT;
+        const bool rows_on = prg < NRGU;
+        C a[RPT];
+#pragma unroll
+        for (int r = 0; r < RPT; ++r) a[r] = (rows_on && rbase + r < H) ? Bs[pc * LDB + rbase + r] : (C)0;
+        C my_inv = 0;
+#pragma unroll
+        for (int ki = 0; ki < 16; ++ki) {
+            const int buf = ki & 1;
+            if (prg == 0) rowk[buf * 16 + pc] = a[ki];
+            if (pc == ki && rows_on) {
+#pragma unroll
+                for (int r = 0; r < RPT; ++r) xs[buf * H + prg * RPT + r] = (prg == 0 && r <= ki) ? (C)0 : a[r];
+            }
+            __syncthreads();
+            C x[RPT];
+            C p = 0;
+            if (rows_on) {
+#pragma unroll
+                for (int r = 0; r < RPT; ++r) {
+                    x[r] = xs[buf * H + prg * RPT + r];
+                    p += x[r] * a[r];
+                }
+            } else {
+#pragma unroll
+                for (int r = 0; r < RPT; ++r) x[r] = 0;
+            }
+            p += __shfl_xor(p, 16, kWave);
+            p += __shfl_xor(p, 32, kWave);
+            if (lane < 16) part[wave * 16 + pc] = p;
+            __syncthreads();
+            C D = 0, ss = 0;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) {
+                D += part[w * 16 + pc];
+                ss += part[w * 16 + ki];
+            }
+            const C alpha = rowk[buf * 16 + ki], akc = rowk[buf * 16 + pc];
+            C tau, beta, inv;
+            if (ss == (C)0) {
+                tau = 0; beta = alpha; inv = 0;
+            } else {
+                const C nrm = sqrt(alpha * alpha + ss);
+                beta = alpha >= (C)0 ? -nrm : nrm;
+                tau = (beta - alpha) / beta;
+                inv = (C)1 / (alpha - beta);
+            }
+            const C wk = akc + inv * D;   // v_k^T (column pc), v_k's tail taken unscaled times inv
+            const C f = tau * wk;
+            if (prg == 0) {
+                if (pc < ki) Gs[pc * 16 + ki] = my_inv * wk;   // v_pc^T v_k (v_pc's tail is stored unscaled)
+                if (pc == ki) taus[ki] = tau;
+            }
+            if (pc == ki) my_inv = inv;
+            if (prg == 0) a[ki] = (pc > ki) ? akc - f : ((pc == ki) ? beta : akc);
+            if (pc > ki && tau != (C)0) {
+                const C coef = f * inv;
+#pragma unroll
+                for (int r = 0; r < RPT; ++r) a[r] -= coef * x[r];   // x is zero at and above the pivot row
+            }
+        }
+        // explicit V block (unit diagonal, zeros above) back to LDS; R block aside
+        if (rows_on) {
+#pragma unroll
+            for (int r = 0; r < RPT; ++r) {
+                const int rel = prg * RPT + r;
+                if (rbase + r < H) {
+                    C v = a[r] * my_inv;
+                    if (rel < 16) v = rel < pc ? (C)0 : (rel == pc ? (C)1 : v);
+                    Bs[pc * LDB + rbase + r] = v;
+                }
+            }
+        }
+        if (prg == 0) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) Rs[pc * LDT + r] = (r <= pc) ? a[r] : (C)0;
+        }
+        __syncthreads();
+
+        // ---- 3./4. first product with V_b (every wave but the owner); the owner builds T_b
+        acc_t p1;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) p1[r] = 0;
+        if (wave == b) {
+            // T_b: T[k][k] = tau_k, T[i][k] = -tau_k sum_{j=i}^{k-1} T[i][j] (v_j^T v_k); lane (row ti, 4 lanes per row)
+            const int ti = i, ts = gq;
+            for (int j = ts; j < 16; j += 4) Tl[ti * LDT + j] = (j == ti) ? taus[ti] : (C)0;
+            wave_lds_sync();
+            for (int k = 1; k < 16; ++k) {
+                C acc = 0;
+                if (ti < k)
+                    for (int j = ti + ts; j < k; j += 4) acc += Tl[ti * LDT + j] * Gs[j * 16 + k];
+                acc += __shfl_xor(acc, 16, kWave);
+                acc += __shfl_xor(acc, 32, kWave);
+                if (ti < k && ts == 0) Tl[ti * LDT + k] = -taus[k] * acc;
+                wave_lds_sync();
+            }
+            C* Tbb = Ts + tblk(b, b) * 16 * LDT;
+            for (int idx = lane; idx < 256; idx += 64) {
+                const int row = idx / 16, col = idx % 16;
+                const C v = Tl[row * LDT + col];
+                Tb[col * LDT + row] = v;
+                Tbb[row * LDT + col] = v;
+            }
+            // registers: tile b <- R block, tiles below <- V; V goes to global memory on the way
+#pragma unroll
+            for (int t = 0; t < HT; ++t) {
+                if (t < ntile) {
+                    if (t < b) {
+                        acc_t z;
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) z[r] = 0;
+                        frag_store<C, C, false>(Pd, ldp, 16 * t, mycol, gq, z);
+                    } else {
+                        C o[4];
+                        F::ld4(&Bs[i * LDB + 16 * t], gq, o);
+                        acc_t v;
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) v[r] = o[r];
+                        frag_store<C, C, false>(Pd, ldp, 16 * t, mycol, gq, v);
+                        if (t == b) {
+                            F::ld4(&Rs[i * LDT], gq, o);
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) v[r] = o[r];
+                        }
+                        c[t] = v;
+                    }
+                }
+            }
+        } else {
+            // P1 = V_b^T C_w over rows 16b ..: C_w's registers are the B operand
+            acc_t pa, pb;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) { pa[r] = 0; pb[r] = 0; }
+#pragma unroll
+            for (int t = 0; t < HT; ++t) {
+                if (t >= b && t < ntile) {
+                    C o[4];
+                    F::ld4(&Bs[i * LDB + 16 * t], gq, o);
+                    if (t & 1) {
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) pb = F::mma(o[r], c[t][r], pb);
+                    } else {
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) pa = F::mma(o[r], c[t][r], pa);
+                    }
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) p1[r] = pa[r] + pb[r];
+        }
+        __syncthreads();
+
+        // ---- right of the block: C_w -= V_b (T_b^T P1);  left of it: Z_w = (V_w^T V_b) T_b
+        if (wave != b) {
+            C tb[4];
+            F::ld4(&Tb[i * LDT], gq, tb);   // T_b[roff(r, gq)][i]
+            if (wave > b) {
+                acc_t w;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) w[r] = 0;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) w = F::mma(tb[r], p1[r], w);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) w[r] = -w[r];
+#pragma unroll
+                for (int t = 0; t < HT; ++t) {
+                    if (t >= b && t < ntile) {
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            c[t] = F::mma(Bs[F::roff(r, gq) * LDB + 16 * t + i], w[r], c[t]);
+                    }
+                }
+            } else {
+                acc_t z;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) z[r] = 0;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) z = F::mma(p1[r], tb[r], z);
+                const C o[4] = {z[0], z[1], z[2], z[3]};
+                F::st4(&Zs[i * LDZ + 16 * wave], gq, o);
+            }
+        }
+        __syncthreads();
+
+        // ---- T[wave, b] = - sum_{w2 = wave}^{b-1} T[wave, w2] Z_w2
+        if (wave < b) {
+            acc_t tn;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) tn[r] = 0;
+            for (int w2 = wave; w2 < b; ++w2) {
+                C ta[4], zb[4];
+                F::ld4(&Ts[tblk(wave, w2) * 16 * LDT + i * LDT], gq, ta);
+                F::ld4(&Zs[i * LDZ + 16 * w2], gq, zb);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) tn = F::mma(ta[r], zb[r], tn);
+            }
+            C* Tn = Ts + tblk(wave, b) * 16 * LDT;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) Tn[F::roff(r, gq) * LDT + i] = -tn[r];
+        }
+    }
+
+    // R: rows 0 .. NB-1 of the factored domain, zero below the diagonal
+#pragma unroll
+    for (int t = 0; t < NW; ++t) {
+        acc_t v;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) v[r] = (t <= wave) ? c[t][r] : (C)0;
+        frag_store<C, C, false>(Rd, ldnext, 16 * t, mycol, gq, v);
+    }
+    __syncthreads();
+    for (int idx = tid; idx < NB * NB; idx += NT) {
+        const int ii = idx % NB, jj = idx / NB;
+        const int bi = ii / 16, bj = jj / 16;
+        Td[ii + jj * NB] = bi <= bj ? Ts[tblk(bi, bj) * 16 * LDT + (ii % 16) * LDT + (jj % 16)] : (C)0;
+    }
+}
+
+template <typename C> constexpr int panel_blk_tiles() { return sizeof(C) == 4 ? 32 : 16; }
+
+template <typename C> int panel_blk_rows() { return panel_blk_tiles<C>() * 16; }
+template int panel_blk_rows<float>();
+template int panel_blk_rows<double>();
+
+template <typename C, int NB>
+static void launch_blk(C* P, int64_t ldp, C* Tws, int chunks, int g, C* Pnext, int64_t ldnext, hipStream_t s)
+{
+    constexpr int HT = panel_blk_tiles<C>();
+    using G = PanelBlkGeom<C, NB, HT>;
+    auto kern = panel_qr_blk_kernel<C, NB, HT>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  (int)G::kSmemBytes);
+        attr_set = true;
+    }
+    const int domains = (chunks + g - 1) / g;
+    hipLaunchKernelGGL(kern, dim3(domains), dim3(G::NT), G::kSmemBytes, s, P, ldp, Tws, chunks, g, Pnext, ldnext);
+}
+
+template <typename C>
+void launch_panel_blk(int nb, C* P, int64_t ldp, C* Tws, int chunks, int g, C* Pnext, int64_t ldnext, hipStream_t s)
+{
+    switch (nb) {
+    case 32: launch_blk<C, 32>(P, ldp, Tws, chunks, g, Pnext, ldnext, s); break;
+    case 64: launch_blk<C, 64>(P, ldp, Tws, chunks, g, Pnext, ldnext, s); break;
+    default: launch_blk<C, 128>(P, ldp, Tws, chunks, g, Pnext, ldnext, s); break;
+    }
+}
+
+template void launch_panel_blk<float>(int, float*, int64_t, float*, int, int, float*, int64_t, hipStream_t);
+template void launch_panel_blk<double>(int, double*, int64_t, double*, int, int, double*, int64_t, hipStream_t);
+
+}  // namespace svb

@@ -78,13 +78,12 @@ bool aligned_for_vectors(const void* A, int64_t lda)
 }
 
 // chunks-per-domain of the panel tree: as many nb-row tiles as the register-resident
-// panel kernel holds (512 rows; 256 for f64 at nb = 128)
+// panel and update kernels hold (512 rows in f32, 256 in f64)
 int domain_chunks(svb_dtype dt, int nb)
 {
     int g = env_int("SVB_DOMAIN_CHUNKS", 0);
     if (g >= 2 && g <= 64) return g;
-    if (dt == SVB_F64 && nb == 128) return 2;
-    return 512 / nb;
+    return (dt == SVB_F64 ? 256 : 512) / nb;
 }
 constexpr int kMinDomainChunks = 2;  // workspace is sized for any g >= this
 

@@ -53,6 +53,12 @@ template <typename C>
 void launch_panel_qr(int nb, C* P, int64_t ldp, C* Y, C* Tws, int chunks, int g,
                      C* Pnext, int64_t ldnext, int* err, hipStream_t s);
 
+// blocked register-resident domain QR (MFMA block reflectors inside the domain); domains of at
+// most panel_blk_rows<C>() rows
+template <typename C>
+void launch_panel_blk(int nb, C* P, int64_t ldp, C* Tws, int chunks, int g, C* Pnext, int64_t ldnext, hipStream_t s);
+template <typename C> int panel_blk_rows();
+
 template <typename C>
 void launch_scatter_r(const C* R, int64_t ldr, int nb, C* band, int64_t ldab,
                       int64_t row0, int64_t col0, bool lq, hipStream_t s);
