@@ -41,29 +41,71 @@ template <typename C, int NB, int HT> struct PanelBlkGeom {
     static constexpr int oTs = oBs + 16 * LDB;           // T, block (bi, bj) row-major at blk(bi, bj) * 16 * LDT
     static constexpr int oZs = oTs + NBLK * 16 * LDT;    // Z = (V_w^T V_b) T_b, [column][row]
     static constexpr int oXs = oZs + 16 * LDZ;           // pivot column, two buffers
-    static constexpr int oPart = oXs + 2 * H;            // partial inner products, [wave][column]
+    static constexpr int XST = RPT + 4;                  // a row group's slot in the pivot-column buffer
+    static constexpr int XSB = 4 * NW * XST;             // one buffer (padded: the four groups of a wave on different banks)
+    static constexpr int oPart = oXs + 2 * XSB;          // partial inner products, [wave][column]
     static constexpr int oRowk = oPart + NW * 16;        // pivot row, two buffers
-    static constexpr int oGs = oRowk + 2 * 16;           // v_c^T v_k inside the block
+    static constexpr int oGs = oRowk + 2 * 16;           // v_c^T v_k inside the block, [k][c]
     static constexpr int oRs = oGs + 16 * 16;            // R block, [column][row]
     static constexpr int oTb = oRs + 16 * LDT;           // T_b, [column][row]
-    static constexpr int oTl = oTb + 16 * LDT;           // T_b, [row][column]
-    static constexpr int oTau = oTl + 16 * LDT;
+    static constexpr int oTau = oTb + 16 * LDT;
     static constexpr int kElems = oTau + 16;
     static constexpr size_t kSmemBytes = (size_t)kElems * sizeof(C);
     static_assert(RPT % 4 == 0 && NRGU <= 4 * NW, "row split");
     static_assert(kSmemBytes <= 160 * 1024, "LDS");
 };
 
-__device__ __forceinline__ int tblk(int bi, int bj) { return bj * (bj + 1) / 2 + bi; }
-
-__device__ __forceinline__ void wave_lds_sync()
+// N consecutive elements to / from 16-byte aligned LDS
+template <typename C, int N> __device__ __forceinline__ void lds_ldn(const C* p, C (&o)[N])
 {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    constexpr int NV = 16 / (int)sizeof(C);
+#pragma unroll
+    for (int j = 0; j < N; j += NV) {
+        C t[NV];
+        VecIO<C, C>::ld(p + j, t);
+#pragma unroll
+        for (int q = 0; q < NV; ++q) o[j + q] = t[q];
+    }
+}
+template <typename C, int N> __device__ __forceinline__ void lds_stn(C* p, const C (&o)[N])
+{
+    constexpr int NV = 16 / (int)sizeof(C);
+#pragma unroll
+    for (int j = 0; j < N; j += NV) {
+        C t[NV];
+#pragma unroll
+        for (int q = 0; q < NV; ++q) t[q] = o[j + q];
+        VecIO<C, C>::st(p + j, t);
+    }
 }
 
+// value of lane (l ^ 1) / (l ^ 2) inside quads of four lanes
+template <int CTRL> __device__ __forceinline__ float quad_get(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+}
+template <int CTRL> __device__ __forceinline__ double quad_get(double v)
+{
+    const long long b = __builtin_bit_cast(long long, v);
+    const int lo = __builtin_amdgcn_update_dpp(0, (int)(b & 0xffffffffll), CTRL, 0xF, 0xF, true);
+    const int hi = __builtin_amdgcn_update_dpp(0, (int)(b >> 32), CTRL, 0xF, 0xF, true);
+    return __builtin_bit_cast(double, ((long long)hi << 32) | (long long)(unsigned)lo);
+}
+constexpr int kQuadXor1 = 0xB1, kQuadXor2 = 0x4E;   // quad_perm [1,0,3,2] and [2,3,0,1]
+
+__device__ __forceinline__ int tblk(int bi, int bj) { return bj * (bj + 1) / 2 + bi; }
+
 }  // namespace
+
+// Optional phase timing (compile with -DSVB_PANEL_TIMING): thread 0 of workgroup 0 adds the
+// shader-clock cycles of each phase to svb_panel_timing[slot].
+#ifdef SVB_PANEL_TIMING
+__device__ unsigned long long svb_panel_timing[16];
+#define PT_MARK(slot_) do { if (tid == 0 && blockIdx.x == 0) { const unsigned long long now_ = clock64(); \
+    atomicAdd(&svb_panel_timing[slot_], now_ - pt_last); pt_last = now_; } } while (0)
+#else
+#define PT_MARK(slot_) do { } while (0)
+#endif
 
 template <typename C, int NB, int HT>
 __global__ __launch_bounds__(NB * 4) void panel_qr_blk_kernel(C* __restrict__ P, int64_t ldp,
@@ -73,7 +115,7 @@ __global__ __launch_bounds__(NB * 4) void panel_qr_blk_kernel(C* __restrict__ P,
     using F = Frag<C>;
     using G = PanelBlkGeom<C, NB, HT>;
     typedef typename F::acc_t acc_t;
-    constexpr int NW = G::NW, NT = G::NT, H = G::H, RPT = G::RPT, NRGU = G::NRGU;
+    constexpr int NW = G::NW, NT = G::NT, H = G::H, RPT = G::RPT, NRGU = G::NRGU, XST = G::XST, XSB = G::XSB;
     constexpr int LDB = G::LDB, LDT = G::LDT, LDZ = G::LDZ;
     extern __shared__ __align__(16) unsigned char smem_raw[];
     C* sm = reinterpret_cast<C*>(smem_raw);
@@ -86,7 +128,6 @@ __global__ __launch_bounds__(NB * 4) void panel_qr_blk_kernel(C* __restrict__ P,
     C* Gs = sm + G::oGs;
     C* Rs = sm + G::oRs;
     C* Tb = sm + G::oTb;
-    C* Tl = sm + G::oTl;
     C* taus = sm + G::oTau;
 
     const int d = blockIdx.x;
@@ -97,9 +138,14 @@ __global__ __launch_bounds__(NB * 4) void panel_qr_blk_kernel(C* __restrict__ P,
     C* Rd = Pnext + (int64_t)d * NB;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int i = lane & 15, gq = lane >> 4;      // MFMA fragment coordinates
-    const int pc = tid & 15, prg = tid >> 4;      // step 2: column of the block, row group
+    // step 2: column of the block and row group; the four row groups of a wave sit in one quad
+    // of lanes, so their partial sums meet through DPP
+    const int pc = lane >> 2, prg = 4 * wave + (lane & 3);
     const int64_t mycol = 16 * wave + i;
 
+#ifdef SVB_PANEL_TIMING
+    unsigned long long pt_last = clock64();
+#endif
     acc_t c[HT];
 #pragma unroll
     for (int t = 0; t < HT; ++t) {
@@ -110,6 +156,7 @@ __global__ __launch_bounds__(NB * 4) void panel_qr_blk_kernel(C* __restrict__ P,
     }
     for (int idx = tid; idx < G::NBLK * 16 * LDT; idx += NT) Ts[idx] = 0;
 
+    PT_MARK(0);
     for (int b = 0; b < NW; ++b) {
         // ---- 1. the owner's columns (rows 16b ..) to LDS
         if (wave == b) {
@@ -121,38 +168,59 @@ __global__ __launch_bounds__(NB * 4) void panel_qr_blk_kernel(C* __restrict__ P,
                 }
         }
         __syncthreads();
+        PT_MARK(1);
 
         // ---- 2. Householder QR of the block: thread (pc, prg) holds rows 16b + prg*RPT + r of column pc
         const int rbase = 16 * b + prg * RPT;
-        const bool rows_on = prg < NRGU;
+        const bool rows_on = NRGU == 4 * NW || prg < NRGU;   // compile-time true unless row groups are spare
+        // (a 16-byte vector never straddles row H: rbase and H are multiples of 16)
+        constexpr bool kVecB = sizeof(C) == 4;   // f64 block columns have an odd row length
         C a[RPT];
+        if (rows_on) {
+            if constexpr (kVecB) {
 #pragma unroll
-        for (int r = 0; r < RPT; ++r) a[r] = (rows_on && rbase + r < H) ? Bs[pc * LDB + rbase + r] : (C)0;
+                for (int r = 0; r < RPT; r += 4) {
+                    C t4[4] = {0, 0, 0, 0};
+                    if (rbase + r < H) lds_ldn<C, 4>(&Bs[pc * LDB + rbase + r], t4);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) a[r + q] = t4[q];
+                }
+            } else {
+#pragma unroll
+                for (int r = 0; r < RPT; ++r) a[r] = (rbase + r < H) ? Bs[pc * LDB + rbase + r] : (C)0;
+            }
+        } else {
+#pragma unroll
+            for (int r = 0; r < RPT; ++r) a[r] = 0;
+        }
         C my_inv = 0;
+        PT_MARK(2);
 #pragma unroll
         for (int ki = 0; ki < 16; ++ki) {
             const int buf = ki & 1;
             if (prg == 0) rowk[buf * 16 + pc] = a[ki];
             if (pc == ki && rows_on) {
+                C o[RPT];
 #pragma unroll
-                for (int r = 0; r < RPT; ++r) xs[buf * H + prg * RPT + r] = (prg == 0 && r <= ki) ? (C)0 : a[r];
+                for (int r = 0; r < RPT; ++r) o[r] = (prg == 0 && r <= ki) ? (C)0 : a[r];
+                lds_stn<C, RPT>(&xs[buf * XSB + prg * XST], o);
             }
             __syncthreads();
             C x[RPT];
             C p = 0;
             if (rows_on) {
+                lds_ldn<C, RPT>(&xs[buf * XSB + prg * XST], x);
+                C p4[4] = {0, 0, 0, 0};
 #pragma unroll
-                for (int r = 0; r < RPT; ++r) {
-                    x[r] = xs[buf * H + prg * RPT + r];
-                    p += x[r] * a[r];
-                }
+                for (int r = 0; r < RPT; ++r) p4[r & 3] += x[r] * a[r];
+                p = (p4[0] + p4[1]) + (p4[2] + p4[3]);
             } else {
 #pragma unroll
                 for (int r = 0; r < RPT; ++r) x[r] = 0;
             }
-            p += __shfl_xor(p, 16, kWave);
-            p += __shfl_xor(p, 32, kWave);
-            if (lane < 16) part[wave * 16 + pc] = p;
+            p += quad_get<kQuadXor1>(p);
+            p += quad_get<kQuadXor2>(p);
+            if ((lane & 3) == 0) part[wave * 16 + pc] = p;
             __syncthreads();
             C D = 0, ss = 0;
 #pragma unroll
@@ -165,15 +233,15 @@ __global__ __launch_bounds__(NB * 4) void panel_qr_blk_kernel(C* __restrict__ P,
             if (ss == (C)0) {
                 tau = 0; beta = alpha; inv = 0;
             } else {
-                const C nrm = sqrt(alpha * alpha + ss);
+                const C nrm = newton_sqrt(alpha * alpha + ss);
                 beta = alpha >= (C)0 ? -nrm : nrm;
-                tau = (beta - alpha) / beta;
-                inv = (C)1 / (alpha - beta);
+                tau = (beta - alpha) * newton_rcp(beta);
+                inv = newton_rcp(alpha - beta);
             }
             const C wk = akc + inv * D;   // v_k^T (column pc), v_k's tail taken unscaled times inv
             const C f = tau * wk;
             if (prg == 0) {
-                if (pc < ki) Gs[pc * 16 + ki] = my_inv * wk;   // v_pc^T v_k (v_pc's tail is stored unscaled)
+                if (pc < ki) Gs[ki * 16 + pc] = my_inv * wk;   // v_pc^T v_k (v_pc's tail is stored unscaled)
                 if (pc == ki) taus[ki] = tau;
             }
             if (pc == ki) my_inv = inv;
@@ -184,16 +252,26 @@ __global__ __launch_bounds__(NB * 4) void panel_qr_blk_kernel(C* __restrict__ P,
                 for (int r = 0; r < RPT; ++r) a[r] -= coef * x[r];   // x is zero at and above the pivot row
             }
         }
+        PT_MARK(3);
         // explicit V block (unit diagonal, zeros above) back to LDS; R block aside
         if (rows_on) {
+            C v[RPT];
 #pragma unroll
             for (int r = 0; r < RPT; ++r) {
                 const int rel = prg * RPT + r;
-                if (rbase + r < H) {
-                    C v = a[r] * my_inv;
-                    if (rel < 16) v = rel < pc ? (C)0 : (rel == pc ? (C)1 : v);
-                    Bs[pc * LDB + rbase + r] = v;
+                v[r] = a[r] * my_inv;
+                if (rel < 16) v[r] = rel < pc ? (C)0 : (rel == pc ? (C)1 : v[r]);
+            }
+            if constexpr (kVecB) {
+#pragma unroll
+                for (int r = 0; r < RPT; r += 4) {
+                    const C t4[4] = {v[r], v[r + 1], v[r + 2], v[r + 3]};
+                    if (rbase + r < H) lds_stn<C, 4>(&Bs[pc * LDB + rbase + r], t4);
                 }
+            } else {
+#pragma unroll
+                for (int r = 0; r < RPT; ++r)
+                    if (rbase + r < H) Bs[pc * LDB + rbase + r] = v[r];
             }
         }
         if (prg == 0) {
@@ -201,31 +279,35 @@ __global__ __launch_bounds__(NB * 4) void panel_qr_blk_kernel(C* __restrict__ P,
             for (int r = 0; r < 16; ++r) Rs[pc * LDT + r] = (r <= pc) ? a[r] : (C)0;
         }
         __syncthreads();
+        PT_MARK(4);
 
         // ---- 3./4. first product with V_b (every wave but the owner); the owner builds T_b
         acc_t p1;
 #pragma unroll
         for (int r = 0; r < 4; ++r) p1[r] = 0;
         if (wave == b) {
-            // T_b: T[k][k] = tau_k, T[i][k] = -tau_k sum_{j=i}^{k-1} T[i][j] (v_j^T v_k); lane (row ti, 4 lanes per row)
-            const int ti = i, ts = gq;
-            for (int j = ts; j < 16; j += 4) Tl[ti * LDT + j] = (j == ti) ? taus[ti] : (C)0;
-            wave_lds_sync();
-            for (int k = 1; k < 16; ++k) {
+            // T_b: T[k][k] = tau_k, T[i][k] = -tau_k sum_{j=i}^{k-1} T[i][j] (v_j^T v_k); lane i keeps
+            // row i in registers (zero left of the diagonal), so a column costs no exchange
+            C trow[16];
+#pragma unroll
+            for (int k = 0; k < 16; ++k) {
                 C acc = 0;
-                if (ti < k)
-                    for (int j = ti + ts; j < k; j += 4) acc += Tl[ti * LDT + j] * Gs[j * 16 + k];
-                acc += __shfl_xor(acc, 16, kWave);
-                acc += __shfl_xor(acc, 32, kWave);
-                if (ti < k && ts == 0) Tl[ti * LDT + k] = -taus[k] * acc;
-                wave_lds_sync();
+                if (k > 0) {
+                    C gk[16];
+                    lds_ldn<C, 16>(&Gs[k * 16], gk);
+#pragma unroll
+                    for (int j = 0; j < k; ++j) acc += trow[j] * gk[j];
+                }
+                const C tk = taus[k];
+                trow[k] = (k == i) ? tk : (k > i ? -tk * acc : (C)0);
             }
-            C* Tbb = Ts + tblk(b, b) * 16 * LDT;
-            for (int idx = lane; idx < 256; idx += 64) {
-                const int row = idx / 16, col = idx % 16;
-                const C v = Tl[row * LDT + col];
-                Tb[col * LDT + row] = v;
-                Tbb[row * LDT + col] = v;
+            if (gq == 0) {
+                C* Tbb = Ts + tblk(b, b) * 16 * LDT;
+#pragma unroll
+                for (int k = 0; k < 16; ++k) {
+                    Tb[k * LDT + i] = trow[k];
+                    Tbb[i * LDT + k] = trow[k];
+                }
             }
             // registers: tile b <- R block, tiles below <- V; V goes to global memory on the way
 #pragma unroll
@@ -275,6 +357,7 @@ __global__ __launch_bounds__(NB * 4) void panel_qr_blk_kernel(C* __restrict__ P,
             for (int r = 0; r < 4; ++r) p1[r] = pa[r] + pb[r];
         }
         __syncthreads();
+        PT_MARK(5);
 
         // ---- right of the block: C_w -= V_b (T_b^T P1);  left of it: Z_w = (V_w^T V_b) T_b
         if (wave != b) {
@@ -307,6 +390,7 @@ __global__ __launch_bounds__(NB * 4) void panel_qr_blk_kernel(C* __restrict__ P,
             }
         }
         __syncthreads();
+        PT_MARK(6);
 
         // ---- T[wave, b] = - sum_{w2 = wave}^{b-1} T[wave, w2] Z_w2
         if (wave < b) {
@@ -326,6 +410,7 @@ __global__ __launch_bounds__(NB * 4) void panel_qr_blk_kernel(C* __restrict__ P,
         }
     }
 
+    PT_MARK(7);
     // R: rows 0 .. NB-1 of the factored domain, zero below the diagonal
 #pragma unroll
     for (int t = 0; t < NW; ++t) {
@@ -340,7 +425,9 @@ __global__ __launch_bounds__(NB * 4) void panel_qr_blk_kernel(C* __restrict__ P,
         const int bi = ii / 16, bj = jj / 16;
         Td[ii + jj * NB] = bi <= bj ? Ts[tblk(bi, bj) * 16 * LDT + (ii % 16) * LDT + (jj % 16)] : (C)0;
     }
+    PT_MARK(8);
 }
+#undef PT_MARK
 
 template <typename C> constexpr int panel_blk_tiles() { return sizeof(C) == 4 ? 32 : 16; }
 

@@ -23,6 +23,23 @@ template <> __device__ __forceinline__ float ld_as<float, __half>(const __half* 
 template <typename T, typename C> __device__ __forceinline__ void st_as(T* p, C v) { *p = (T)v; }
 template <> __device__ __forceinline__ void st_as<__half, float>(__half* p, float v) { *p = __float2half(v); }
 
+// Reciprocal and square root for reflector scalars: the hardware approximations (1 ulp,
+// biased) refined by Newton steps.  A biased tau or scale would make every reflector
+// non-orthogonal in the same direction, which adds up over a sweep.
+__device__ __forceinline__ float newton_rcp(float x)
+{
+    const float r = __builtin_amdgcn_rcpf(x);
+    return fmaf(r, fmaf(-x, r, 1.0f), r);
+}
+__device__ __forceinline__ double newton_rcp(double x) { return 1.0 / x; }
+__device__ __forceinline__ float newton_sqrt(float x)   // x > 0, normal
+{
+    const float r = __builtin_amdgcn_rsqf(x);
+    const float s = x * r;
+    return fmaf(fmaf(-s, s, x), 0.5f * r, s);
+}
+__device__ __forceinline__ double newton_sqrt(double x) { return sqrt(x); }
+
 // Geometry of one half-sweep's panel tree (Section 3.1: GEQRT on the first
 // tile, then the tiles below are annihilated; here the tiles of a panel are
 // grouped into domains that are factored independently and merged level by
