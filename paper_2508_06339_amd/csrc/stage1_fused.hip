@@ -40,10 +40,23 @@ template <typename C, int NB> struct FusedGeom {
 
 }  // namespace
 
+// Optional phase timing (compile with -DSVB_FUSED_TIMING): thread 0 of workgroup 0 adds the
+// shader-clock cycles of each phase to svb_fused_timing[slot].
+#ifdef SVB_FUSED_TIMING
+__device__ unsigned long long svb_fused_timing[8];
+#define FT_MARK(slot_) do { if (tid == 0 && blockIdx.x == 0) { const unsigned long long now_ = clock64(); \
+    atomicAdd(&svb_fused_timing[slot_], now_ - ft_last); ft_last = now_; } } while (0)
+#else
+#define FT_MARK(slot_) do { } while (0)
+#endif
+
 // HT: 16-row tiles a wave holds (HT * 16 = rows of the largest domain).
 // Two workgroups per compute unit (one loads or stores its block while the other computes)
 // wherever the block and W fit in 256 registers per lane.
-template <typename T, typename C, int NB, int HT, bool LQ>
+// TRI: the panel is a stack of upper triangular NB x NB factors (every tree level above the
+// first), so in every NB-row chunk of V and of Y = V T the 16 x 16 blocks below the block
+// diagonal are exactly zero and their products are skipped.
+template <typename T, typename C, int NB, int HT, bool LQ, bool TRI>
 __global__ __launch_bounds__(256, (sizeof(C) == 8 && NB == 128) ? 1 : 2) void update_fused_kernel(T* __restrict__ Cb, int64_t lda, int64_t qlen,
                                                            const C* __restrict__ V, const C* __restrict__ Y,
                                                            int64_t ldp, int chunks, int g, int64_t stride,
@@ -80,14 +93,17 @@ __global__ __launch_bounds__(256, (sizeof(C) == 8 && NB == 128) ? 1 : 2) void up
         return ((int64_t)d * g + (16 * t) / NB) * stride + (16 * t) % NB;
     };
 
+    // The block is fetched tile by tile, PF tiles ahead of the first product's progress, and
+    // written back tile by tile as the second product finishes with it, so that the memory
+    // traffic runs under the MFMAs instead of before and after them.
+    constexpr int PF = HT < 8 ? HT : 8;
     acc_t c[HT];
-#pragma unroll
-    for (int t = 0; t < HT; ++t) {
+    auto tile_ld = [&](int t) {
         if (active && t < ntile) c[t] = frag_load<T, C, LQ>(Cb, lda, tile_p(t), q, gq);
         else
 #pragma unroll
             for (int r = 0; r < 4; ++r) c[t][r] = 0;
-    }
+    };
     acc_t w[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
@@ -127,10 +143,22 @@ __global__ __launch_bounds__(256, (sizeof(C) == 8 && NB == 128) ? 1 : 2) void up
         }
     };
 
+    // barrier that orders LDS traffic only (s_waitcnt lgkmcnt(0); s_barrier): __syncthreads()
+    // would also wait for every outstanding global load and store
+    auto lds_barrier = [] {
+        __builtin_amdgcn_s_waitcnt(0xc07f);
+        __builtin_amdgcn_s_barrier();
+    };
+#ifdef SVB_FUSED_TIMING
+    unsigned long long ft_last = clock64();
+#endif
     int cur = 0;
     slice_ld(Y, 0);
+#pragma unroll
+    for (int t = 0; t < PF; ++t) tile_ld(t);
     slice_st_y(smem);
-    __syncthreads();
+    lds_barrier();
+    FT_MARK(0);
 #pragma unroll
     for (int s = 0; s < 2 * NCK; ++s) {
         const bool isV = s >= NCK;
@@ -140,24 +168,33 @@ __global__ __launch_bounds__(256, (sizeof(C) == 8 && NB == 128) ? 1 : 2) void up
             const bool have_next = !(isV && last);
             const bool nextV = isV || last;
             if (have_next) slice_ld(nextV ? V : Y, last ? 0 : ck + 1);
+            if (!isV) {
+#pragma unroll
+                for (int tt = 0; tt < RC / 16; ++tt)
+                    if (ck * (RC / 16) + tt + PF < HT) tile_ld(ck * (RC / 16) + tt + PF);
+            }
             const C* buf = smem + cur * BUF;
+            FT_MARK(1);
             if (active) {
                 if (!isV) {
                     // W += Y_slice^T C_slice
 #pragma unroll
                     for (int tt = 0; tt < RC / 16; ++tt) {
                         const int t = ck * (RC / 16) + tt;
+                        const int rb = TRI ? (16 * t % NB) / 16 : 0;   // first non-zero block column of this tile
                         // four tiles of W at a time: consecutive MFMAs are independent
                         constexpr int MG = MT < 4 ? MT : 4;
 #pragma unroll
                         for (int m0 = 0; m0 < MT; m0 += MG) {
                             C a[MG][4];
 #pragma unroll
-                            for (int m = 0; m < MG; ++m) F::ld4(&buf[(16 * (m0 + m) + i) * LDR + 16 * tt], gq, a[m]);
+                            for (int m = 0; m < MG; ++m)
+                                if (m0 + m >= rb) F::ld4(&buf[(16 * (m0 + m) + i) * LDR + 16 * tt], gq, a[m]);
 #pragma unroll
                             for (int r = 0; r < 4; ++r)
 #pragma unroll
-                                for (int m = 0; m < MG; ++m) w[m0 + m] = F::mma(a[m][r], c[t][r], w[m0 + m]);
+                                for (int m = 0; m < MG; ++m)
+                                    if (m0 + m >= rb) w[m0 + m] = F::mma(a[m][r], c[t][r], w[m0 + m]);
                         }
                     }
                     if (last) {
@@ -170,42 +207,43 @@ __global__ __launch_bounds__(256, (sizeof(C) == 8 && NB == 128) ? 1 : 2) void up
                     // C_slice += V_slice (-W)
                     static_assert(RC / 16 == 2, "two tiles per slice");
                     const int t0 = ck * 2, t1 = ck * 2 + 1;
+                    const int rb0 = TRI ? (16 * t0 % NB) / 16 : 0, rb1 = TRI ? (16 * t1 % NB) / 16 : 0;
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt) {
                         C a0[4], a1[4];
-                        F::ld4(&buf[i * LDC + 16 * mt], gq, a0);
-                        F::ld4(&buf[(16 + i) * LDC + 16 * mt], gq, a1);
+                        if (mt >= rb0) F::ld4(&buf[i * LDC + 16 * mt], gq, a0);
+                        if (mt >= rb1) F::ld4(&buf[(16 + i) * LDC + 16 * mt], gq, a1);
 #pragma unroll
                         for (int r = 0; r < 4; ++r) {
-                            c[t0] = F::mma(a0[r], w[mt][r], c[t0]);
-                            c[t1] = F::mma(a1[r], w[mt][r], c[t1]);
+                            if (mt >= rb0) c[t0] = F::mma(a0[r], w[mt][r], c[t0]);
+                            if (mt >= rb1) c[t1] = F::mma(a1[r], w[mt][r], c[t1]);
                         }
                     }
+                    frag_store<T, C, LQ>(Cb, lda, tile_p(t0), q, gq, c[t0]);
+                    frag_store<T, C, LQ>(Cb, lda, tile_p(t1), q, gq, c[t1]);
                 }
             }
+            FT_MARK(isV ? 3 : 2);
             if (have_next) {
                 C* nbuf = smem + (cur ^ 1) * BUF;
                 if (nextV) slice_st_v(nbuf);
                 else slice_st_y(nbuf);
             }
-            __syncthreads();
+            FT_MARK(4);
+            lds_barrier();
+            FT_MARK(5);
             cur ^= 1;
         }
     }
-
-    if (active) {
-#pragma unroll
-        for (int t = 0; t < HT; ++t)
-            if (t < ntile) frag_store<T, C, LQ>(Cb, lda, tile_p(t), q, gq, c[t]);
-    }
 }
+#undef FT_MARK
 
-template <typename T, typename C, int NB, int HT, bool LQ>
+template <typename T, typename C, int NB, int HT, bool LQ, bool TRI>
 static void launch_fused(T* Cb, int64_t lda, int64_t qlen, const C* V, const C* Y, int64_t ldp, int chunks,
                          int g, int64_t stride, bool credited, hipStream_t s)
 {
     using G = FusedGeom<C, NB>;
-    auto kern = update_fused_kernel<T, C, NB, HT, LQ>;
+    auto kern = update_fused_kernel<T, C, NB, HT, LQ, TRI>;
     static bool attr_set = false;
     if (!attr_set) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -234,14 +272,16 @@ template int fused_update_rows<double>();
 
 template <typename T, typename C>
 void launch_update_fused(int nb, bool lq, T* Cb, int64_t lda, int64_t qlen, const C* V, const C* Y,
-                         int64_t ldp, int chunks, int g, int64_t stride, bool credited, hipStream_t s)
+                         int64_t ldp, int chunks, int g, int64_t stride, bool tri, bool credited, hipStream_t s)
 {
     if (qlen <= 0) return;
     constexpr int HT = fused_tiles<C>();
 #define SVB_FUSED_CASE(NBV)                                                                                   \
     case NBV:                                                                                                 \
-        if (lq) launch_fused<T, C, NBV, HT, true>(Cb, lda, qlen, V, Y, ldp, chunks, g, stride, credited, s);  \
-        else launch_fused<T, C, NBV, HT, false>(Cb, lda, qlen, V, Y, ldp, chunks, g, stride, credited, s);    \
+        if (lq && tri) launch_fused<T, C, NBV, HT, true, true>(Cb, lda, qlen, V, Y, ldp, chunks, g, stride, credited, s);        \
+        else if (lq) launch_fused<T, C, NBV, HT, true, false>(Cb, lda, qlen, V, Y, ldp, chunks, g, stride, credited, s);         \
+        else if (tri) launch_fused<T, C, NBV, HT, false, true>(Cb, lda, qlen, V, Y, ldp, chunks, g, stride, credited, s);        \
+        else launch_fused<T, C, NBV, HT, false, false>(Cb, lda, qlen, V, Y, ldp, chunks, g, stride, credited, s);                \
         break;
     switch (nb) {
         SVB_FUSED_CASE(32)
@@ -252,8 +292,8 @@ void launch_update_fused(int nb, bool lq, T* Cb, int64_t lda, int64_t qlen, cons
 #undef SVB_FUSED_CASE
 }
 
-template void launch_update_fused<float, float>(int, bool, float*, int64_t, int64_t, const float*, const float*, int64_t, int, int, int64_t, bool, hipStream_t);
-template void launch_update_fused<__half, float>(int, bool, __half*, int64_t, int64_t, const float*, const float*, int64_t, int, int, int64_t, bool, hipStream_t);
-template void launch_update_fused<double, double>(int, bool, double*, int64_t, int64_t, const double*, const double*, int64_t, int, int, int64_t, bool, hipStream_t);
+template void launch_update_fused<float, float>(int, bool, float*, int64_t, int64_t, const float*, const float*, int64_t, int, int, int64_t, bool, bool, hipStream_t);
+template void launch_update_fused<__half, float>(int, bool, __half*, int64_t, int64_t, const float*, const float*, int64_t, int, int, int64_t, bool, bool, hipStream_t);
+template void launch_update_fused<double, double>(int, bool, double*, int64_t, int64_t, const double*, const double*, int64_t, int, int, int64_t, bool, bool, hipStream_t);
 
 }  // namespace svb

@@ -286,7 +286,7 @@ int ge2gb_impl(int64_t n, T* A, int64_t lda, int nb, C* band, int64_t ldab, unsi
                 if (impl == 2) {
                     for (int L = 0; L < nl; ++L)
                         launch_update_fused<T, C>(nb, lq, Cb, lda, qlen, Vb + lv[L].poff, Yb + lv[L].poff,
-                                                  lv[L].ldp, lv[L].chunks, g, lv[L].stride, L == 0, s);
+                                                  lv[L].ldp, lv[L].chunks, g, lv[L].stride, L > 0, L == 0, s);
                 } else
                 for (int L = 0; L < nl; ++L)
                     launch_update<T, C>(nb, lq, Cb, lda, qlen, Vb + lv[L].poff, Yb + lv[L].poff, lv[L].ldp,

@@ -92,10 +92,11 @@ void launch_update(int nb, bool lq, T* Cbase, int64_t lda, int64_t qlen,
                    C* W, int impl, bool credited, int phase, hipStream_t s);
 
 // The same update in one pass over the trailing matrix (W stays in registers); domains of
-// at most fused_update_rows<C>() rows.
+// at most fused_update_rows<C>() rows.  tri: the panel is a stack of upper triangular factors
+// (tree levels above the first), whose structural zeros in V and Y are skipped.
 template <typename T, typename C>
 void launch_update_fused(int nb, bool lq, T* Cbase, int64_t lda, int64_t qlen, const C* V, const C* Y,
-                         int64_t ldp, int chunks, int g, int64_t stride, bool credited, hipStream_t s);
+                         int64_t ldp, int chunks, int g, int64_t stride, bool tri, bool credited, hipStream_t s);
 template <typename C> int fused_update_rows();
 
 // per-kernel timing hooks (no-ops unless profiling is enabled)
