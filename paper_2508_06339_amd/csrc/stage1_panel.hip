@@ -438,7 +438,7 @@ template <typename C>
 void launch_panel_qr(int nb, C* P, int64_t ldp, C* Y, C* Tws, int chunks, int g,
                      C* Pnext, int64_t ldnext, int* /*err*/, hipStream_t s)
 {
-    static const int impl = env_int("SVB_PANEL_IMPL", 2);
+    const int impl = env_int("SVB_PANEL_IMPL", 2);
     // blocked register-resident kernel (2, default) or the reflector-at-a-time register kernel (1),
     // each followed by the MFMA Y product, when the domain fits (and 128-row Y tiles never
     // straddle two domains); otherwise the plain kernel below

@@ -78,6 +78,18 @@ def test_small_tree_parameters(monkeypatch):
     _check(_gpu_sigma(a, 32), ref, 288, "f64")
 
 
+@pytest.mark.parametrize("panel,update", [("1", "2"), ("0", "2"), ("2", "1"), ("2", "0"), ("1", "1")])
+@pytest.mark.parametrize("name,n,nb", [("c4", 640, 64), ("c5b", 768, 128), ("c3b", 512, 32)])
+def test_stage1_alternative_kernels(monkeypatch, panel, update, name, n, nb):
+    # stage-1 kernels kept beside the defaults: reflector-at-a-time register panel (1) and plain
+    # panel (0); two-kernel MFMA update with look-ahead (1) and plain FMA update (0)
+    monkeypatch.setenv("SVB_PANEL_IMPL", panel)
+    monkeypatch.setenv("SVB_UPDATE_IMPL", update)
+    a, info = workloads.make(name, n=n, nb=nb)
+    fro = 2e-2 if info["dtype"] == "f16" else None
+    _check(_gpu_sigma(a, nb), oracle.svdvals(a), n, info["dtype"], fro)
+
+
 def test_degenerate_inputs():
     n, nb = 128, 32
     z = np.zeros((n, n), order="F")
