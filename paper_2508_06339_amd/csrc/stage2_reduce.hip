@@ -175,8 +175,10 @@ template <int D> __device__ __forceinline__ void load_v(const double* v, double 
 // H_0 H_1 .. H_{D-1} = I - V T V^T, row-major.  One D-vector reduction over the wave per
 // reflector yields its norm, the products with the lines below and the products v_j^T v_k
 // that T needs; the sums are wave-uniform scalars.  D = 8.
-template <typename C, int B, int D>
-__device__ __forceinline__ void panel_wave(C* P, int sk, int se, C* Vs, C* Ts)
+// With G the panel lies in the packed band in device memory (device-scope accesses, elements
+// e >= ne outside the matrix: read as zero, not written).
+template <typename C, int B, int D, bool G = false>
+__device__ __forceinline__ void panel_wave(C* P, int64_t sk, int64_t se, C* Vs, C* Ts, int ne = B)
 {
     constexpr int QN = (B + kWave - 1) / kWave;
     const int lane = threadIdx.x & (kWave - 1);
@@ -186,7 +188,8 @@ __device__ __forceinline__ void panel_wave(C* P, int sk, int se, C* Vs, C* Ts)
 #pragma unroll
         for (int q = 0; q < QN; ++q) {
             const int e = lane + kWave * q;
-            x[k][q] = (e < B) ? P[k * sk + e * se] : (C)0;
+            if (G) x[k][q] = (e < ne) ? rgld(P + k * sk + e * se) : (C)0;
+            else x[k][q] = (e < B) ? P[k * sk + e * se] : (C)0;
         }
     const int tj = lane & (D - 1);   // this lane builds row tj of T as the reflectors appear
     C trow[D];
@@ -246,7 +249,11 @@ __device__ __forceinline__ void panel_wave(C* P, int sk, int se, C* Vs, C* Ts)
         if (e < B) {
 #pragma unroll
             for (int k = 0; k < D; ++k) {
-                P[k * sk + e * se] = (e <= k) ? x[k][q] : (C)0;
+                if (G) {
+                    if (e < ne) rgst(P + k * sk + e * se, (e <= k) ? x[k][q] : (C)0);
+                } else {
+                    P[k * sk + e * se] = (e <= k) ? x[k][q] : (C)0;
+                }
                 Vs[vidx<B, D>(e) + k] = (e < k) ? (C)0 : (e == k ? (C)1 : x[k][q]);
             }
         }
@@ -305,6 +312,61 @@ __device__ __forceinline__ void apply_line(C* base, int es, bool valid, const C*
     }
 }
 
+// The same for a line of the packed band in device memory (device-scope accesses): elements
+// base[e*es], e < ne, eight lanes per line (an eighth of the line each, held in registers
+// between the two passes).  With IL the eight lanes own interleaved elements (e = 8*jj + p),
+// which keeps their accesses together when the line is contiguous in memory.
+template <typename C, int B, int D, bool IL>
+__device__ __forceinline__ void apply_line_g(C* base, int64_t es, bool valid, int ne, const C* Vs, const C* Ts)
+{
+    constexpr int SEG = B / 8;
+    const int p = threadIdx.x & 7;
+    C a[SEG];
+    C w[D];
+#pragma unroll
+    for (int k = 0; k < D; ++k) w[k] = 0;
+    if (valid) {
+#pragma unroll
+        for (int jj = 0; jj < SEG; ++jj) {
+            const int e = IL ? 8 * jj + p : p * SEG + jj;
+            a[jj] = (e < ne) ? rgld(base + e * es) : (C)0;
+        }
+#pragma unroll
+        for (int jj = 0; jj < SEG; ++jj) {
+            const int e = IL ? 8 * jj + p : p * SEG + jj;
+            C v[D];
+            load_v<D>(Vs + vidx<B, D>(e), v);
+#pragma unroll
+            for (int k = 0; k < D; ++k) w[k] += a[jj] * v[k];
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < D; ++k) {
+        w[k] = quad_allsum(w[k]);
+        w[k] += dpp_get<kDppHalfMirror>(w[k]);   // the other quad of the eight
+    }
+    C z[D];
+#pragma unroll
+    for (int k = 0; k < D; ++k) {
+        C acc = 0;
+#pragma unroll
+        for (int j = 0; j <= k; ++j) acc += w[j] * Ts[j * D + k];
+        z[k] = acc;
+    }
+    if (valid) {
+#pragma unroll
+        for (int jj = 0; jj < SEG; ++jj) {
+            const int e = IL ? 8 * jj + p : p * SEG + jj;
+            C v[D];
+            load_v<D>(Vs + vidx<B, D>(e), v);
+            C x = a[jj];
+#pragma unroll
+            for (int k = 0; k < D; ++k) x -= z[k] * v[k];
+            if (e < ne) rgst(base + e * es, x);
+        }
+    }
+}
+
 // threads of the band reduction kernel: 8*B apply threads (four per line of a 2B-line pass),
 // plus one extra wave for the panels where that still fits in a workgroup.  Blocks are moved
 // by "traffic" waves, each lane keeping one block row: a wave covers 64 consecutive rows of
@@ -322,7 +384,10 @@ template <int B> struct ReduceShape {
     static constexpr int PER = (B + JS - 1) / JS;                 // accesses per traffic wave and block
 };
 
-template <typename C, int B, int D>
+// UG: only the diagonal block Z lives in LDS; the upper block U and the block right of Z are
+// transformed where they lie, in the packed band in device memory (for element types of which
+// two B x B blocks do not fit in LDS).
+template <typename C, int B, int D, bool UG = false>
 __global__ __launch_bounds__(ReduceShape<B>::NT) void band_reduce_kernel(C* __restrict__ band, int64_t ldab, int64_t n,
                                                                         int* __restrict__ ctrl,
                                                                         int* __restrict__ progress, int spin_limit)
@@ -332,9 +397,10 @@ __global__ __launch_bounds__(ReduceShape<B>::NT) void band_reduce_kernel(C* __re
     // and LDS.  The panel wave's work overlaps the traffic: the right panel of step t with the
     // write-back of Z of step t-1, the left panel with the write-back of U.
     using SH = ReduceShape<B>;
-    constexpr int LD = 2 * B + 1, PER = SH::PER, JS = SH::JS;
+    constexpr int LD = UG ? B + 1 : 2 * B + 1, PER = SH::PER, JS = SH::JS;
+    constexpr int ZO = UG ? 0 : B;                // first row of Z inside S
     extern __shared__ __align__(16) unsigned char smem_raw[];
-    C* S = reinterpret_cast<C*>(smem_raw);        // rows c0-B .. c0+B-1, columns c0 .. c0+B-1: S[row + col*LD]
+    C* S = reinterpret_cast<C*>(smem_raw);        // rows c0-B .. c0+B-1 (UG: c0 ..), columns c0 .. c0+B-1: S[row + col*LD]
     C* Vs = S + ((B * LD + 3) & ~3);              // (B + 4) * D
     C* Ts = Vs + (B + 4) * D;                     // D * D
     __shared__ int sh_s, sh_fail;
@@ -421,14 +487,14 @@ __global__ __launch_bounds__(ReduceShape<B>::NT) void band_reduce_kernel(C* __re
             const int lds0 = ii + jj0 * LD;
 #pragma unroll
             for (int q = 0; q < PER; ++q) {
-                u0[q] = gload(ub, q, ii >= B - D);
+                if (!UG) u0[q] = gload(ub, q, ii >= B - D);
                 pre[q] = gload(zb, q, true);
             }
 #pragma unroll
             for (int q = 0; q < PER; ++q) {
                 if (jj0 + q * JS < B) {
-                    S[lds0 + q * JS * LD] = (inside(ub, q) && ii >= B - D) ? u0[q] : (C)0;
-                    S[B + lds0 + q * JS * LD] = inside(zb, q) ? pre[q] : (C)0;
+                    if (!UG) S[lds0 + q * JS * LD] = (inside(ub, q) && ii >= B - D) ? u0[q] : (C)0;
+                    S[ZO + lds0 + q * JS * LD] = inside(zb, q) ? pre[q] : (C)0;
                 }
             }
         }
@@ -445,8 +511,23 @@ __global__ __launch_bounds__(ReduceShape<B>::NT) void band_reduce_kernel(C* __re
             if (lead) { tlast = wall_clock64(); ++nstep_acc; }
 #endif
             // ---- S1: right panel (LQ of X)  ||  Z of the previous step back, this step's Z in
+            const int ncol = (int)min((int64_t)B, n - c0);                            // columns c0 .. inside the matrix
+            const int64_t rho = (t == 0) ? c00 - D : c0 - B;                          // first row of X
             if (pw) {
-                panel_wave<C, B, D>(S + xoff, 1, LD, Vs, Ts);
+                if (UG) panel_wave<C, B, D, true>(band + (rho - c0 + ku) + c0 * ldab, 1, ldm1, Vs, Ts, ncol);
+                else panel_wave<C, B, D>(S + xoff, 1, LD, Vs, Ts);
+            } else if (UG && traffic && t > 0) {
+                // this step's Z is requested here (its registers would otherwise be live across the
+                // in-band applies, which need theirs), the previous Z goes back meanwhile
+                const Blk zp = block_at(c0 - B, c0 - B), zc = block_at(c0, c0);
+#pragma unroll
+                for (int q = 0; q < PER; ++q) pre[q] = gload(zc, q, true);
+#pragma unroll
+                for (int q = 0; q < PER; ++q)
+                    if (inside(zp, q)) gstore(zp, q, S[lds0 + q * JS * LD]);
+#pragma unroll
+                for (int q = 0; q < PER; ++q)
+                    if (jj0 + q * JS < B) S[lds0 + q * JS * LD] = inside(zc, q) ? pre[q] : (C)0;
             } else if (traffic && t > 0) {
                 // two passes: LDS first (one wait for the prefetch), then all stores back to back
                 // (loads and stores complete out of order with each other, so a store between
@@ -455,7 +536,7 @@ __global__ __launch_bounds__(ReduceShape<B>::NT) void band_reduce_kernel(C* __re
 #pragma unroll
                 for (int q = 0; q < PER; ++q) {
                     if (jj0 + q * JS < B) {
-                        const int li = B + lds0 + q * JS * LD;
+                        const int li = ZO + lds0 + q * JS * LD;
                         const C old = S[li];
                         S[li] = inside(zc, q) ? pre[q] : (C)0;
                         pre[q] = old;
@@ -467,6 +548,9 @@ __global__ __launch_bounds__(ReduceShape<B>::NT) void band_reduce_kernel(C* __re
                 stores_done();
             }
             RMARK(0);
+            // UG: every wave's band stores of the previous step (and the panel's) are acknowledged
+            // before the barrier that precedes the progress store
+            if (UG) stores_done();
             lds_barrier();
             RMARK(1);
             // ---- S2: publish the previous step, wait for the predecessor's step t+2
@@ -477,12 +561,27 @@ __global__ __launch_bounds__(ReduceShape<B>::NT) void band_reduce_kernel(C* __re
             RMARK(2);
             if (failed) break;
             // ---- S3: A3 requested; block reflector onto the rows below X
-            if (traffic) {
+            if (!UG && traffic) {
                 const Blk a3 = block_at(c0, c0 + B);
 #pragma unroll
                 for (int q = 0; q < PER; ++q) pre[q] = gload(a3, q, true);
             }
-            if (applies) {
+            if (UG) {
+                // (waves 0 .. 7: the rows of Z, in LDS, four lanes per line; waves 8 .. 15: rows D .. B-1
+                // of U, in the band, eight lanes per line, two rounds; none in the first step, whose X
+                // is the sweep's own rows)
+                if (line < B) {
+                    apply_line<C, B, D>(S + line, LD, true, Vs, Ts);
+                } else if (t > 0) {
+#pragma unroll 1
+                    for (int rd = 0; rd < 2; ++rd) {
+                        const int row = D + rd * (B / 2) + (wv - 8) * 8 + (lane >> 3);
+                        apply_line_g<C, B, D, false>(band + ((c0 - B + row) - c0 + ku) + c0 * ldab, ldm1,
+                                                     row < B, ncol, Vs, Ts);
+                    }
+                    stores_done();
+                }
+            } else if (applies) {
                 const int row = xoff + D + line;
                 apply_line<C, B, D>(S + row, LD, row < 2 * B, Vs, Ts);
             }
@@ -490,8 +589,8 @@ __global__ __launch_bounds__(ReduceShape<B>::NT) void band_reduce_kernel(C* __re
             RMARK(3);
             // ---- S4: left panel (QR of Z's first D columns)  ||  U back, A3 in, next Z requested
             if (pw) {
-                panel_wave<C, B, D>(S + B, LD, 1, Vs, Ts);
-            } else if (traffic) {
+                panel_wave<C, B, D>(S + ZO, LD, 1, Vs, Ts);
+            } else if (!UG && traffic) {
                 const Blk ub = block_at(c0 - B, c0), zn = block_at(c0 + B, c0 + B), a3 = block_at(c0, c0 + B);
 #pragma unroll
                 for (int q = 0; q < PER; ++q) {
@@ -512,7 +611,21 @@ __global__ __launch_bounds__(ReduceShape<B>::NT) void band_reduce_kernel(C* __re
             lds_barrier();
             RMARK(5);
             // ---- S5: block reflector onto the other columns of Z and onto A3
-            if (applies) {
+            if (UG) {
+                // lines 0 .. B-1: columns D .. B-1 of Z, in LDS; lines B .. 2B-1: the columns of the
+                // block right of Z, in the band
+                if (line < B) {
+                    apply_line<C, B, D>(S + (D + line) * LD, 1, line < B - D, Vs, Ts);
+                } else {
+                    const int nrow = (int)min((int64_t)B, n - c0);
+#pragma unroll 1
+                    for (int rd = 0; rd < 2; ++rd) {
+                        const int64_t cg = c0 + B + rd * (B / 2) + (wv - 8) * 8 + (lane >> 3);
+                        apply_line_g<C, B, D, true>(band + (c0 - cg + ku) + cg * ldab, 1, cg < n, nrow, Vs, Ts);
+                    }
+                    stores_done();
+                }
+            } else if (applies) {
                 const bool valid = line < 2 * B - D;
                 C* base = (line < B - D) ? S + B + (D + line) * LD : S + (line - (B - D)) * LD;
                 apply_line<C, B, D>(base, 1, valid, Vs, Ts);
@@ -527,7 +640,7 @@ __global__ __launch_bounds__(ReduceShape<B>::NT) void band_reduce_kernel(C* __re
             const int lds0 = ii + jj0 * LD;
 #pragma unroll
             for (int q = 0; q < PER; ++q)
-                if (inside(zl, q)) gstore(zl, q, S[B + lds0 + q * JS * LD]);
+                if (inside(zl, q)) gstore(zl, q, S[ZO + lds0 + q * JS * LD]);
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
         }
         __syncthreads();
@@ -554,9 +667,13 @@ template <typename C, int B>
 int launch_band_reduce(int64_t n, C* band, int64_t ldab, int* ctrl, hipStream_t s)
 {
     constexpr int D = 8;
-    constexpr size_t smem = sizeof(C) * (size_t)(((B * (2 * B + 1) + 3) & ~3) + (B + 4) * D + D * D);
-    static_assert(smem <= 160 * 1024, "block pair does not fit in LDS");
-    auto kern = band_reduce_kernel<C, B, D>;
+    // two blocks in LDS where they fit, otherwise only the diagonal block
+    constexpr bool UG = sizeof(C) * (size_t)(((B * (2 * B + 1) + 3) & ~3) + (B + 4) * D + D * D) > 160 * 1024;
+    constexpr int LD = UG ? B + 1 : 2 * B + 1;
+    constexpr size_t smem = sizeof(C) * (size_t)(((B * LD + 3) & ~3) + (B + 4) * D + D * D);
+    static_assert(smem <= 160 * 1024, "diagonal block does not fit in LDS");
+    static_assert(!UG || ReduceShape<B>::NT == 1024, "one-block form: waves 0-7 on LDS lines, waves 8-15 on band lines");
+    auto kern = band_reduce_kernel<C, B, D, UG>;
     static bool attr_set = false;
     if (!attr_set) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -580,8 +697,8 @@ size_t band_reduce_workspace_bytes(int64_t n) { return (size_t)((64 + n / 8 + 8)
 
 bool band_reduce_supported(int nb, size_t elem_size)
 {
-    if (nb != 32 && nb != 64 && nb != 128) return false;
-    return elem_size * ((size_t)nb * (2 * nb + 1) + (size_t)(nb + 4) * 8 + 64 + 4) <= 160 * 1024;
+    (void)elem_size;
+    return nb == 32 || nb == 64 || nb == 128;
 }
 
 template <typename C>
@@ -589,9 +706,7 @@ int run_band_reduce(int64_t n, int nb, C* band, int64_t ldab, int* ctrl, hipStre
 {
     if (nb == 32) return launch_band_reduce<C, 32>(n, band, ldab, ctrl, s);
     if (nb == 64) return launch_band_reduce<C, 64>(n, band, ldab, ctrl, s);
-    if constexpr (sizeof(C) == 4) {
-        if (nb == 128) return launch_band_reduce<C, 128>(n, band, ldab, ctrl, s);
-    }
+    if (nb == 128) return launch_band_reduce<C, 128>(n, band, ldab, ctrl, s);
     return SVB_ERR_UNSUPPORTED;
 }
 

@@ -134,7 +134,8 @@ def test_stage1_band_preserves_singular_values():
                                          ("f64", 9, 8), ("f64", 130, 8), ("f32", 1000, 8), ("f64", 1337, 8),
                                          ("f32", 5000, 8),
                                          ("f64", 777, 32), ("f32", 2000, 32), ("f32", 1500, 64), ("f64", 64, 64),
-                                         ("f32", 3001, 128), ("f32", 129, 128), ("f64", 41, 32)])
+                                         ("f32", 3001, 128), ("f32", 129, 128), ("f64", 41, 32),
+                                         ("f64", 1111, 128), ("f64", 257, 128), ("f64", 640, 128)])
 def test_stage2_on_random_band(dtype, n, nb):
     # random upper band input: Frobenius norm kept, bdsvals(d, e) = oracle(band as dense)
     npdt = workloads.NP_DTYPE[dtype]
