@@ -158,24 +158,25 @@ def main():
                     traffic=None, launches=pk["launches"],
                     avg_launch_ms=pk["seconds"] / max(pk["launches"], 1) * 1e3)
     # HBM bytes per launch from the committed rocprofv3 --pmc summary of this workload, if there is one
+    # (first-tree-level launches of the dominant kernel: the ones whose flops and bytes are credited)
     tfile = os.path.join(ROOT, "profiles", f"hbm_traffic_{args.config}_{n}_{dtype}_nb{nb}.json")
+    roofline_stage2_traffic = None
     if os.path.exists(tfile):
         tr = json.load(open(tfile))
         kname = {"k1": "k1_mfma", "k2": "k2_mfma", "fused": "update_fused_kernel"}[dom]
-        rd = sum(v["read_GB"] for k, v in tr.items() if k.startswith(kname))
-        wr = sum(v["write_GB"] for k, v in tr.items() if k.startswith(kname))
-        nl = sum(v["launches"] for k, v in tr.items() if k.startswith(kname))
+        lvl0 = {k: v for k, v in tr.items() if k.startswith(kname) and not k.rstrip(">").endswith("true")} \
+            if dom == "fused" else {k: v for k, v in tr.items() if k.startswith(kname)}
+        rd = sum(v["read_GB"] for v in lvl0.values())
+        wr = sum(v["write_GB"] for v in lvl0.values())
+        nl = sum(v["launches"] for v in lvl0.values())
         if nl:
+            credited_launches = 2 * (n // nb - 1) * args.steps     # half-sweeps with a trailing matrix
             roofline["traffic"] = (rd + wr) * 1e9 / nl
-            roofline["traffic_unit"] = "HBM bytes per launch (FETCH_SIZE + WRITE_SIZE, calibrated)"
-            roofline["algorithmic_bytes_per_launch"] = pk["bytes"] / max(pk["launches"], 1)
-        chk = [v for k, v in tr.items() if k.startswith("chase_persistent")]
+            roofline["traffic_unit"] = "HBM bytes per first-level launch (FETCH_SIZE + WRITE_SIZE, calibrated)"
+            roofline["algorithmic_bytes_per_launch"] = pk["bytes"] / max(credited_launches, 1)
+        chk = [v for k, v in tr.items() if k.startswith(("band_reduce_kernel", "chase_narrow_kernel", "chase_persistent"))]
         if chk:
-            roofline_stage2_traffic = (chk[0]["read_GB"] + chk[0]["write_GB"]) * 1e9
-        else:
-            roofline_stage2_traffic = None
-    else:
-        roofline_stage2_traffic = None
+            roofline_stage2_traffic = sum(v["read_GB"] + v["write_GB"] for v in chk) * 1e9
     upd_s = prof["k1"]["seconds"] + prof["k2"]["seconds"] + prof["fused"]["seconds"]
     ch = prof["chase"]
     ch_gbs = ch["bytes"] / ch["seconds"] / 1e9 if ch["seconds"] > 0 else 0.0

@@ -31,14 +31,25 @@ __device__ __forceinline__ float newton_rcp(float x)
     const float r = __builtin_amdgcn_rcpf(x);
     return fmaf(r, fmaf(-x, r, 1.0f), r);
 }
-__device__ __forceinline__ double newton_rcp(double x) { return 1.0 / x; }
+__device__ __forceinline__ double newton_rcp(double x)
+{
+    double r = __builtin_amdgcn_rcp(x);
+    r = fma(r, fma(-x, r, 1.0), r);
+    return fma(r, fma(-x, r, 1.0), r);
+}
 __device__ __forceinline__ float newton_sqrt(float x)   // x > 0, normal
 {
     const float r = __builtin_amdgcn_rsqf(x);
     const float s = x * r;
     return fmaf(fmaf(-s, s, x), 0.5f * r, s);
 }
-__device__ __forceinline__ double newton_sqrt(double x) { return sqrt(x); }
+__device__ __forceinline__ double newton_sqrt(double x)   // x > 0, normal
+{
+    const double r = __builtin_amdgcn_rsq(x), h = 0.5 * r;
+    double s = x * r;
+    s = fma(fma(-s, s, x), h, s);
+    return fma(fma(-s, s, x), h, s);
+}
 
 // Geometry of one half-sweep's panel tree (Section 3.1: GEQRT on the first
 // tile, then the tiles below are annihilated; here the tiles of a panel are
