@@ -6,7 +6,7 @@
 //
 // Same idea, with the domain's reflectors in compact-WY form (Y = V T) and the
 // products on MFMA: a workgroup owns the block C_d[:, strip] (all rows of one
-// panel domain, 64 columns of the trailing matrix), each of its 4 waves keeps
+// panel domain, 64 columns of the trailing matrix; 128 for f64 at nb = 128), each of its waves keeps
 // 16 of those columns in accumulator registers for the whole kernel:
 //     W  = Y_d^T C      (contraction over the rows: C's registers are the B operand)
 //     C -= V_d W        (W's registers are the B operand, C's the accumulators)
@@ -25,6 +25,10 @@ namespace svb {
 namespace {
 
 template <typename C, int NB> struct FusedGeom {
+    // waves per workgroup (16 columns each): eight where the block and W leave room for only one
+    // workgroup per compute unit (f64, nb = 128), so that a SIMD still has two waves to switch between
+    static constexpr int NWV = (sizeof(C) == 8 && NB == 128) ? 8 : 4;
+    static constexpr int NT = NWV * 64, SW = NWV * 16;   // threads, columns of a strip
     static constexpr int RC = 32;                         // rows of Y / V per LDS slice
     static constexpr int NV = Frag<C>::NV;
     static constexpr int MT = NB / 16;                    // 16-row tiles of W
@@ -33,8 +37,8 @@ template <typename C, int NB> struct FusedGeom {
     static constexpr int LDR = sizeof(C) == 4 ? RC + 4 : RC + 1;   // Y slice: [column][row]
     static constexpr int LDC = sizeof(C) == 4 ? NB + 4 : NB + 1;   // V slice: [row][column]
     static constexpr int BUF = NB * LDR > RC * LDC ? NB * LDR : RC * LDC;
-    static constexpr int NLD = RC * NB / NV / 256;        // 16-byte vectors per thread and slice
-    static_assert(NLD >= 1, "slice too small for 256 threads");
+    static constexpr int NLD = RC * NB / NV / NT;         // 16-byte vectors per thread and slice
+    static_assert(NLD >= 1, "slice too small for the workgroup");
     static constexpr size_t kSmemBytes = 2 * (size_t)BUF * sizeof(C);
 };
 
@@ -57,7 +61,7 @@ __device__ unsigned long long svb_fused_timing[8];
 // first), so in every NB-row chunk of V and of Y = V T the 16 x 16 blocks below the block
 // diagonal are exactly zero and their products are skipped.
 template <typename T, typename C, int NB, int HT, bool LQ, bool TRI>
-__global__ __launch_bounds__(256, (sizeof(C) == 8 && NB == 128) ? 1 : 2) void update_fused_kernel(T* __restrict__ Cb, int64_t lda, int64_t qlen,
+__global__ __launch_bounds__((FusedGeom<C, NB>::NT), (sizeof(C) == 8 && NB == 128) ? 1 : 2) void update_fused_kernel(T* __restrict__ Cb, int64_t lda, int64_t qlen,
                                                            const C* __restrict__ V, const C* __restrict__ Y,
                                                            int64_t ldp, int chunks, int g, int64_t stride,
                                                            int strips, int total)
@@ -84,8 +88,8 @@ __global__ __launch_bounds__(256, (sizeof(C) == 8 && NB == 128) ? 1 : 2) void up
     const int nck = nch * NB / RC;     // slices of this domain
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int i = lane & 15, gq = lane >> 4;
-    const int64_t q = (int64_t)strip * 64 + wave * 16 + i;
-    const bool active = (int64_t)strip * 64 + wave * 16 < qlen;   // qlen is a multiple of 16
+    const int64_t q = (int64_t)strip * G::SW + wave * 16 + i;
+    const bool active = (int64_t)strip * G::SW + wave * 16 < qlen;   // qlen is a multiple of 16
     const int64_t prow0 = (int64_t)d * g * NB;                    // first row of the domain in V / Y
 
     // global p index of tile t: chunk (16t / NB) of the domain, offset (16t % NB) inside it
@@ -115,7 +119,7 @@ __global__ __launch_bounds__(256, (sizeof(C) == 8 && NB == 128) ? 1 : 2) void up
     auto slice_ld = [&](const C* __restrict__ src, int ck) {
 #pragma unroll
         for (int e = 0; e < NLD; ++e) {
-            const int idx = tid + e * 256;
+            const int idx = tid + e * G::NT;
             const int rv = idx % VPC, col = idx / VPC;
             VecIO<C, C>::ld(&src[(prow0 + (int64_t)ck * RC + rv * NV) + (int64_t)col * ldp], sreg[e]);
         }
@@ -123,7 +127,7 @@ __global__ __launch_bounds__(256, (sizeof(C) == 8 && NB == 128) ? 1 : 2) void up
     auto slice_st_y = [&](C* buf) {   // [column][row]
 #pragma unroll
         for (int e = 0; e < NLD; ++e) {
-            const int idx = tid + e * 256;
+            const int idx = tid + e * G::NT;
             const int rv = idx % VPC, col = idx / VPC;
             if constexpr (sizeof(C) == 4) {
                 VecIO<C, C>::st(&buf[col * LDR + rv * NV], sreg[e]);
@@ -136,7 +140,7 @@ __global__ __launch_bounds__(256, (sizeof(C) == 8 && NB == 128) ? 1 : 2) void up
     auto slice_st_v = [&](C* buf) {   // [row][column]
 #pragma unroll
         for (int e = 0; e < NLD; ++e) {
-            const int idx = tid + e * 256;
+            const int idx = tid + e * G::NT;
             const int rv = idx % VPC, col = idx / VPC;
 #pragma unroll
             for (int j = 0; j < NV; ++j) buf[(rv * NV + j) * LDC + col] = sreg[e][j];
@@ -183,7 +187,7 @@ __global__ __launch_bounds__(256, (sizeof(C) == 8 && NB == 128) ? 1 : 2) void up
                         const int t = ck * (RC / 16) + tt;
                         const int rb = TRI ? (16 * t % NB) / 16 : 0;   // first non-zero block column of this tile
                         // four tiles of W at a time: consecutive MFMAs are independent
-                        constexpr int MG = MT < 4 ? MT : 4;
+                        constexpr int MG = sizeof(C) == 8 ? 2 : (MT < 4 ? MT : 4);
 #pragma unroll
                         for (int m0 = 0; m0 < MT; m0 += MG) {
                             C a[MG][4];
@@ -251,14 +255,14 @@ static void launch_fused(T* Cb, int64_t lda, int64_t qlen, const C* V, const C* 
         attr_set = true;
     }
     const int domains = (chunks + g - 1) / g;
-    const int strips = (int)((qlen + 63) / 64);
+    const int strips = (int)((qlen + G::SW - 1) / G::SW);
     const int total = domains * strips;
     const int per = (total + 7) / 8;
     // both products: 2 * rows * NB * cols flops each; the block is read once and written once
     const double fl = credited ? 4.0 * chunks * NB * (double)NB * (double)qlen : 0.0;
     const double by = credited ? 2.0 * chunks * NB * (double)qlen * sizeof(T) : 0.0;
     prof_begin(SVB_PROF_FUSED, s, fl, by);
-    hipLaunchKernelGGL(kern, dim3((unsigned)(per * 8)), dim3(256), G::kSmemBytes, s, Cb, lda, qlen, V, Y, ldp,
+    hipLaunchKernelGGL(kern, dim3((unsigned)(per * 8)), dim3(G::NT), G::kSmemBytes, s, Cb, lda, qlen, V, Y, ldp,
                        chunks, g, stride, strips, total);
     prof_end(s);
 }
