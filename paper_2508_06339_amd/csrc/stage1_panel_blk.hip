@@ -309,6 +309,34 @@ __global__ __launch_bounds__(NB * 4) void panel_qr_blk_kernel(C* __restrict__ P,
                     Tbb[i * LDT + k] = trow[k];
                 }
             }
+        } else {
+            // P1 = V_b^T C_w over rows 16b ..: C_w's registers are the B operand
+            acc_t pa, pb;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) { pa[r] = 0; pb[r] = 0; }
+#pragma unroll
+            for (int t = 0; t < HT; ++t) {
+                if (t >= b && t < ntile) {
+                    C o[4];
+                    F::ld4(&Bs[i * LDB + 16 * t], gq, o);
+                    if (t & 1) {
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) pb = F::mma(o[r], c[t][r], pb);
+                    } else {
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) pa = F::mma(o[r], c[t][r], pa);
+                    }
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) p1[r] = pa[r] + pb[r];
+        }
+        __syncthreads();
+        PT_MARK(5);
+
+        // ---- right of the block: C_w -= V_b (T_b^T P1);  left of it: Z_w = (V_w^T V_b) T_b;
+        //      the owner meanwhile reloads its registers
+        if (wave == b) {
             // registers: tile b <- R block, tiles below <- V; V goes to global memory on the way
 #pragma unroll
             for (int t = 0; t < HT; ++t) {
@@ -335,32 +363,6 @@ __global__ __launch_bounds__(NB * 4) void panel_qr_blk_kernel(C* __restrict__ P,
                 }
             }
         } else {
-            // P1 = V_b^T C_w over rows 16b ..: C_w's registers are the B operand
-            acc_t pa, pb;
-#pragma unroll
-            for (int r = 0; r < 4; ++r) { pa[r] = 0; pb[r] = 0; }
-#pragma unroll
-            for (int t = 0; t < HT; ++t) {
-                if (t >= b && t < ntile) {
-                    C o[4];
-                    F::ld4(&Bs[i * LDB + 16 * t], gq, o);
-                    if (t & 1) {
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) pb = F::mma(o[r], c[t][r], pb);
-                    } else {
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) pa = F::mma(o[r], c[t][r], pa);
-                    }
-                }
-            }
-#pragma unroll
-            for (int r = 0; r < 4; ++r) p1[r] = pa[r] + pb[r];
-        }
-        __syncthreads();
-        PT_MARK(5);
-
-        // ---- right of the block: C_w -= V_b (T_b^T P1);  left of it: Z_w = (V_w^T V_b) T_b
-        if (wave != b) {
             C tb[4];
             F::ld4(&Tb[i * LDT], gq, tb);   // T_b[roff(r, gq)][i]
             if (wave > b) {
