@@ -198,19 +198,41 @@ struct Profiler {
     }
 } g_prof;
 
-// Helper stream and events for the look-ahead (created once per process).
+// Streams and events for the look-ahead (created once per process).  Stage 1 runs on two
+// internal streams forked from the caller's stream and joined back to it: `m` carries the
+// chain panel -> first part of the update -> next panel, `h` the deferred part of the update.
+// `h` is confined to a subset of the compute units (SVB_HELPER_MASK_BITS of them, default 224
+// of 256), so that the few workgroups of a panel kernel, each of which needs a compute unit
+// of its own, find one free while the deferred update is running.  (A stream with a CU mask
+// is an ordinary blocking stream: it would serialise with the NULL stream, which is why the
+// chain does not run on the caller's stream itself.)
 struct Lookahead {
-    hipStream_t h = nullptr;
-    hipEvent_t crit[2] = {nullptr, nullptr}, rest[2] = {nullptr, nullptr};
-    bool ok = false;
+    hipStream_t m = nullptr, h = nullptr;
+    hipEvent_t crit[2] = {nullptr, nullptr}, rest[2] = {nullptr, nullptr}, fork = nullptr, join = nullptr;
+    bool ok = false, tried = false;
     bool init()
     {
-        if (ok) return true;
-        if (hipStreamCreateWithFlags(&h, hipStreamNonBlocking) != hipSuccess) return false;
+        if (tried) return ok;
+        tried = true;
+        if (hipStreamCreateWithFlags(&m, hipStreamNonBlocking) != hipSuccess) return false;
+        const int bits = env_int("SVB_HELPER_MASK_BITS", 224);
+        if (bits > 0 && bits < 256) {
+            uint32_t mask[8];
+            for (int w = 0; w < 8; ++w) {
+                const int nb = bits - 32 * w;
+                mask[w] = nb >= 32 ? 0xffffffffu : (nb <= 0 ? 0u : ((1u << nb) - 1u));
+            }
+            if (hipExtStreamCreateWithCUMask(&h, 8, mask) != hipSuccess) return false;
+        } else if (hipStreamCreateWithFlags(&h, hipStreamNonBlocking) != hipSuccess) {
+            return false;
+        }
         for (int i = 0; i < 2; ++i)
             if (hipEventCreateWithFlags(&crit[i], hipEventDisableTiming) != hipSuccess ||
                 hipEventCreateWithFlags(&rest[i], hipEventDisableTiming) != hipSuccess)
                 return false;
+        if (hipEventCreateWithFlags(&fork, hipEventDisableTiming) != hipSuccess ||
+            hipEventCreateWithFlags(&join, hipEventDisableTiming) != hipSuccess)
+            return false;
         ok = true;
         return true;
     }
@@ -223,7 +245,7 @@ struct Lookahead {
 // The next half-sweep's K1 waits for it.
 template <typename T, typename C>
 int ge2gb_impl(int64_t n, T* A, int64_t lda, int nb, C* band, int64_t ldab, unsigned char* work,
-               const Carve& cv, hipStream_t s)
+               const Carve& cv, hipStream_t caller)
 {
     int* err = reinterpret_cast<int*>(work + cv.off_err);
     const int g = domain_chunks(sizeof(C) == 8 ? SVB_F64 : SVB_F32, nb);
@@ -231,10 +253,18 @@ int ge2gb_impl(int64_t n, T* A, int64_t lda, int nb, C* band, int64_t ldab, unsi
     // the kernel's registers), 1 = two MFMA kernels with look-ahead, 0 = plain FMA kernels
     int impl = env_int("SVB_UPDATE_IMPL", 2);
     if (impl == 2 && g * nb > fused_update_rows<C>()) impl = 1;
-    const bool la = impl == 1 && env_int("SVB_LOOKAHEAD", 1) != 0 && g_la.init();
+    const bool la = impl != 0 && env_int("SVB_LOOKAHEAD", 1) != 0 && g_la.init();
     const int64_t N = n / nb;
     Level lv[kMaxLevels];
     int64_t woff[kMaxLevels];
+    // with look-ahead the work runs on the internal streams, forked from the caller's here and
+    // joined back at the end
+    hipStream_t s = caller;
+    if (la) {
+        s = g_la.m;
+        (void)hipEventRecord(g_la.fork, caller);
+        (void)hipStreamWaitEvent(s, g_la.fork, 0);
+    }
 
     launch_band_clear<C>(band, ldab, n, s);
     int hs = 0;            // half-sweep counter: selects the buffer set and the events
@@ -284,10 +314,24 @@ int ge2gb_impl(int64_t n, T* A, int64_t lda, int nb, C* band, int64_t ldab, unsi
                 }
                 const bool defer = la && any_rest;
                 if (impl == 2) {
+                    // one pass per level; with look-ahead split in two: the part the next panel
+                    // waits for here, the rest on the helper stream under that panel
                     for (int L = 0; L < nl; ++L)
                         launch_update_fused<T, C>(nb, lq, Cb, lda, qlen, Vb + lv[L].poff, Yb + lv[L].poff,
-                                                  lv[L].ldp, lv[L].chunks, g, lv[L].stride, L > 0, L == 0, s);
-                } else
+                                                  lv[L].ldp, lv[L].chunks, g, lv[L].stride, L > 0, defer ? 1 : 0,
+                                                  Wb + woff[L], L == 0, s);
+                    if (defer) {
+                        (void)hipEventRecord(g_la.crit[set], s);
+                        (void)hipStreamWaitEvent(g_la.h, g_la.crit[set], 0);
+                        for (int L = 0; L < nl; ++L)
+                            if (lv[L].chunks > lv[L].domains)
+                                launch_update_fused<T, C>(nb, lq, Cb, lda, qlen, Vb + lv[L].poff, Yb + lv[L].poff,
+                                                          lv[L].ldp, lv[L].chunks, g, lv[L].stride, L > 0, 2,
+                                                          Wb + woff[L], L == 0, g_la.h);
+                        (void)hipEventRecord(g_la.rest[set], g_la.h);
+                        pending = true;
+                    }
+                } else {
                 for (int L = 0; L < nl; ++L)
                     launch_update<T, C>(nb, lq, Cb, lda, qlen, Vb + lv[L].poff, Yb + lv[L].poff, lv[L].ldp,
                                         lv[L].chunks, g, lv[L].stride, Wb + woff[L], impl, L == 0, defer ? 1 : 0, s);
@@ -300,11 +344,16 @@ int ge2gb_impl(int64_t n, T* A, int64_t lda, int nb, C* band, int64_t ldab, unsi
                     (void)hipEventRecord(g_la.rest[set], g_la.h);
                     pending = true;
                 }
+                }
             }
             ++hs;
         }
     }
     if (pending) (void)hipStreamWaitEvent(s, g_la.rest[(hs - 1) & 1], 0);
+    if (la) {
+        (void)hipEventRecord(g_la.join, s);
+        (void)hipStreamWaitEvent(caller, g_la.join, 0);
+    }
     return hipGetLastError() == hipSuccess ? SVB_OK : SVB_ERR_DEVICE;
 }
 

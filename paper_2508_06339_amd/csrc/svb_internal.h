@@ -105,9 +105,12 @@ void launch_update(int nb, bool lq, T* Cbase, int64_t lda, int64_t qlen,
 // The same update in one pass over the trailing matrix (W stays in registers); domains of
 // at most fused_update_rows<C>() rows.  tri: the panel is a stack of upper triangular factors
 // (tree levels above the first), whose structural zeros in V and Y are skipped.
+// mode 0: the whole update; 1: W formed and stored in W, first chunk of every domain finished;
+// 2: the other chunks finished from the stored W (may run beside the next panel).
 template <typename T, typename C>
 void launch_update_fused(int nb, bool lq, T* Cbase, int64_t lda, int64_t qlen, const C* V, const C* Y,
-                         int64_t ldp, int chunks, int g, int64_t stride, bool tri, bool credited, hipStream_t s);
+                         int64_t ldp, int chunks, int g, int64_t stride, bool tri, int mode, C* W,
+                         bool credited, hipStream_t s);
 template <typename C> int fused_update_rows();
 
 // per-kernel timing hooks (no-ops unless profiling is enabled)
