@@ -14,9 +14,11 @@
  *   - The caller owns every buffer.  The library allocates no device memory;
  *     scratch space comes in through work_dev / work_bytes
  *     (size from svb_workspace_bytes).
- *   - GPU work is enqueued on the HIP stream passed as `stream` (a hipStream_t
- *     cast to void*, NULL = the default stream) and on one internal helper
- *     stream that is forked from and joined back to it with events.
+ *   - GPU work is ordered after what the HIP stream passed as `stream` (a
+ *     hipStream_t cast to void*, NULL = the default stream) holds at the call,
+ *     and that stream waits for it: stage 1 runs on two internal streams that
+ *     are forked from and joined back to `stream` with events (the second one
+ *     restricted to a subset of the compute units), the rest on `stream`.
  *   - Return value: an svb_status.  On SVB_ERR_ARG / SVB_ERR_UNSUPPORTED /
  *     SVB_ERR_WORKSPACE nothing has been read or written.
  *   - Supported in this version: m == n, n a positive multiple of nb,

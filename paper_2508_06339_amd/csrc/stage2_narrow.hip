@@ -351,7 +351,7 @@ template <typename C>
 int run_chase_narrow(int64_t n, C* band, int64_t ldab, int64_t ku, int* ctrl, hipStream_t s)
 {
     constexpr int D = 8;
-    constexpr int NW = sizeof(C) == 8 ? 16 : 32;   // sweeps per bundle (four per wave)
+    constexpr int NW = sizeof(C) == 8 ? 16 : 48;   // sweeps per bundle (four per wave): as many as the window holds
     constexpr int WC = sizeof(C) == 8 ? 512 : 1024;
     constexpr int GS = 8;   // super-steps per group (chunk = GS*D columns)
     if (n < 3) return SVB_OK;
