@@ -206,6 +206,7 @@ struct Profiler {
 // of its own, find one free while the deferred update is running.  (A stream with a CU mask
 // is an ordinary blocking stream: it would serialise with the NULL stream, which is why the
 // chain does not run on the caller's stream itself.)
+void g_la_release();
 struct Lookahead {
     hipStream_t m = nullptr, h = nullptr;
     hipEvent_t crit[2] = {nullptr, nullptr}, rest[2] = {nullptr, nullptr}, fork = nullptr, join = nullptr;
@@ -234,9 +235,28 @@ struct Lookahead {
             hipEventCreateWithFlags(&join, hipEventDisableTiming) != hipSuccess)
             return false;
         ok = true;
+        // released while the HIP runtime is still up (handlers registered later run earlier):
+        // a CU-masked stream left to process teardown has crashed tools that hook the runtime
+        std::atexit([] { g_la_release(); });
         return true;
     }
+    void release()
+    {
+        if (!ok) return;
+        ok = false;
+        (void)hipStreamSynchronize(h);
+        (void)hipStreamSynchronize(m);
+        for (int i = 0; i < 2; ++i) {
+            (void)hipEventDestroy(crit[i]);
+            (void)hipEventDestroy(rest[i]);
+        }
+        (void)hipEventDestroy(fork);
+        (void)hipEventDestroy(join);
+        (void)hipStreamDestroy(h);
+        (void)hipStreamDestroy(m);
+    }
 } g_la;
+void g_la_release() { g_la.release(); }
 
 // Stage 1 driver.  Per half-sweep: panel tree on the caller's stream; then, level by
 // level, K1 and the part of K2 that the next level and the next panel read (the first
