@@ -164,16 +164,23 @@ def main():
     if os.path.exists(tfile):
         tr = json.load(open(tfile))
         kname = {"k1": "k1_mfma", "k2": "k2_mfma", "fused": "update_fused_kernel"}[dom]
-        lvl0 = {k: v for k, v in tr.items() if k.startswith(kname) and not k.rstrip(">").endswith("true")} \
-            if dom == "fused" else {k: v for k, v in tr.items() if k.startswith(kname)}
+
+        def first_level(k):
+            # update_fused_kernel<T, C, NB, HT, LQ, TRI, MODE>: TRI marks the tree levels above the first
+            if dom != "fused":
+                return True
+            targs = [a.strip() for a in k[k.index("<") + 1:k.rindex(">")].split(",")]
+            return len(targs) < 6 or targs[5] != "true"
+
+        lvl0 = {k: v for k, v in tr.items() if k.startswith(kname) and first_level(k)}
         rd = sum(v["read_GB"] for v in lvl0.values())
         wr = sum(v["write_GB"] for v in lvl0.values())
-        nl = sum(v["launches"] for v in lvl0.values())
-        if nl:
-            credited_launches = 2 * (n // nb - 1) * args.steps     # half-sweeps with a trailing matrix
-            roofline["traffic"] = (rd + wr) * 1e9 / nl
-            roofline["traffic_unit"] = "HBM bytes per first-level launch (FETCH_SIZE + WRITE_SIZE, calibrated)"
-            roofline["algorithmic_bytes_per_launch"] = pk["bytes"] / max(credited_launches, 1)
+        if lvl0:
+            halfsweeps = 2 * (n // nb - 1)                    # half-sweeps with a trailing matrix, one call
+            roofline["traffic"] = (rd + wr) * 1e9 / halfsweeps
+            roofline["traffic_unit"] = ("HBM bytes per half-sweep, first tree level, all its launches "
+                                        "(FETCH_SIZE + WRITE_SIZE, calibrated)")
+            roofline["algorithmic_bytes_per_halfsweep"] = pk["bytes"] / (halfsweeps * args.steps)
         chk = [v for k, v in tr.items() if k.startswith(("band_reduce_kernel", "chase_narrow_kernel", "chase_persistent"))]
         if chk:
             roofline_stage2_traffic = sum(v["read_GB"] + v["write_GB"] for v in chk) * 1e9
