@@ -25,6 +25,7 @@
 //
 // Packed band: entry (i,j) at band[(i - j + ku) + j*ldab], ku = 2B-1, ldab >= 3B.
 #include "svb_internal.h"
+#include "mfma_frag.h"
 
 namespace svb {
 
@@ -312,6 +313,63 @@ __device__ __forceinline__ void apply_line(C* base, int es, bool valid, const C*
     }
 }
 
+// The block reflector (Vs, Ts) applied to SIXTEEN lines at once on MFMA, by one wave: element e
+// of line n of the tile lives at base[e*es + n*ls] (LDS), e < B, lines n >= nvalid are left
+// alone.  With Y(e, n) the tile's elements:
+//     P = V^T Y  (16 x 16, rows 8.. zero),  Z = -T^T P,  Y += V Z
+// (line <- line - ((line . V) T) V^T for every line, the expression of apply_line).  The
+// first product contracts over e with Y as the B operand straight from LDS; the second and
+// third use the accumulator registers of the previous one as their B operand (Frag).
+template <typename C, int B, int D>
+__device__ __forceinline__ void apply_tile(C* base, int es, int ls, int nvalid, const C* Vs, const C* Ts)
+{
+    using F = Frag<C>;
+    typedef typename F::acc_t acc_t;
+    const int lane = threadIdx.x & 63, i = lane & 15, gq = lane >> 4;
+    const bool valid = i < nvalid;
+    C* mine = base + i * ls;   // this lane's line (B / accumulator operands)
+    acc_t p0, p1;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) { p0[r] = 0; p1[r] = 0; }
+#pragma unroll 8
+    for (int s4 = 0; s4 < B / 4; ++s4) {
+        const int k = 4 * s4 + gq;
+        const C a = (i < D) ? Vs[vidx<B, D>(k) + i] : (C)0;   // A[m = i][k] = V(k, i)
+        const C b = valid ? mine[k * es] : (C)0;              // B[k][n = i] = Y(k, i)
+        if (s4 & 1) p1 = F::mma(a, b, p1);
+        else p0 = F::mma(a, b, p0);
+    }
+    acc_t z;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) { p0[r] += p1[r]; z[r] = 0; }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int kk = F::roff(r, gq);
+        const C a = (i < D && kk < D) ? Ts[kk * D + i] : (C)0;   // A[m = i][kk] = T(kk, i)
+        z = F::mma(a, p0[r], z);
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) z[r] = -z[r];
+#pragma unroll 2
+    for (int e0 = 0; e0 < B; e0 += 16) {
+        acc_t y;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) y[r] = valid ? mine[(e0 + F::roff(r, gq)) * es] : (C)0;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int j = F::roff(r, gq);
+            if (F::roff(r, 0) < D) {   // some lane group still has a reflector index below D in this slot
+                const C a = (j < D) ? Vs[vidx<B, D>(e0 + i) + j] : (C)0;   // A[m = i][j] = V(e0 + i, j)
+                y = F::mma(a, z[r], y);
+            }
+        }
+        if (valid) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) mine[(e0 + F::roff(r, gq)) * es] = y[r];
+        }
+    }
+}
+
 // The same for a line of the packed band in device memory (device-scope accesses): elements
 // base[e*es], e < ne, eight lanes per line (an eighth of the line each, held in registers
 // between the two passes).  With IL the eight lanes own interleaved elements (e = 8*jj + p),
@@ -399,6 +457,9 @@ __global__ __launch_bounds__(ReduceShape<B>::NT) void band_reduce_kernel(C* __re
     using SH = ReduceShape<B>;
     constexpr int LD = UG ? B + 1 : 2 * B + 1, PER = SH::PER, JS = SH::JS;
     constexpr int ZO = UG ? 0 : B;                // first row of Z inside S
+    // block reflectors onto LDS lines: sixteen lines per wave on MFMA in f64 (half the FMA rate and
+    // twice the LDS traffic of f32 make the line-per-quad form slow there), a line per quad in f32
+    constexpr bool kTile = sizeof(C) == 8;
     extern __shared__ __align__(16) unsigned char smem_raw[];
     C* S = reinterpret_cast<C*>(smem_raw);        // rows c0-B .. c0+B-1 (UG: c0 ..), columns c0 .. c0+B-1: S[row + col*LD]
     C* Vs = S + ((B * LD + 3) & ~3);              // (B + 4) * D
@@ -571,7 +632,8 @@ __global__ __launch_bounds__(ReduceShape<B>::NT) void band_reduce_kernel(C* __re
                 // of U, in the band, eight lanes per line, two rounds; none in the first step, whose X
                 // is the sweep's own rows)
                 if (line < B) {
-                    apply_line<C, B, D>(S + line, LD, true, Vs, Ts);
+                    if (kTile) apply_tile<C, B, D>(S + 16 * wv, LD, 1, 16, Vs, Ts);
+                    else apply_line<C, B, D>(S + line, LD, true, Vs, Ts);
                 } else if (t > 0) {
 #pragma unroll 1
                     for (int rd = 0; rd < 2; ++rd) {
@@ -581,6 +643,10 @@ __global__ __launch_bounds__(ReduceShape<B>::NT) void band_reduce_kernel(C* __re
                     }
                     stores_done();
                 }
+            } else if (applies && kTile) {
+                // sixteen rows per wave, from row xoff + D on
+                const int row0 = xoff + D + 16 * wv;
+                if (row0 < 2 * B) apply_tile<C, B, D>(S + row0, LD, 1, 2 * B - row0, Vs, Ts);
             } else if (applies) {
                 const int row = xoff + D + line;
                 apply_line<C, B, D>(S + row, LD, row < 2 * B, Vs, Ts);
@@ -615,7 +681,8 @@ __global__ __launch_bounds__(ReduceShape<B>::NT) void band_reduce_kernel(C* __re
                 // lines 0 .. B-1: columns D .. B-1 of Z, in LDS; lines B .. 2B-1: the columns of the
                 // block right of Z, in the band
                 if (line < B) {
-                    apply_line<C, B, D>(S + (D + line) * LD, 1, line < B - D, Vs, Ts);
+                    if (kTile) apply_tile<C, B, D>(S + (D + 16 * wv) * LD, 1, LD, B - D - 16 * wv, Vs, Ts);
+                    else apply_line<C, B, D>(S + (D + line) * LD, 1, line < B - D, Vs, Ts);
                 } else {
                     const int nrow = (int)min((int64_t)B, n - c0);
 #pragma unroll 1
@@ -625,6 +692,11 @@ __global__ __launch_bounds__(ReduceShape<B>::NT) void band_reduce_kernel(C* __re
                     }
                     stores_done();
                 }
+            } else if (applies && kTile) {
+                // waves 0 .. B/16-1: sixteen columns of Z each, from column D on; the others:
+                // sixteen columns of the block right of Z each
+                if (wv < B / 16) apply_tile<C, B, D>(S + B + (D + 16 * wv) * LD, 1, LD, B - D - 16 * wv, Vs, Ts);
+                else apply_tile<C, B, D>(S + 16 * (wv - B / 16) * LD, 1, LD, 16, Vs, Ts);
             } else if (applies) {
                 const bool valid = line < 2 * B - D;
                 C* base = (line < B - D) ? S + B + (D + line) * LD : S + (line - (B - D)) * LD;
