@@ -434,17 +434,26 @@ static void launch_panel_y(const C* V, C* Y, const C* Tws, int64_t ldp, int64_t 
                        Tws, ldp, rows, g);
 }
 
-template <typename C>
+template <typename C> bool panel_blk_serves(int nb, int g)
+{
+    return env_int("SVB_PANEL_IMPL", 2) == 2 && panel_blk_rows<C>() >= g * nb && (g * nb) % 128 == 0;
+}
+template bool panel_blk_serves<float>(int, int);
+template bool panel_blk_serves<double>(int, int);
+
+template <typename T, typename C>
 void launch_panel_qr(int nb, C* P, int64_t ldp, C* Y, C* Tws, int chunks, int g,
-                     C* Pnext, int64_t ldnext, int* /*err*/, hipStream_t s)
+                     C* Pnext, int64_t ldnext, const T* Asrc, int64_t lda, bool lq, C* band, int64_t ldab,
+                     int64_t row0, int64_t col0, hipStream_t s)
 {
     const int impl = env_int("SVB_PANEL_IMPL", 2);
     // blocked register-resident kernel (2, default) or the reflector-at-a-time register kernel (1),
     // each followed by the MFMA Y product, when the domain fits (and 128-row Y tiles never
-    // straddle two domains); otherwise the plain kernel below
-    const bool blk = impl == 2 && panel_blk_rows<C>() >= g * nb;
+    // straddle two domains); otherwise the plain kernel below.  Only the blocked kernel reads the
+    // matrix and writes the band itself (Asrc, band: null for the others).
+    const bool blk = panel_blk_serves<C>(nb, g);
     if ((blk || (impl != 0 && panel_reg_rows<C>(nb) >= g * nb)) && (g * nb) % 128 == 0) {
-        if (blk) launch_panel_blk<C>(nb, P, ldp, Tws, chunks, g, Pnext, ldnext, s);
+        if (blk) launch_panel_blk<T, C>(nb, P, ldp, Tws, chunks, g, Pnext, ldnext, Asrc, lda, lq, band, ldab, row0, col0, s);
         else PanelRegDispatch<C>::run(nb, P, ldp, Tws, chunks, g, Pnext, ldnext, s);
         const int64_t rows = (int64_t)chunks * nb;
         if (nb == 32) launch_panel_y<C, 32>(P, Y, Tws, ldp, rows, g, s);
@@ -518,8 +527,9 @@ void launch_band_clear(C* band, int64_t ldab, int64_t n, hipStream_t s)
 template void launch_panel_gather<double, double>(const double*, int64_t, int64_t, int64_t, bool, int64_t, int, double*, int64_t, hipStream_t);
 template void launch_panel_gather<float, float>(const float*, int64_t, int64_t, int64_t, bool, int64_t, int, float*, int64_t, hipStream_t);
 template void launch_panel_gather<__half, float>(const __half*, int64_t, int64_t, int64_t, bool, int64_t, int, float*, int64_t, hipStream_t);
-template void launch_panel_qr<double>(int, double*, int64_t, double*, double*, int, int, double*, int64_t, int*, hipStream_t);
-template void launch_panel_qr<float>(int, float*, int64_t, float*, float*, int, int, float*, int64_t, int*, hipStream_t);
+template void launch_panel_qr<double, double>(int, double*, int64_t, double*, double*, int, int, double*, int64_t, const double*, int64_t, bool, double*, int64_t, int64_t, int64_t, hipStream_t);
+template void launch_panel_qr<float, float>(int, float*, int64_t, float*, float*, int, int, float*, int64_t, const float*, int64_t, bool, float*, int64_t, int64_t, int64_t, hipStream_t);
+template void launch_panel_qr<__half, float>(int, float*, int64_t, float*, float*, int, int, float*, int64_t, const __half*, int64_t, bool, float*, int64_t, int64_t, int64_t, hipStream_t);
 template void launch_scatter_r<double>(const double*, int64_t, int, double*, int64_t, int64_t, int64_t, bool, hipStream_t);
 template void launch_scatter_r<float>(const float*, int64_t, int, float*, int64_t, int64_t, int64_t, bool, hipStream_t);
 template void launch_band_clear<double>(double*, int64_t, int64_t, hipStream_t);

@@ -107,10 +107,21 @@ __device__ unsigned long long svb_panel_timing[16];
 #define PT_MARK(slot_) do { } while (0)
 #endif
 
-template <typename C, int NB, int HT>
+// Where a panel comes from and where its R goes when they are not the work panels: the first
+// tree level reads its panel straight from the matrix (QR sweep: element (i, j) of the panel is
+// A[row0 + i, col0 + j]; LQ sweep: A[row0 + j, col0 + i]; Asrc points at A[row0, col0]), the
+// last level writes its R -- a final piece of the band (Figure 1) -- straight into the packed
+// band.  Null pointers select the work panels.
+template <typename T, typename C> struct PanelEnds {
+    const T* Asrc; int64_t lda; int lq;
+    C* band; int64_t ldab, row0, col0;
+};
+
+template <typename T, typename C, int NB, int HT>
 __global__ __launch_bounds__(NB * 4) void panel_qr_blk_kernel(C* __restrict__ P, int64_t ldp,
                                                               C* __restrict__ Tws, int chunks, int g,
-                                                              C* __restrict__ Pnext, int64_t ldnext)
+                                                              C* __restrict__ Pnext, int64_t ldnext,
+                                                              PanelEnds<T, C> ends)
 {
     using F = Frag<C>;
     using G = PanelBlkGeom<C, NB, HT>;
@@ -149,7 +160,15 @@ __global__ __launch_bounds__(NB * 4) void panel_qr_blk_kernel(C* __restrict__ P,
     acc_t c[HT];
 #pragma unroll
     for (int t = 0; t < HT; ++t) {
-        if (t < ntile) c[t] = frag_load<C, C, false>(Pd, ldp, 16 * t, mycol, gq);
+        if (t < ntile) {
+            if (ends.Asrc) {
+                const int64_t p0 = (int64_t)d * g * NB + 16 * t;
+                c[t] = ends.lq ? frag_load<T, C, true>(ends.Asrc, ends.lda, p0, mycol, gq)
+                               : frag_load<T, C, false>(ends.Asrc, ends.lda, p0, mycol, gq);
+            } else {
+                c[t] = frag_load<C, C, false>(Pd, ldp, 16 * t, mycol, gq);
+            }
+        }
         else
 #pragma unroll
             for (int r = 0; r < 4; ++r) c[t][r] = 0;
@@ -416,10 +435,26 @@ __global__ __launch_bounds__(NB * 4) void panel_qr_blk_kernel(C* __restrict__ P,
     // R: rows 0 .. NB-1 of the factored domain, zero below the diagonal
 #pragma unroll
     for (int t = 0; t < NW; ++t) {
-        acc_t v;
+        if (ends.band) {
+            // upper triangle of R into the band: entry (ri, cj) of R is band entry
+            // (row0 + ri, col0 + cj) in a QR sweep, (row0 + cj, col0 + ri) in an LQ sweep
+            if (t <= wave) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) v[r] = (t <= wave) ? c[t][r] : (C)0;
-        frag_store<C, C, false>(Rd, ldnext, 16 * t, mycol, gq, v);
+                for (int r = 0; r < 4; ++r) {
+                    const int64_t ri = 16 * t + F::roff(r, gq), cj = mycol;
+                    if (ri <= cj) {
+                        const int64_t gi = ends.lq ? ends.row0 + cj : ends.row0 + ri;
+                        const int64_t gj = ends.lq ? ends.col0 + ri : ends.col0 + cj;
+                        ends.band[(gi - gj + 2 * NB - 1) + gj * ends.ldab] = c[t][r];
+                    }
+                }
+            }
+        } else {
+            acc_t v;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) v[r] = (t <= wave) ? c[t][r] : (C)0;
+            frag_store<C, C, false>(Rd, ldnext, 16 * t, mycol, gq, v);
+        }
     }
     __syncthreads();
     for (int idx = tid; idx < NB * NB; idx += NT) {
@@ -437,12 +472,13 @@ template <typename C> int panel_blk_rows() { return panel_blk_tiles<C>() * 16; }
 template int panel_blk_rows<float>();
 template int panel_blk_rows<double>();
 
-template <typename C, int NB>
-static void launch_blk(C* P, int64_t ldp, C* Tws, int chunks, int g, C* Pnext, int64_t ldnext, hipStream_t s)
+template <typename T, typename C, int NB>
+static void launch_blk(C* P, int64_t ldp, C* Tws, int chunks, int g, C* Pnext, int64_t ldnext,
+                       const PanelEnds<T, C>& ends, hipStream_t s)
 {
     constexpr int HT = panel_blk_tiles<C>();
     using G = PanelBlkGeom<C, NB, HT>;
-    auto kern = panel_qr_blk_kernel<C, NB, HT>;
+    auto kern = panel_qr_blk_kernel<T, C, NB, HT>;
     static bool attr_set = false;
     if (!attr_set) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -450,20 +486,24 @@ static void launch_blk(C* P, int64_t ldp, C* Tws, int chunks, int g, C* Pnext, i
         attr_set = true;
     }
     const int domains = (chunks + g - 1) / g;
-    hipLaunchKernelGGL(kern, dim3(domains), dim3(G::NT), G::kSmemBytes, s, P, ldp, Tws, chunks, g, Pnext, ldnext);
+    hipLaunchKernelGGL(kern, dim3(domains), dim3(G::NT), G::kSmemBytes, s, P, ldp, Tws, chunks, g, Pnext, ldnext, ends);
 }
 
-template <typename C>
-void launch_panel_blk(int nb, C* P, int64_t ldp, C* Tws, int chunks, int g, C* Pnext, int64_t ldnext, hipStream_t s)
+template <typename T, typename C>
+void launch_panel_blk(int nb, C* P, int64_t ldp, C* Tws, int chunks, int g, C* Pnext, int64_t ldnext,
+                      const T* Asrc, int64_t lda, bool lq, C* band, int64_t ldab, int64_t row0, int64_t col0,
+                      hipStream_t s)
 {
+    const PanelEnds<T, C> ends{Asrc, lda, lq ? 1 : 0, band, ldab, row0, col0};
     switch (nb) {
-    case 32: launch_blk<C, 32>(P, ldp, Tws, chunks, g, Pnext, ldnext, s); break;
-    case 64: launch_blk<C, 64>(P, ldp, Tws, chunks, g, Pnext, ldnext, s); break;
-    default: launch_blk<C, 128>(P, ldp, Tws, chunks, g, Pnext, ldnext, s); break;
+    case 32: launch_blk<T, C, 32>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, s); break;
+    case 64: launch_blk<T, C, 64>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, s); break;
+    default: launch_blk<T, C, 128>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, s); break;
     }
 }
 
-template void launch_panel_blk<float>(int, float*, int64_t, float*, int, int, float*, int64_t, hipStream_t);
-template void launch_panel_blk<double>(int, double*, int64_t, double*, int, int, double*, int64_t, hipStream_t);
+template void launch_panel_blk<float, float>(int, float*, int64_t, float*, int, int, float*, int64_t, const float*, int64_t, bool, float*, int64_t, int64_t, int64_t, hipStream_t);
+template void launch_panel_blk<__half, float>(int, float*, int64_t, float*, int, int, float*, int64_t, const __half*, int64_t, bool, float*, int64_t, int64_t, int64_t, hipStream_t);
+template void launch_panel_blk<double, double>(int, double*, int64_t, double*, int, int, double*, int64_t, const double*, int64_t, bool, double*, int64_t, int64_t, int64_t, hipStream_t);
 
 }  // namespace svb

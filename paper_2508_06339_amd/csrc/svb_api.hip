@@ -304,15 +304,21 @@ int ge2gb_impl(int64_t n, T* A, int64_t lda, int nb, C* band, int64_t ldab, unsi
             const int64_t len = lq ? n - (k + 1) * nb : n - k * nb;
             const int nl = build_levels(len, nb, g, lv);
             g_prof.begin(SVB_PROF_PANEL, s, 2.0 * (double)len * nb * nb, 0.0);
-            launch_panel_gather<T, C>(A, lda, row0, col0, lq, len, nb, Vb + lv[0].poff, lv[0].ldp, s);
+            // the blocked panel kernel reads the first level's panel straight from the matrix and
+            // writes the last level's R straight into the band; the other kernels go through a
+            // gathered copy and a scatter
+            const bool direct = panel_blk_serves<C>(nb, g);
+            if (!direct) launch_panel_gather<T, C>(A, lda, row0, col0, lq, len, nb, Vb + lv[0].poff, lv[0].ldp, s);
             for (int L = 0; L < nl; ++L) {
                 // the R factors of level L are stacked into level L+1's panel; the last
                 // level's single R lands right behind it
                 const int64_t next_off = lv[L].poff + lv[L].ldp * nb;
                 const int64_t ldnext = (int64_t)lv[L].domains * nb;
-                launch_panel_qr<C>(nb, Vb + lv[L].poff, lv[L].ldp, Yb + lv[L].poff, Tb, lv[L].chunks, g,
-                                   Vb + next_off, ldnext, err, s);
-                if (L == nl - 1)
+                const bool last = L == nl - 1;
+                launch_panel_qr<T, C>(nb, Vb + lv[L].poff, lv[L].ldp, Yb + lv[L].poff, Tb, lv[L].chunks, g,
+                                      Vb + next_off, ldnext, (direct && L == 0) ? A + row0 + col0 * lda : nullptr, lda, lq,
+                                      (direct && last) ? band : nullptr, ldab, row0, col0, s);
+                if (last && !direct)
                     launch_scatter_r<C>(Vb + next_off, ldnext, nb, band, ldab, row0, col0, lq, s);
             }
             g_prof.end(s);

@@ -77,15 +77,24 @@ template <typename T, typename C>
 void launch_panel_gather(const T* A, int64_t lda, int64_t row0, int64_t col0, bool lq,
                          int64_t len, int nb, C* P, int64_t ldp, hipStream_t s);
 
-template <typename C>
+template <typename T, typename C>
 void launch_panel_qr(int nb, C* P, int64_t ldp, C* Y, C* Tws, int chunks, int g,
-                     C* Pnext, int64_t ldnext, int* err, hipStream_t s);
+                     C* Pnext, int64_t ldnext, const T* Asrc, int64_t lda, bool lq, C* band, int64_t ldab,
+                     int64_t row0, int64_t col0, hipStream_t s);
 
 // blocked register-resident domain QR (MFMA block reflectors inside the domain); domains of at
 // most panel_blk_rows<C>() rows
-template <typename C>
-void launch_panel_blk(int nb, C* P, int64_t ldp, C* Tws, int chunks, int g, C* Pnext, int64_t ldnext, hipStream_t s);
+// Asrc != nullptr: the panel is read straight from the matrix (Asrc = &A[row0, col0], QR / LQ
+// orientation) instead of the work panel P; band != nullptr: R goes straight into the packed band
+// (the last tree level) instead of Pnext.
+template <typename T, typename C>
+void launch_panel_blk(int nb, C* P, int64_t ldp, C* Tws, int chunks, int g, C* Pnext, int64_t ldnext,
+                      const T* Asrc, int64_t lda, bool lq, C* band, int64_t ldab, int64_t row0, int64_t col0,
+                      hipStream_t s);
 template <typename C> int panel_blk_rows();
+// does the blocked kernel serve this (type, nb, chunks per domain)?  Then the first level needs no
+// gathered copy of its panel and the last level no separate scatter of R.
+template <typename C> bool panel_blk_serves(int nb, int g);
 
 template <typename C>
 void launch_scatter_r(const C* R, int64_t ldr, int nb, C* band, int64_t ldab,
