@@ -117,7 +117,10 @@ template <typename T, typename C> struct PanelEnds {
     C* band; int64_t ldab, row0, col0;
 };
 
-template <typename T, typename C, int NB, int HT>
+// TRI: the panel is a stack of upper triangular NB x NB factors (tree levels above the first).
+// Block b's reflectors are then exactly zero in every 16-row tile that lies below block row b
+// of its chunk, and both products skip those tiles.
+template <typename T, typename C, int NB, int HT, bool TRI>
 __global__ __launch_bounds__(NB * 4) void panel_qr_blk_kernel(C* __restrict__ P, int64_t ldp,
                                                               C* __restrict__ Tws, int chunks, int g,
                                                               C* __restrict__ Pnext, int64_t ldnext,
@@ -335,7 +338,7 @@ __global__ __launch_bounds__(NB * 4) void panel_qr_blk_kernel(C* __restrict__ P,
             for (int r = 0; r < 4; ++r) { pa[r] = 0; pb[r] = 0; }
 #pragma unroll
             for (int t = 0; t < HT; ++t) {
-                if (t >= b && t < ntile) {
+                if (t >= b && t < ntile && (!TRI || (t % (NB / 16)) <= b)) {
                     C o[4];
                     F::ld4(&Bs[i * LDB + 16 * t], gq, o);
                     if (t & 1) {
@@ -394,7 +397,7 @@ __global__ __launch_bounds__(NB * 4) void panel_qr_blk_kernel(C* __restrict__ P,
                 for (int r = 0; r < 4; ++r) w[r] = -w[r];
 #pragma unroll
                 for (int t = 0; t < HT; ++t) {
-                    if (t >= b && t < ntile) {
+                    if (t >= b && t < ntile && (!TRI || (t % (NB / 16)) <= b)) {
 #pragma unroll
                         for (int r = 0; r < 4; ++r)
                             c[t] = F::mma(Bs[F::roff(r, gq) * LDB + 16 * t + i], w[r], c[t]);
@@ -478,11 +481,14 @@ static void launch_blk(C* P, int64_t ldp, C* Tws, int chunks, int g, C* Pnext, i
 {
     constexpr int HT = panel_blk_tiles<C>();
     using G = PanelBlkGeom<C, NB, HT>;
-    auto kern = panel_qr_blk_kernel<T, C, NB, HT>;
+    // a panel that does not come from the matrix is a stack of triangular factors
+    auto kern = ends.Asrc ? panel_qr_blk_kernel<T, C, NB, HT, false> : panel_qr_blk_kernel<T, C, NB, HT, true>;
     static bool attr_set = false;
     if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                  (int)G::kSmemBytes);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(panel_qr_blk_kernel<T, C, NB, HT, false>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)G::kSmemBytes);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(panel_qr_blk_kernel<T, C, NB, HT, true>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)G::kSmemBytes);
         attr_set = true;
     }
     const int domains = (chunks + g - 1) / g;
