@@ -25,7 +25,9 @@
  *     nb in {32, 64, 128}, dtype f64 / f32 / f16 (f16 is storage only: every
  *     product and sum is formed in f32, as the paper does for half precision,
  *     Section 4.3).  Anything else returns SVB_ERR_UNSUPPORTED.
- *   - Calls that share a workspace, a matrix or a stream must not overlap.
+ *   - Calls that share a workspace, a matrix or a stream must not overlap, and
+ *     calls into the library from different host threads must not overlap at
+ *     all (the internal streams and events are per process).
  */
 #ifndef SVB_H
 #define SVB_H
