@@ -338,9 +338,9 @@ int ge2gb_impl(int64_t n, T* A, int64_t lda, int nb, C* band, int64_t ldab, unsi
                     wo += (int64_t)lv[L].domains * nb * qlen;
                     any_rest = any_rest || lv[L].chunks > lv[L].domains;
                 }
-                // splitting pays once a launch is more than a round or two of workgroups; below that
+                // splitting pays once a launch is many rounds of workgroups; below that
                 // both parts would take as long as the whole
-                const bool big = impl != 2 || (int64_t)lv[0].domains * ((qlen + 63) / 64) >= env_int("SVB_LOOKAHEAD_MIN_TILES", 1024);
+                const bool big = impl != 2 || (int64_t)lv[0].domains * ((qlen + 63) / 64) >= env_int("SVB_LOOKAHEAD_MIN_TILES", 4096);
                 const bool defer = la && any_rest && big;
                 if (impl == 2) {
                     // one pass per level; with look-ahead split in two: the part the next panel
