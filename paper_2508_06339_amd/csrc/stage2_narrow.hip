@@ -162,6 +162,84 @@ __device__ __forceinline__ void narrow_half4(C* win, C* vbuf, int i, int t, bool
 #undef WIN
 }
 
+// The same half step for the common case: every active sweep of the wave is at least 2D
+// columns away from the end of the matrix (full-length reflectors, full blocks) and, for a
+// right reflector, its D columns do not straddle the wrap of the window.  Then every element
+// a lane touches sits at a constant offset from one base address (consecutive columns of one
+// row are RS - 1 apart, consecutive rows of one column 1 apart), each lane reads the pivot
+// row / column itself (the 16 lanes of a sweep read the same addresses: a broadcast), and
+// nothing but the row / column count needs a predicate.  H = I (tau = 0) falls out of the
+// arithmetic: then s = 0 and the stores write back what was read.
+template <typename C, int D, int WC, bool LEFT>
+__device__ __forceinline__ void narrow_half4_fast(C* win, int i, int t, bool act)
+{
+    constexpr int RS = 3 * D, M = WC - 1;
+    constexpr int SV = LEFT ? 1 : RS - 1;   // distance between consecutive elements of the pivot / of a lane's line
+    const int sub = threadIdx.x & 15;
+    const int c0 = i + 1 + t * D;
+    C* pv;        // pivot element jj at pv[jj * SV]
+    C* pa;        // this lane's row / column: element jj at pa[jj * SV]
+    bool mine;
+    if constexpr (!LEFT) {
+        const int r = (t == 0) ? i : c0 - D;
+        mine = act && sub < c0 + D - 1 - r;                 // rows r+1 .. c0+D-1
+        pv = win + (c0 & M) * RS + (r - c0) + 2 * D - 1;    // (r, c0 + jj)
+        pa = pv + 1 + sub;                                  // (r + 1 + sub, c0 + jj)
+    } else {
+        mine = act && sub < 2 * D - 1;                      // columns c0+1 .. c0+2D-1
+        pv = win + (c0 & M) * RS + 2 * D - 1;               // (c0 + jj, c0)
+        pa = win + ((c0 + 1 + sub) & M) * RS + 2 * D - 2 - sub;   // (c0 + jj, c0 + 1 + sub)
+    }
+    if (mine) {
+        C v[D], a[D];
+#pragma unroll
+        for (int jj = 0; jj < D; ++jj) { v[jj] = pv[jj * SV]; a[jj] = pa[jj * SV]; }
+        C ss = 0;
+#pragma unroll
+        for (int jj = 1; jj < D; ++jj) ss += v[jj] * v[jj];
+        // the reflector without a branch: with ss = 0 the selects give H = I whatever the
+        // discarded operands evaluate to
+        const C alpha = v[0];
+        const C x2 = alpha * alpha + ss;
+        // the refined hardware square root wants a normal argument; sums of squares near the
+        // underflow threshold (rare) take the library routine, for the whole wave
+        constexpr C kTiny = sizeof(C) == 8 ? (C)1e-290 : (C)1e-30f;
+        C nrm;
+        if (__any(x2 < kTiny)) nrm = sqrt(x2); else nrm = newton_sqrt(x2);
+        const C bc = alpha >= (C)0 ? -nrm : nrm;
+        const bool ident = ss == (C)0;
+        const C beta = ident ? alpha : bc;
+        const C tau = ident ? (C)0 : (bc - alpha) * fast_rcp(bc);
+        const C inv = ident ? (C)0 : fast_rcp(alpha - bc);
+        v[0] = (C)1;
+        C s = a[0];
+#pragma unroll
+        for (int jj = 1; jj < D; ++jj) {
+            v[jj] *= inv;
+            s += v[jj] * a[jj];
+        }
+        s *= tau;
+        if (sub < D) pv[sub * SV] = (sub == 0) ? beta : (C)0;
+#pragma unroll
+        for (int jj = 0; jj < D; ++jj) pa[jj * SV] = a[jj] - s * v[jj];
+    }
+}
+
+// One super-step of a wave: the half step h of each of its four sweeps, then the workgroup barrier.
+template <typename C, int D, int WC, bool LEFT>
+__device__ __forceinline__ void narrow_super_step(C* win, C* vbuf, int my_i, int64_t h, bool have, int64_t my_steps, int n)
+{
+    const bool act = have && h >= 0 && h < 2 * my_steps;
+    const int tt = act ? (int)(h >> 1) : 0;
+    const int c0 = my_i + 1 + tt * D;
+    const bool fast = !act || (c0 + 2 * D <= n && (LEFT || (c0 & (WC - 1)) <= WC - D));
+    if (__all(fast))
+        narrow_half4_fast<C, D, WC, LEFT>(win, my_i, tt, act);
+    else
+        narrow_half4<C, D, WC>(win, vbuf, my_i, tt, LEFT, act, n);
+    lds_block_sync();
+}
+
 template <typename C, int D, int NW, int WC, int GS>
 __global__ __launch_bounds__(NW * 16) void chase_narrow_kernel(C* __restrict__ band, int64_t ldab, int64_t ku,
                                                                int64_t n, int* __restrict__ ctrl,
@@ -285,11 +363,10 @@ __global__ __launch_bounds__(NW * 16) void chase_narrow_kernel(C* __restrict__ b
                     pre[q] = ok ? ngld(p) : (C)0;
                 }
             }
-            for (int hs = 0; hs < 2 * GS; ++hs) {
-                const int64_t h = g * 2 * GS + hs - 4 * slot;      // this sweep's half step
-                const bool act = have && h >= 0 && h < 2 * my_steps;
-                narrow_half4<C, D, WC>(win, vbuf, (int)my_i, act ? (int)(h >> 1) : 0, (hs & 1) != 0, act, (int)n);
-                lds_block_sync();
+            for (int hp = 0; hp < GS; ++hp) {
+                const int64_t h = g * 2 * GS + 2 * hp - 4 * slot;      // this sweep's half step (right, then left)
+                narrow_super_step<C, D, WC, false>(win, vbuf, (int)my_i, h, have, my_steps, (int)n);
+                narrow_super_step<C, D, WC, true>(win, vbuf, (int)my_i, h + 1, have, my_steps, (int)n);
             }
             NMARK(1);
             if (want) {
@@ -347,12 +424,10 @@ __global__ __launch_bounds__(256) void narrow_clear_kernel(int* __restrict__ p, 
 // ctrl: 64 ints (ticket, error flag) followed by one flushed counter per bundle
 size_t chase_narrow_workspace_bytes(int64_t n) { return (size_t)(64 + n / 8 + 8) * sizeof(int); }
 
-template <typename C>
-int run_chase_narrow(int64_t n, C* band, int64_t ldab, int64_t ku, int* ctrl, hipStream_t s)
+template <typename C, int NW, int WC>
+static int run_chase_narrow_nw(int64_t n, C* band, int64_t ldab, int64_t ku, int* ctrl, hipStream_t s)
 {
     constexpr int D = 8;
-    constexpr int NW = sizeof(C) == 8 ? 16 : 48;   // sweeps per bundle (four per wave): as many as the window holds
-    constexpr int WC = sizeof(C) == 8 ? 512 : 1024;
     constexpr int GS = 8;   // super-steps per group (chunk = GS*D columns)
     if (n < 3) return SVB_OK;
     const size_t smem = sizeof(C) * ((size_t)WC * 3 * D + (size_t)(NW / 4) * 4 * D);
@@ -370,6 +445,22 @@ int run_chase_narrow(int64_t n, C* band, int64_t ldab, int64_t ku, int* ctrl, hi
     const int spin_limit = env_int("SVB_CHASE_SPIN", 1 << 20);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(NW * 16), smem, s, band, ldab, ku, n, ctrl, ctrl + 64, spin_limit);
     return hipGetLastError() == hipSuccess ? SVB_OK : SVB_ERR_DEVICE;
+}
+
+template <typename C>
+int run_chase_narrow(int64_t n, C* band, int64_t ldab, int64_t ku, int* ctrl, hipStream_t s)
+{
+    // sweeps per bundle (four per wave)
+    const int nw = env_int("SVB_NARROW_NW", sizeof(C) == 8 ? 16 : 48);
+    if constexpr (sizeof(C) == 8) {
+        if (nw == 8) return run_chase_narrow_nw<C, 8, 512>(n, band, ldab, ku, ctrl, s);
+        return run_chase_narrow_nw<C, 16, 512>(n, band, ldab, ku, ctrl, s);
+    } else {
+        if (nw == 8) return run_chase_narrow_nw<C, 8, 512>(n, band, ldab, ku, ctrl, s);
+        if (nw == 16) return run_chase_narrow_nw<C, 16, 512>(n, band, ldab, ku, ctrl, s);
+        if (nw == 32) return run_chase_narrow_nw<C, 32, 1024>(n, band, ldab, ku, ctrl, s);
+        return run_chase_narrow_nw<C, 48, 1024>(n, band, ldab, ku, ctrl, s);
+    }
 }
 
 template int run_chase_narrow<double>(int64_t, double*, int64_t, int64_t, int*, hipStream_t);

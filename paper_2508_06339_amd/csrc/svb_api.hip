@@ -208,31 +208,43 @@ struct Profiler {
 // chain does not run on the caller's stream itself.)
 void g_la_release();
 struct Lookahead {
-    hipStream_t m = nullptr, h = nullptr;
+    hipStream_t m = nullptr, h = nullptr, u = nullptr;
     hipEvent_t crit[2] = {nullptr, nullptr}, rest[2] = {nullptr, nullptr}, fork = nullptr, join = nullptr;
+    // level pipeline: panel level L of a half-sweep done / its update done; the update stream's join
+    hipEvent_t lvl[2][kMaxLevels] = {}, udone[2] = {nullptr, nullptr}, join_u = nullptr;
     bool ok = false, tried = false;
-    bool init()
+    static bool masked_stream(hipStream_t* st, int bits)
     {
-        if (tried) return ok;
-        tried = true;
-        if (hipStreamCreateWithFlags(&m, hipStreamNonBlocking) != hipSuccess) return false;
-        const int bits = env_int("SVB_HELPER_MASK_BITS", 224);
+        // bit i of a CU mask is compute unit i / 8 of XCD i % 8 (measured): clearing the top bits
+        // takes the same number of CUs away from every XCD
         if (bits > 0 && bits < 256) {
             uint32_t mask[8];
             for (int w = 0; w < 8; ++w) {
                 const int nb = bits - 32 * w;
                 mask[w] = nb >= 32 ? 0xffffffffu : (nb <= 0 ? 0u : ((1u << nb) - 1u));
             }
-            if (hipExtStreamCreateWithCUMask(&h, 8, mask) != hipSuccess) return false;
-        } else if (hipStreamCreateWithFlags(&h, hipStreamNonBlocking) != hipSuccess) {
-            return false;
+            return hipExtStreamCreateWithCUMask(st, 8, mask) == hipSuccess;
         }
-        for (int i = 0; i < 2; ++i)
+        return hipStreamCreateWithFlags(st, hipStreamNonBlocking) == hipSuccess;
+    }
+    bool init()
+    {
+        if (tried) return ok;
+        tried = true;
+        if (hipStreamCreateWithFlags(&m, hipStreamNonBlocking) != hipSuccess) return false;
+        if (!masked_stream(&h, env_int("SVB_HELPER_MASK_BITS", 224))) return false;
+        if (!masked_stream(&u, env_int("SVB_UPDATE_MASK_BITS", 256))) return false;
+        for (int i = 0; i < 2; ++i) {
             if (hipEventCreateWithFlags(&crit[i], hipEventDisableTiming) != hipSuccess ||
-                hipEventCreateWithFlags(&rest[i], hipEventDisableTiming) != hipSuccess)
+                hipEventCreateWithFlags(&rest[i], hipEventDisableTiming) != hipSuccess ||
+                hipEventCreateWithFlags(&udone[i], hipEventDisableTiming) != hipSuccess)
                 return false;
+            for (int L = 0; L < kMaxLevels; ++L)
+                if (hipEventCreateWithFlags(&lvl[i][L], hipEventDisableTiming) != hipSuccess) return false;
+        }
         if (hipEventCreateWithFlags(&fork, hipEventDisableTiming) != hipSuccess ||
-            hipEventCreateWithFlags(&join, hipEventDisableTiming) != hipSuccess)
+            hipEventCreateWithFlags(&join, hipEventDisableTiming) != hipSuccess ||
+            hipEventCreateWithFlags(&join_u, hipEventDisableTiming) != hipSuccess)
             return false;
         ok = true;
         // released while the HIP runtime is still up (handlers registered later run earlier):
@@ -245,18 +257,93 @@ struct Lookahead {
         if (!ok) return;
         ok = false;
         (void)hipStreamSynchronize(h);
+        (void)hipStreamSynchronize(u);
         (void)hipStreamSynchronize(m);
         for (int i = 0; i < 2; ++i) {
             (void)hipEventDestroy(crit[i]);
             (void)hipEventDestroy(rest[i]);
+            (void)hipEventDestroy(udone[i]);
+            for (int L = 0; L < kMaxLevels; ++L) (void)hipEventDestroy(lvl[i][L]);
         }
         (void)hipEventDestroy(fork);
         (void)hipEventDestroy(join);
+        (void)hipEventDestroy(join_u);
         (void)hipStreamDestroy(h);
+        (void)hipStreamDestroy(u);
         (void)hipStreamDestroy(m);
     }
 } g_la;
 void g_la_release() { g_la.release(); }
+
+// Stage 1 driver, level pipeline (the default with the one-pass update).  The tree levels of a
+// panel depend on each other only through the R factors, not through the trailing matrix, so
+// once level L of the panel is factored its update can start while level L+1 is being
+// factored:  panel stream  P0 | P1 | P2 ...     update stream  . | U0 | U1 | U2
+// The next half-sweep's panel waits for the last update.  The update stream is confined to 240
+// of the 256 compute units (two per XCD are left out), so that the one or few workgroups of
+// the upper panel levels, each of which needs a compute unit of its own, start at once.
+template <typename T, typename C>
+int ge2gb_pipeline(int64_t n, T* A, int64_t lda, int nb, C* band, int64_t ldab, unsigned char* work,
+                   const Carve& cv, int g, hipStream_t caller)
+{
+    const int64_t N = n / nb;
+    Level lv[kMaxLevels];
+    hipStream_t ps = g_la.m, us = g_la.u;
+    (void)hipEventRecord(g_la.fork, caller);
+    (void)hipStreamWaitEvent(ps, g_la.fork, 0);
+    (void)hipStreamWaitEvent(us, g_la.fork, 0);
+    launch_band_clear<C>(band, ldab, n, ps);
+    C* Vb = reinterpret_cast<C*>(work + cv.off_V[0]);
+    C* Yb = reinterpret_cast<C*>(work + cv.off_Y[0]);
+    C* Tb = reinterpret_cast<C*>(work + cv.off_T[0]);
+    const bool direct = panel_blk_serves<C>(nb, g);
+    int hs = 0;
+    bool updated = false;   // an update of the previous half-sweep is in flight
+    for (int64_t k = 0; k < N; ++k) {
+        for (int half = 0; half < 2; ++half) {
+            const bool lq = half == 1;
+            if (lq && k == N - 1) break;
+            const int set = hs & 1;
+            const int64_t row0 = k * nb;
+            const int64_t col0 = lq ? (k + 1) * nb : k * nb;
+            const int64_t len = lq ? n - (k + 1) * nb : n - k * nb;
+            const int nl = build_levels(len, nb, g, lv);
+            if (updated) (void)hipStreamWaitEvent(ps, g_la.udone[(hs - 1) & 1], 0);
+            g_prof.begin(SVB_PROF_PANEL, ps, 2.0 * (double)len * nb * nb, 0.0);
+            if (!direct) launch_panel_gather<T, C>(A, lda, row0, col0, lq, len, nb, Vb + lv[0].poff, lv[0].ldp, ps);
+            for (int L = 0; L < nl; ++L) {
+                const int64_t next_off = lv[L].poff + lv[L].ldp * nb;
+                const int64_t ldnext = (int64_t)lv[L].domains * nb;
+                const bool last = L == nl - 1;
+                launch_panel_qr<T, C>(nb, Vb + lv[L].poff, lv[L].ldp, Yb + lv[L].poff, Tb, lv[L].chunks, g,
+                                      Vb + next_off, ldnext, (direct && L == 0) ? A + row0 + col0 * lda : nullptr, lda, lq,
+                                      (direct && last) ? band : nullptr, ldab, row0, col0, ps);
+                if (last && !direct)
+                    launch_scatter_r<C>(Vb + next_off, ldnext, nb, band, ldab, row0, col0, lq, ps);
+                (void)hipEventRecord(g_la.lvl[set][L], ps);
+            }
+            g_prof.end(ps);
+            const int64_t qlen = n - (k + 1) * nb;
+            updated = false;
+            if (qlen > 0) {
+                T* Cb = lq ? A + (k + 1) * nb + (k + 1) * nb * lda : A + k * nb + (k + 1) * nb * lda;
+                for (int L = 0; L < nl; ++L) {
+                    (void)hipStreamWaitEvent(us, g_la.lvl[set][L], 0);
+                    launch_update_fused<T, C>(nb, lq, Cb, lda, qlen, Vb + lv[L].poff, Yb + lv[L].poff, lv[L].ldp,
+                                              lv[L].chunks, g, lv[L].stride, L > 0, 0, (C*)nullptr, L == 0, us);
+                }
+                (void)hipEventRecord(g_la.udone[set], us);
+                updated = true;
+            }
+            ++hs;
+        }
+    }
+    (void)hipEventRecord(g_la.join, ps);
+    (void)hipEventRecord(g_la.join_u, us);
+    (void)hipStreamWaitEvent(caller, g_la.join, 0);
+    (void)hipStreamWaitEvent(caller, g_la.join_u, 0);
+    return hipGetLastError() == hipSuccess ? SVB_OK : SVB_ERR_DEVICE;
+}
 
 // Stage 1 driver.  Per half-sweep: panel tree on the caller's stream; then, level by
 // level, K1 and the part of K2 that the next level and the next panel read (the first
@@ -273,6 +360,8 @@ int ge2gb_impl(int64_t n, T* A, int64_t lda, int nb, C* band, int64_t ldab, unsi
     // the kernel's registers), 1 = two MFMA kernels with look-ahead, 0 = plain FMA kernels
     int impl = env_int("SVB_UPDATE_IMPL", 2);
     if (impl == 2 && g * nb > fused_update_rows<C>()) impl = 1;
+    if (impl == 2 && env_int("SVB_PIPELINE", 1) != 0 && g_la.init())
+        return ge2gb_pipeline<T, C>(n, A, lda, nb, band, ldab, work, cv, g, caller);
     const bool la = impl != 0 && env_int("SVB_LOOKAHEAD", 1) != 0 && g_la.init();
     const int64_t N = n / nb;
     Level lv[kMaxLevels];
