@@ -424,11 +424,10 @@ __global__ __launch_bounds__(256) void narrow_clear_kernel(int* __restrict__ p, 
 // ctrl: 64 ints (ticket, error flag) followed by one flushed counter per bundle
 size_t chase_narrow_workspace_bytes(int64_t n) { return (size_t)(64 + n / 8 + 8) * sizeof(int); }
 
-template <typename C, int NW, int WC>
+template <typename C, int NW, int WC, int GS = 8>   // GS: super-steps per group (chunk = GS*D columns)
 static int run_chase_narrow_nw(int64_t n, C* band, int64_t ldab, int64_t ku, int* ctrl, hipStream_t s)
 {
     constexpr int D = 8;
-    constexpr int GS = 8;   // super-steps per group (chunk = GS*D columns)
     if (n < 3) return SVB_OK;
     const size_t smem = sizeof(C) * ((size_t)WC * 3 * D + (size_t)(NW / 4) * 4 * D);
     auto kern = chase_narrow_kernel<C, D, NW, WC, GS>;
@@ -457,6 +456,9 @@ int run_chase_narrow(int64_t n, C* band, int64_t ldab, int64_t ku, int* ctrl, hi
         return run_chase_narrow_nw<C, 16, 512>(n, band, ldab, ku, ctrl, s);
     } else {
         if (nw == 8) return run_chase_narrow_nw<C, 8, 512>(n, band, ldab, ku, ctrl, s);
+        const int gs = env_int("SVB_NARROW_GS", 8);
+        if (nw == 16 && gs == 16) return run_chase_narrow_nw<C, 16, 1024, 16>(n, band, ldab, ku, ctrl, s);
+        if (nw == 32 && gs == 16) return run_chase_narrow_nw<C, 32, 1024, 16>(n, band, ldab, ku, ctrl, s);
         if (nw == 16) return run_chase_narrow_nw<C, 16, 512>(n, band, ldab, ku, ctrl, s);
         if (nw == 32) return run_chase_narrow_nw<C, 32, 1024>(n, band, ldab, ku, ctrl, s);
         return run_chase_narrow_nw<C, 48, 1024>(n, band, ldab, ku, ctrl, s);

@@ -13,13 +13,16 @@
 //          other columns of Z and to the block right of it (A3), which becomes the next
 //          step's upper block.
 // Only D rows / columns of every bulge are annihilated per step; the rest moves down the band
-// with the following sweeps.  Step (s+1, t) touches data of step (s, t+2) and nothing later of
-// sweep s, so sweeps are pipelined three steps apart: one workgroup per sweep, sweeps drawn
-// from a ticket counter, a progress counter per sweep, bounded waits (as in stage2_chase.hip).
+// with the following sweeps.  Sweeps are pipelined: one workgroup per sweep, sweeps drawn from a
+// ticket counter, a progress counter per sweep, bounded waits (as in stage2_chase.hip).  Of the
+// blocks step (s+1, t) brings in, the one right of Z was last written by the right half of step
+// (s, t+2) (that step's upper block) and the next diagonal block by its left half (the corner it
+// shares with that step's Z); progress is therefore published per block (upper block final /
+// whole step final) and a sweep follows its predecessor a little over two steps behind.
 //
 // Per step the workgroup holds the upper block U (rows c0-B .., the previous step's A3) and Z
-// stacked in LDS (2B x B); A3 is requested at the start of the step and the next step's Z in
-// the middle of it, and they take the place of U and Z once those have been written back, so
+// stacked in LDS (2B x B); A3 is requested after the right panel and the next step's Z after
+// the left panel, and they take the place of U and Z once those have been written back, so
 // every block is read once and written once per sweep.  One wave factors the panels while the
 // others do that traffic.
 //
@@ -505,9 +508,19 @@ __global__ __launch_bounds__(ReduceShape<B>::NT) void band_reduce_kernel(C* __re
         return rgld(p);
     };
     auto gstore = [&](const Blk& k, int q, C v) { rgst(k.p + (int64_t)(q * JS) * ldm1, v); };
-    // waits (one lane) until sweep s-1 has finished `need` steps; an expired wait sets sh_fail
-    auto wait_for = [&](int64_t s, int need) {
-        if (lead && s > 0) {
+    // Progress of a sweep: 2k+1 once the upper block U of its step k is final in the band (and
+    // every block of the steps before), 2k+2 once all blocks of step k are.
+    // poll: the predecessor's progress, requested ahead of the work it is checked after;
+    // wait_for: waits (one lane) until sweep s-1 has reached `need`, `seen` being an earlier
+    // poll; an expired wait sets sh_fail
+    auto poll = [&](int64_t s) -> int {
+        return (lead && s > 0) ? __hip_atomic_load(&progress[s - 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
+    };
+    auto publish = [&](int64_t s, int value) {
+        if (lead) __hip_atomic_store(&progress[s], value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    };
+    auto wait_for = [&](int64_t s, int need, int seen) {
+        if (lead && s > 0 && seen < need) {
             int spins = 0;
             while (__hip_atomic_load(&progress[s - 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < need) {
                 if (++spins > spin_limit) {
@@ -537,7 +550,8 @@ __global__ __launch_bounds__(ReduceShape<B>::NT) void band_reduce_kernel(C* __re
         if (lead) tlast = wall_clock64();
 #endif
         // ---- prologue: the sweep's own D rows and the first diagonal block, straight into LDS
-        wait_for(s, 3);
+        // (the first diagonal block was last touched by the predecessor's step 1)
+        wait_for(s, 4, 0);
         __syncthreads();
         bool failed = sh_fail != 0;
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
@@ -574,6 +588,7 @@ __global__ __launch_bounds__(ReduceShape<B>::NT) void band_reduce_kernel(C* __re
             // ---- S1: right panel (LQ of X)  ||  Z of the previous step back, this step's Z in
             const int ncol = (int)min((int64_t)B, n - c0);                            // columns c0 .. inside the matrix
             const int64_t rho = (t == 0) ? c00 - D : c0 - B;                          // first row of X
+            const int seen1 = poll(s);
             if (pw) {
                 if (UG) panel_wave<C, B, D, true>(band + (rho - c0 + ku) + c0 * ldab, 1, ldm1, Vs, Ts, ncol);
                 else panel_wave<C, B, D>(S + xoff, 1, LD, Vs, Ts);
@@ -614,9 +629,11 @@ __global__ __launch_bounds__(ReduceShape<B>::NT) void band_reduce_kernel(C* __re
             if (UG) stores_done();
             lds_barrier();
             RMARK(1);
-            // ---- S2: publish the previous step, wait for the predecessor's step t+2
-            if (lead && t > 0) __hip_atomic_store(&progress[s], t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            wait_for(s, t + 3);
+            // ---- S2: publish the previous step; the block right of Z (requested or transformed in
+            // place from here on) was last touched by the right half of the predecessor's step
+            // t+2, whose result is that step's upper block
+            if (t > 0) publish(s, 2 * t);
+            wait_for(s, 2 * t + 5, seen1);
             lds_barrier();
             failed = sh_fail != 0;
             RMARK(2);
@@ -653,11 +670,13 @@ __global__ __launch_bounds__(ReduceShape<B>::NT) void band_reduce_kernel(C* __re
             }
             lds_barrier();
             RMARK(3);
-            // ---- S4: left panel (QR of Z's first D columns)  ||  U back, A3 in, next Z requested
+            if (UG) publish(s, 2 * t + 1);   // U was transformed where it lies; the stores are acknowledged
+            // ---- S4: left panel (QR of Z's first D columns)  ||  U back, A3 in
+            const int seen2 = poll(s);
             if (pw) {
                 panel_wave<C, B, D>(S + ZO, LD, 1, Vs, Ts);
             } else if (!UG && traffic) {
-                const Blk ub = block_at(c0 - B, c0), zn = block_at(c0 + B, c0 + B), a3 = block_at(c0, c0 + B);
+                const Blk ub = block_at(c0 - B, c0), a3 = block_at(c0, c0 + B);
 #pragma unroll
                 for (int q = 0; q < PER; ++q) {
                     if (jj0 + q * JS < B) {
@@ -670,12 +689,23 @@ __global__ __launch_bounds__(ReduceShape<B>::NT) void band_reduce_kernel(C* __re
 #pragma unroll
                 for (int q = 0; q < PER; ++q)
                     if (inside(ub, q) && ii >= xoff) gstore(ub, q, pre[q]);
-#pragma unroll
-                for (int q = 0; q < PER; ++q) pre[q] = gload(zn, q, true);
+                stores_done();
             }
             RMARK(4);
             lds_barrier();
+            // the next step's Z (requested below; UG: at the start of that step) has a corner that
+            // the left half of the predecessor's step t+2 wrote
+            if (!UG) publish(s, 2 * t + 1);
+            wait_for(s, 2 * t + 6, seen2);
+            lds_barrier();
+            failed = sh_fail != 0;
+            if (failed) break;
             RMARK(5);
+            if (!UG && traffic) {
+                const Blk zn = block_at(c0 + B, c0 + B);
+#pragma unroll
+                for (int q = 0; q < PER; ++q) pre[q] = gload(zn, q, true);
+            }
             // ---- S5: block reflector onto the other columns of Z and onto A3
             if (UG) {
                 // lines 0 .. B-1: columns D .. B-1 of Z, in LDS; lines B .. 2B-1: the columns of the
