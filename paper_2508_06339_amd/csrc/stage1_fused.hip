@@ -11,7 +11,10 @@
 //     W  = Y_d^T C      (contraction over the rows: C's registers are the B operand)
 //     C -= V_d W        (W's registers are the B operand, C's the accumulators)
 // Y_d and V_d stream through LDS in 32-row slices shared by the 4 waves
-// (double buffered, one barrier per slice).  The trailing matrix is read once
+// (double buffered, one barrier per slice).  Given the domain's triangular factor T_d
+// instead of Y_d, the kernel forms V_d^T C first and then W = T_d^T (V_d^T C) in place
+// (T_d streams through the same buffers in slices of 32 columns, W's registers again
+// the B operand), so that no Y has to be produced between the panel and its update.  The trailing matrix is read once
 // and written once per tree level; W never leaves the registers.
 //
 // Trailing-matrix element (p, q) lives at Cb[p*sp + q*sq]; p runs along the
@@ -64,11 +67,12 @@ __device__ unsigned long long svb_fused_timing[8];
 // in Wb (NB values per domain and column, already negated) and finishes only the first chunk
 // of every domain -- the rows the next tree level and the next panel read; 2 fetches W and
 // finishes the other chunks, and can run beside the next panel.
-template <typename T, typename C, int NB, int HT, bool LQ, bool TRI, int MODE>
+template <typename T, typename C, int NB, int HT, bool LQ, bool TRI, int MODE, bool USET>
 __global__ __launch_bounds__((FusedGeom<C, NB>::NT), (sizeof(C) == 8 && NB == 128) ? 1 : 2) void update_fused_kernel(T* __restrict__ Cb, int64_t lda, int64_t qlen,
                                                            const C* __restrict__ V, const C* __restrict__ Y,
                                                            int64_t ldp, int chunks, int g, int64_t stride,
-                                                           int strips, int total, C* __restrict__ Wb)
+                                                           int strips, int total, C* __restrict__ Wb,
+                                                           const C* __restrict__ Tw)
 {
     using F = Frag<C>;
     using G = FusedGeom<C, NB>;
@@ -151,6 +155,28 @@ __global__ __launch_bounds__((FusedGeom<C, NB>::NT), (sizeof(C) == 8 && NB == 12
         }
     };
 
+    // T_d (column-major, NB x NB, upper triangular): columns 32*ts .. 32*ts+31 are one contiguous
+    // piece; in LDS [column][row] with the row length of a V slice
+    const C* Td = USET ? Tw + (int64_t)d * NB * NB : nullptr;
+    auto tslice_ld = [&](int ts) {
+#pragma unroll
+        for (int e = 0; e < NLD; ++e)
+            VecIO<C, C>::ld(&Td[(int64_t)ts * RC * NB + (int64_t)(tid + e * G::NT) * NV], sreg[e]);
+    };
+    auto tslice_st = [&](C* buf) {
+#pragma unroll
+        for (int e = 0; e < NLD; ++e) {
+            const int off = (tid + e * G::NT) * NV;
+            const int kk = off / NB, j = off % NB;
+            if constexpr (sizeof(C) == 4) {
+                VecIO<C, C>::st(&buf[kk * LDC + j], sreg[e]);
+            } else {
+#pragma unroll
+                for (int jj = 0; jj < NV; ++jj) buf[kk * LDC + j + jj] = sreg[e][jj];
+            }
+        }
+    };
+
     // barrier that orders LDS traffic only (s_waitcnt lgkmcnt(0); s_barrier): __syncthreads()
     // would also wait for every outstanding global load and store
     auto lds_barrier = [] {
@@ -168,6 +194,9 @@ __global__ __launch_bounds__((FusedGeom<C, NB>::NT), (sizeof(C) == 8 && NB == 12
     // this lane's part of W in the copy: rows 16*mt + roff(r, gq) of column q of domain d
     C* wcol = (MODE != 0) ? Wb + ((int64_t)d * qlen + q) * NB : nullptr;
 
+    constexpr bool useT = USET && MODE != 2;   // (Tw is null otherwise)
+    const C* __restrict__ Y1 = useT ? V : Y;   // operand of the first product
+    constexpr int NTS = NB / RC;               // slices of T
     int cur = 0;
     if (MODE == 2) {
         slice_ld(V, vlo);
@@ -185,7 +214,7 @@ __global__ __launch_bounds__((FusedGeom<C, NB>::NT), (sizeof(C) == 8 && NB == 12
         }
         slice_st_v(smem);
     } else {
-        slice_ld(Y, 0);
+        slice_ld(Y1, 0);
 #pragma unroll
         for (int t = 0; t < PF; ++t) tile_ld(t);
         slice_st_y(smem);
@@ -204,8 +233,10 @@ __global__ __launch_bounds__((FusedGeom<C, NB>::NT), (sizeof(C) == 8 && NB == 12
             // product's first slice after the first product's last
             const bool last = ck + 1 == (isV ? vhi : nck);
             const bool have_next = !(isV && last);
+            const bool nextT = !isV && last && useT;   // T's last column slice comes first
             const bool nextV = isV || last;
-            if (have_next) slice_ld(nextV ? V : Y, last ? vlo : ck + 1);
+            if (nextT) tslice_ld(NTS - 1);
+            else if (have_next) slice_ld(nextV ? V : Y1, last ? vlo : ck + 1);
             if (!isV || MODE == 2) {
 #pragma unroll
                 for (int tt = 0; tt < RC / 16; ++tt)
@@ -235,7 +266,7 @@ __global__ __launch_bounds__((FusedGeom<C, NB>::NT), (sizeof(C) == 8 && NB == 12
                                     if (m0 + m >= rb) w[m0 + m] = F::mma(a[m][r], c[t][r], w[m0 + m]);
                         }
                     }
-                    if (last) {
+                    if (last && !useT) {
 #pragma unroll
                         for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
@@ -269,24 +300,62 @@ __global__ __launch_bounds__((FusedGeom<C, NB>::NT), (sizeof(C) == 8 && NB == 12
             FT_MARK(isV ? 3 : 2);
             if (have_next) {
                 C* nbuf = smem + (cur ^ 1) * BUF;
-                if (nextV) slice_st_v(nbuf);
+                if (nextT) tslice_st(nbuf);
+                else if (nextV) slice_st_v(nbuf);
                 else slice_st_y(nbuf);
             }
             FT_MARK(4);
             lds_barrier();
             FT_MARK(5);
             cur ^= 1;
+            if (nextT) {
+                // ---- W = -T^T W, tile rows from the last to the first: tile m of the result needs
+                // tiles 0 .. m of the operand (T is upper triangular), which are still untouched
+#pragma unroll
+                for (int ts = NTS - 1; ts >= 0; --ts) {
+                    if (ts > 0) tslice_ld(ts - 1);
+                    else slice_ld(V, vlo);
+                    const C* tb = smem + cur * BUF;
+                    if (active) {
+#pragma unroll
+                        for (int mm = RC / 16 - 1; mm >= 0; --mm) {
+                            const int m = ts * (RC / 16) + mm;
+                            acc_t acc;
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) acc[r] = 0;
+#pragma unroll
+                            for (int mt = 0; mt <= m; ++mt) {
+                                C a[4];
+                                F::ld4(&tb[(16 * mm + i) * LDC + 16 * mt], gq, a);
+#pragma unroll
+                                for (int r = 0; r < 4; ++r) acc = F::mma(a[r], w[mt][r], acc);
+                            }
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) w[m][r] = -acc[r];
+                            if (MODE == 1) {
+                                const C o[4] = {w[m][0], w[m][1], w[m][2], w[m][3]};
+                                F::st4(wcol + 16 * m, gq, o);
+                            }
+                        }
+                    }
+                    C* nbuf = smem + (cur ^ 1) * BUF;
+                    if (ts > 0) tslice_st(nbuf);
+                    else slice_st_v(nbuf);
+                    lds_barrier();
+                    cur ^= 1;
+                }
+            }
         }
     }
 }
 #undef FT_MARK
 
-template <typename T, typename C, int NB, int HT, bool LQ, bool TRI, int MODE>
+template <typename T, typename C, int NB, int HT, bool LQ, bool TRI, int MODE, bool USET>
 static void launch_fused(T* Cb, int64_t lda, int64_t qlen, const C* V, const C* Y, int64_t ldp, int chunks,
-                         int g, int64_t stride, C* Wb, bool credited, hipStream_t s)
+                         int g, int64_t stride, C* Wb, const C* Tw, bool credited, hipStream_t s)
 {
     using G = FusedGeom<C, NB>;
-    auto kern = update_fused_kernel<T, C, NB, HT, LQ, TRI, MODE>;
+    auto kern = update_fused_kernel<T, C, NB, HT, LQ, TRI, MODE, USET>;
     static bool attr_set = false;
     if (!attr_set) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -312,17 +381,25 @@ static void launch_fused(T* Cb, int64_t lda, int64_t qlen, const C* V, const C* 
     if (!credited) fl = by = 0.0;
     prof_begin(SVB_PROF_FUSED, s, fl, by);
     hipLaunchKernelGGL(kern, dim3((unsigned)(per * 8)), dim3(G::NT), G::kSmemBytes, s, Cb, lda, qlen, V, Y, ldp,
-                       chunks, g, stride, strips, total, Wb);
+                       chunks, g, stride, strips, total, Wb, Tw);
     prof_end(s);
 }
 
 template <typename T, typename C, int NB, int HT, bool LQ, bool TRI>
 static void launch_fused_mode(int mode, T* Cb, int64_t lda, int64_t qlen, const C* V, const C* Y, int64_t ldp,
-                              int chunks, int g, int64_t stride, C* Wb, bool credited, hipStream_t s)
+                              int chunks, int g, int64_t stride, C* Wb, const C* Tw, bool credited, hipStream_t s)
 {
-    if (mode == 1) launch_fused<T, C, NB, HT, LQ, TRI, 1>(Cb, lda, qlen, V, Y, ldp, chunks, g, stride, Wb, credited, s);
-    else if (mode == 2) launch_fused<T, C, NB, HT, LQ, TRI, 2>(Cb, lda, qlen, V, Y, ldp, chunks, g, stride, Wb, credited, s);
-    else launch_fused<T, C, NB, HT, LQ, TRI, 0>(Cb, lda, qlen, V, Y, ldp, chunks, g, stride, Wb, credited, s);
+    // the form that applies T itself exists for the whole update at nb <= 64 (at nb = 128 the
+    // extra accumulators do not fit beside the block)
+    if constexpr (NB <= 64) {
+        if (Tw != nullptr && mode == 0) {
+            launch_fused<T, C, NB, HT, LQ, TRI, 0, true>(Cb, lda, qlen, V, Y, ldp, chunks, g, stride, Wb, Tw, credited, s);
+            return;
+        }
+    }
+    if (mode == 1) launch_fused<T, C, NB, HT, LQ, TRI, 1, false>(Cb, lda, qlen, V, Y, ldp, chunks, g, stride, Wb, nullptr, credited, s);
+    else if (mode == 2) launch_fused<T, C, NB, HT, LQ, TRI, 2, false>(Cb, lda, qlen, V, Y, ldp, chunks, g, stride, Wb, nullptr, credited, s);
+    else launch_fused<T, C, NB, HT, LQ, TRI, 0, false>(Cb, lda, qlen, V, Y, ldp, chunks, g, stride, Wb, nullptr, credited, s);
 }
 
 template <typename C> constexpr int fused_tiles() { return sizeof(C) == 4 ? 32 : 16; }
@@ -335,11 +412,11 @@ template int fused_update_rows<double>();
 template <typename T, typename C>
 void launch_update_fused(int nb, bool lq, T* Cb, int64_t lda, int64_t qlen, const C* V, const C* Y,
                          int64_t ldp, int chunks, int g, int64_t stride, bool tri, int mode, C* Wb,
-                         bool credited, hipStream_t s)
+                         const C* Tw, bool credited, hipStream_t s)
 {
     if (qlen <= 0) return;
     constexpr int HT = fused_tiles<C>();
-#define SVB_FUSED_ARGS mode, Cb, lda, qlen, V, Y, ldp, chunks, g, stride, Wb, credited, s
+#define SVB_FUSED_ARGS mode, Cb, lda, qlen, V, Y, ldp, chunks, g, stride, Wb, Tw, credited, s
 #define SVB_FUSED_CASE(NBV)                                                          \
     case NBV:                                                                        \
         if (lq && tri) launch_fused_mode<T, C, NBV, HT, true, true>(SVB_FUSED_ARGS);   \
@@ -357,8 +434,8 @@ void launch_update_fused(int nb, bool lq, T* Cb, int64_t lda, int64_t qlen, cons
 #undef SVB_FUSED_ARGS
 }
 
-template void launch_update_fused<float, float>(int, bool, float*, int64_t, int64_t, const float*, const float*, int64_t, int, int, int64_t, bool, int, float*, bool, hipStream_t);
-template void launch_update_fused<__half, float>(int, bool, __half*, int64_t, int64_t, const float*, const float*, int64_t, int, int, int64_t, bool, int, float*, bool, hipStream_t);
-template void launch_update_fused<double, double>(int, bool, double*, int64_t, int64_t, const double*, const double*, int64_t, int, int, int64_t, bool, int, double*, bool, hipStream_t);
+template void launch_update_fused<float, float>(int, bool, float*, int64_t, int64_t, const float*, const float*, int64_t, int, int, int64_t, bool, int, float*, const float*, bool, hipStream_t);
+template void launch_update_fused<__half, float>(int, bool, __half*, int64_t, int64_t, const float*, const float*, int64_t, int, int, int64_t, bool, int, float*, const float*, bool, hipStream_t);
+template void launch_update_fused<double, double>(int, bool, double*, int64_t, int64_t, const double*, const double*, int64_t, int, int, int64_t, bool, int, double*, const double*, bool, hipStream_t);
 
 }  // namespace svb

@@ -456,6 +456,7 @@ void launch_panel_qr(int nb, C* P, int64_t ldp, C* Y, C* Tws, int chunks, int g,
         if (blk) launch_panel_blk<T, C>(nb, P, ldp, Tws, chunks, g, Pnext, ldnext, Asrc, lda, lq, band, ldab, row0, col0, s);
         else PanelRegDispatch<C>::run(nb, P, ldp, Tws, chunks, g, Pnext, ldnext, s);
         const int64_t rows = (int64_t)chunks * nb;
+        if (Y == nullptr) return;   // the caller applies T itself
         if (nb == 32) launch_panel_y<C, 32>(P, Y, Tws, ldp, rows, g, s);
         else if (nb == 64) launch_panel_y<C, 64>(P, Y, Tws, ldp, rows, g, s);
         else launch_panel_y<C, 128>(P, Y, Tws, ldp, rows, g, s);

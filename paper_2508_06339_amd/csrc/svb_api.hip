@@ -277,28 +277,30 @@ void g_la_release() { g_la.release(); }
 
 // Stage 1 driver, level pipeline (the default with the one-pass update).  The tree levels of a
 // panel depend on each other only through the R factors, not through the trailing matrix, so
-// once level L of the panel is factored its update can start while level L+1 is being
-// factored:  panel stream  P0 | P1 | P2 ...     update stream  . | U0 | U1 | U2
-// The next half-sweep's panel waits for the last update.  The update stream is confined to 240
-// of the 256 compute units (two per XCD are left out), so that the one or few workgroups of
-// the upper panel levels, each of which needs a compute unit of its own, start at once.
+// once level L of the panel is factored its update U_L can run while level L+1 is being factored.
+// Two internal streams:   main: P0 P1 .. Pl Ul P0' ..      side: U0 .. Ul-1
+// The last level's update and the next half-sweep's first panel follow the panel tree on the main
+// stream: a dependency that crosses streams costs two to three times what one inside a stream
+// does (measured), and for all but the largest trailing matrices the panel tree is the longer
+// chain of a half-sweep.  (SVB_PIPELINE_LAYOUT=0: every update on the side stream.)
 template <typename T, typename C>
 int ge2gb_pipeline(int64_t n, T* A, int64_t lda, int nb, C* band, int64_t ldab, unsigned char* work,
                    const Carve& cv, int g, hipStream_t caller)
 {
     const int64_t N = n / nb;
     Level lv[kMaxLevels];
-    hipStream_t ps = g_la.m, us = g_la.u;
+    hipStream_t ms = g_la.m, ss = g_la.u;
     (void)hipEventRecord(g_la.fork, caller);
-    (void)hipStreamWaitEvent(ps, g_la.fork, 0);
-    (void)hipStreamWaitEvent(us, g_la.fork, 0);
-    launch_band_clear<C>(band, ldab, n, ps);
+    (void)hipStreamWaitEvent(ms, g_la.fork, 0);
+    (void)hipStreamWaitEvent(ss, g_la.fork, 0);
+    launch_band_clear<C>(band, ldab, n, ms);
     C* Vb = reinterpret_cast<C*>(work + cv.off_V[0]);
     C* Yb = reinterpret_cast<C*>(work + cv.off_Y[0]);
     C* Tb = reinterpret_cast<C*>(work + cv.off_T[0]);
     const bool direct = panel_blk_serves<C>(nb, g);
+    const int layout = env_int("SVB_PIPELINE_LAYOUT", 1);
     int hs = 0;
-    bool updated = false;   // an update of the previous half-sweep is in flight
+    bool side_pending = false;
     for (int64_t k = 0; k < N; ++k) {
         for (int half = 0; half < 2; ++half) {
             const bool lq = half == 1;
@@ -307,39 +309,75 @@ int ge2gb_pipeline(int64_t n, T* A, int64_t lda, int nb, C* band, int64_t ldab, 
             const int64_t row0 = k * nb;
             const int64_t col0 = lq ? (k + 1) * nb : k * nb;
             const int64_t len = lq ? n - (k + 1) * nb : n - k * nb;
+            const int64_t qlen = n - (k + 1) * nb;
             const int nl = build_levels(len, nb, g, lv);
-            if (updated) (void)hipStreamWaitEvent(ps, g_la.udone[(hs - 1) & 1], 0);
-            g_prof.begin(SVB_PROF_PANEL, ps, 2.0 * (double)len * nb * nb, 0.0);
-            if (!direct) launch_panel_gather<T, C>(A, lda, row0, col0, lq, len, nb, Vb + lv[0].poff, lv[0].ldp, ps);
+            // every level keeps its own T factors until its update has run: the update applies
+            // them itself (no Y = V T between a panel and its update) where they all fit
+            int64_t toff[kMaxLevels], tsum = 0;
             for (int L = 0; L < nl; ++L) {
+                toff[L] = tsum;
+                tsum += (int64_t)lv[L].domains * nb * nb;
+            }
+            const bool useT = direct && nb <= 64 && tsum <= (int64_t)cv.t_elems && env_int("SVB_UPDATE_T", 1) != 0;
+            const bool split = layout == 0 && qlen > 0;
+            T* Cb = lq ? A + (k + 1) * nb + (k + 1) * nb * lda : A + k * nb + (k + 1) * nb * lda;
+            auto panel = [&](int L, hipStream_t st) {
                 const int64_t next_off = lv[L].poff + lv[L].ldp * nb;
                 const int64_t ldnext = (int64_t)lv[L].domains * nb;
                 const bool last = L == nl - 1;
-                launch_panel_qr<T, C>(nb, Vb + lv[L].poff, lv[L].ldp, Yb + lv[L].poff, Tb, lv[L].chunks, g,
+                g_prof.begin(SVB_PROF_PANEL, st, L == 0 ? 2.0 * (double)len * nb * nb : 0.0, 0.0);
+                if (L == 0 && !direct)
+                    launch_panel_gather<T, C>(A, lda, row0, col0, lq, len, nb, Vb + lv[0].poff, lv[0].ldp, st);
+                launch_panel_qr<T, C>(nb, Vb + lv[L].poff, lv[L].ldp, useT ? (C*)nullptr : Yb + lv[L].poff,
+                                      useT ? Tb + toff[L] : Tb, lv[L].chunks, g,
                                       Vb + next_off, ldnext, (direct && L == 0) ? A + row0 + col0 * lda : nullptr, lda, lq,
-                                      (direct && last) ? band : nullptr, ldab, row0, col0, ps);
+                                      (direct && last) ? band : nullptr, ldab, row0, col0, st);
                 if (last && !direct)
-                    launch_scatter_r<C>(Vb + next_off, ldnext, nb, band, ldab, row0, col0, lq, ps);
-                (void)hipEventRecord(g_la.lvl[set][L], ps);
+                    launch_scatter_r<C>(Vb + next_off, ldnext, nb, band, ldab, row0, col0, lq, st);
+                g_prof.end(st);
+            };
+            auto update = [&](int L, hipStream_t st) {
+                launch_update_fused<T, C>(nb, lq, Cb, lda, qlen, Vb + lv[L].poff, Yb + lv[L].poff, lv[L].ldp,
+                                          lv[L].chunks, g, lv[L].stride, L > 0, 0, (C*)nullptr,
+                                          useT ? Tb + toff[L] : (const C*)nullptr, L == 0, st);
+            };
+            if (side_pending) {
+                // the previous half-sweep left its last update on the side stream
+                (void)hipStreamWaitEvent(ms, g_la.udone[(hs - 1) & 1], 0);
+                side_pending = false;
             }
-            g_prof.end(ps);
-            const int64_t qlen = n - (k + 1) * nb;
-            updated = false;
-            if (qlen > 0) {
-                T* Cb = lq ? A + (k + 1) * nb + (k + 1) * nb * lda : A + k * nb + (k + 1) * nb * lda;
+            if (qlen <= 0) {
+                for (int L = 0; L < nl; ++L) panel(L, ms);
+            } else if (split) {
+                // every panel on the main stream, every update on the side stream
                 for (int L = 0; L < nl; ++L) {
-                    (void)hipStreamWaitEvent(us, g_la.lvl[set][L], 0);
-                    launch_update_fused<T, C>(nb, lq, Cb, lda, qlen, Vb + lv[L].poff, Yb + lv[L].poff, lv[L].ldp,
-                                              lv[L].chunks, g, lv[L].stride, L > 0, 0, (C*)nullptr, L == 0, us);
+                    panel(L, ms);
+                    (void)hipEventRecord(g_la.lvl[set][L], ms);
+                    (void)hipStreamWaitEvent(ss, g_la.lvl[set][L], 0);
+                    update(L, ss);
                 }
-                (void)hipEventRecord(g_la.udone[set], us);
-                updated = true;
+                (void)hipEventRecord(g_la.udone[set], ss);
+                side_pending = true;
+            } else {
+                for (int L = 0; L < nl; ++L) {
+                    panel(L, ms);
+                    if (L < nl - 1) {
+                        (void)hipEventRecord(g_la.lvl[set][L], ms);
+                        (void)hipStreamWaitEvent(ss, g_la.lvl[set][L], 0);
+                        update(L, ss);
+                    }
+                }
+                if (nl > 1) {
+                    (void)hipEventRecord(g_la.udone[set], ss);
+                    (void)hipStreamWaitEvent(ms, g_la.udone[set], 0);
+                }
+                update(nl - 1, ms);
             }
             ++hs;
         }
     }
-    (void)hipEventRecord(g_la.join, ps);
-    (void)hipEventRecord(g_la.join_u, us);
+    (void)hipEventRecord(g_la.join, ms);
+    (void)hipEventRecord(g_la.join_u, ss);
     (void)hipStreamWaitEvent(caller, g_la.join, 0);
     (void)hipStreamWaitEvent(caller, g_la.join_u, 0);
     return hipGetLastError() == hipSuccess ? SVB_OK : SVB_ERR_DEVICE;
@@ -437,7 +475,7 @@ int ge2gb_impl(int64_t n, T* A, int64_t lda, int nb, C* band, int64_t ldab, unsi
                     for (int L = 0; L < nl; ++L)
                         launch_update_fused<T, C>(nb, lq, Cb, lda, qlen, Vb + lv[L].poff, Yb + lv[L].poff,
                                                   lv[L].ldp, lv[L].chunks, g, lv[L].stride, L > 0, defer ? 1 : 0,
-                                                  Wb + woff[L], L == 0, s);
+                                                  Wb + woff[L], (const C*)nullptr, L == 0, s);
                     if (defer) {
                         (void)hipEventRecord(g_la.crit[set], s);
                         (void)hipStreamWaitEvent(g_la.h, g_la.crit[set], 0);
@@ -445,7 +483,7 @@ int ge2gb_impl(int64_t n, T* A, int64_t lda, int nb, C* band, int64_t ldab, unsi
                             if (lv[L].chunks > lv[L].domains)
                                 launch_update_fused<T, C>(nb, lq, Cb, lda, qlen, Vb + lv[L].poff, Yb + lv[L].poff,
                                                           lv[L].ldp, lv[L].chunks, g, lv[L].stride, L > 0, 2,
-                                                          Wb + woff[L], L == 0, g_la.h);
+                                                          Wb + woff[L], (const C*)nullptr, L == 0, g_la.h);
                         (void)hipEventRecord(g_la.rest[set], g_la.h);
                         pending = true;
                     }

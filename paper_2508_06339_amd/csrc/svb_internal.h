@@ -116,10 +116,12 @@ void launch_update(int nb, bool lq, T* Cbase, int64_t lda, int64_t qlen,
 // (tree levels above the first), whose structural zeros in V and Y are skipped.
 // mode 0: the whole update; 1: W formed and stored in W, first chunk of every domain finished;
 // 2: the other chunks finished from the stored W (may run beside the next panel).
+// Tw: the domains' triangular factors (NB x NB each, column-major); if given (mode 0, nb <= 64
+// only), Y is not read and W = T^T (V^T C) is formed inside the kernel.
 template <typename T, typename C>
 void launch_update_fused(int nb, bool lq, T* Cbase, int64_t lda, int64_t qlen, const C* V, const C* Y,
                          int64_t ldp, int chunks, int g, int64_t stride, bool tri, int mode, C* W,
-                         bool credited, hipStream_t s);
+                         const C* Tw, bool credited, hipStream_t s);
 template <typename C> int fused_update_rows();
 
 // per-kernel timing hooks (no-ops unless profiling is enabled)
