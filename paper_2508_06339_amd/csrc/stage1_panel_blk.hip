@@ -475,24 +475,48 @@ template <typename C> int panel_blk_rows() { return panel_blk_tiles<C>() * 16; }
 template int panel_blk_rows<float>();
 template int panel_blk_rows<double>();
 
+template <typename T, typename C, int NB, int HT, bool TRI>
+static void launch_blk_ht(C* P, int64_t ldp, C* Tws, int chunks, int g, C* Pnext, int64_t ldnext,
+                          const PanelEnds<T, C>& ends, hipStream_t s)
+{
+    using G = PanelBlkGeom<C, NB, HT>;
+    auto kern = panel_qr_blk_kernel<T, C, NB, HT, TRI>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  (int)G::kSmemBytes);
+        attr_set = true;
+    }
+    const int domains = (chunks + g - 1) / g;
+    hipLaunchKernelGGL(kern, dim3(domains), dim3(G::NT), G::kSmemBytes, s, P, ldp, Tws, chunks, g, Pnext, ldnext, ends);
+}
+
 template <typename T, typename C, int NB>
 static void launch_blk(C* P, int64_t ldp, C* Tws, int chunks, int g, C* Pnext, int64_t ldnext,
                        const PanelEnds<T, C>& ends, hipStream_t s)
 {
     constexpr int HT = panel_blk_tiles<C>();
-    using G = PanelBlkGeom<C, NB, HT>;
-    // a panel that does not come from the matrix is a stack of triangular factors
-    auto kern = ends.Asrc ? panel_qr_blk_kernel<T, C, NB, HT, false> : panel_qr_blk_kernel<T, C, NB, HT, true>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(panel_qr_blk_kernel<T, C, NB, HT, false>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)G::kSmemBytes);
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(panel_qr_blk_kernel<T, C, NB, HT, true>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)G::kSmemBytes);
-        attr_set = true;
+    // a panel that does not come from the matrix is a stack of triangular factors; near the top of
+    // the tree such a stack is short, and a kernel sized for it (fewer rows per thread in the
+    // reflector steps, fewer tiles in the block products) is faster than the full-height one
+    if (ends.Asrc) {
+        launch_blk_ht<T, C, NB, HT, false>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, s);
+        return;
     }
-    const int domains = (chunks + g - 1) / g;
-    hipLaunchKernelGGL(kern, dim3(domains), dim3(G::NT), G::kSmemBytes, s, P, ldp, Tws, chunks, g, Pnext, ldnext, ends);
+    const int need = (chunks < g ? chunks : g) * NB / 16;   // tiles of the tallest domain
+    if constexpr (HT / 4 * 16 >= NB) {
+        if (need <= HT / 4) {
+            launch_blk_ht<T, C, NB, HT / 4, true>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, s);
+            return;
+        }
+    }
+    if constexpr (HT / 2 * 16 >= NB) {
+        if (need <= HT / 2) {
+            launch_blk_ht<T, C, NB, HT / 2, true>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, s);
+            return;
+        }
+    }
+    launch_blk_ht<T, C, NB, HT, true>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, s);
 }
 
 template <typename T, typename C>

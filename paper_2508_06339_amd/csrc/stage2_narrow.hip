@@ -194,9 +194,20 @@ __device__ __forceinline__ void narrow_half4_fast(C* win, int i, int t, bool act
         C v[D], a[D];
 #pragma unroll
         for (int jj = 0; jj < D; ++jj) { v[jj] = pv[jj * SV]; a[jj] = pa[jj * SV]; }
-        C ss = 0;
+        // sum of squares of the pivot's tail and its product with this lane's line, two chains
+        // each, both independent of the reflector's scalars: the tail is used unscaled,
+        //   H a = a - s (1, inv * tail),  s = tau (a_0 + inv * tail^T a_tail)
+        C ssa = v[1] * v[1], ssb = v[2] * v[2], da = v[1] * a[1], db = v[2] * a[2];
 #pragma unroll
-        for (int jj = 1; jj < D; ++jj) ss += v[jj] * v[jj];
+        for (int jj = 3; jj < D; jj += 2) {
+            ssa += v[jj] * v[jj];
+            da += v[jj] * a[jj];
+            if (jj + 1 < D) {
+                ssb += v[jj + 1] * v[jj + 1];
+                db += v[jj + 1] * a[jj + 1];
+            }
+        }
+        const C ss = ssa + ssb;
         // the reflector without a branch: with ss = 0 the selects give H = I whatever the
         // discarded operands evaluate to
         const C alpha = v[0];
@@ -211,23 +222,18 @@ __device__ __forceinline__ void narrow_half4_fast(C* win, int i, int t, bool act
         const C beta = ident ? alpha : bc;
         const C tau = ident ? (C)0 : (bc - alpha) * fast_rcp(bc);
         const C inv = ident ? (C)0 : fast_rcp(alpha - bc);
-        v[0] = (C)1;
-        C s = a[0];
-#pragma unroll
-        for (int jj = 1; jj < D; ++jj) {
-            v[jj] *= inv;
-            s += v[jj] * a[jj];
-        }
-        s *= tau;
+        const C s = tau * (a[0] + inv * (da + db));
+        const C w = s * inv;
         if (sub < D) pv[sub * SV] = (sub == 0) ? beta : (C)0;
+        pa[0] = a[0] - s;
 #pragma unroll
-        for (int jj = 0; jj < D; ++jj) pa[jj * SV] = a[jj] - s * v[jj];
+        for (int jj = 1; jj < D; ++jj) pa[jj * SV] = a[jj] - w * v[jj];
     }
 }
 
 // One super-step of a wave: the half step h of each of its four sweeps, then the workgroup barrier.
 template <typename C, int D, int WC, bool LEFT>
-__device__ __forceinline__ void narrow_super_step(C* win, C* vbuf, int my_i, int64_t h, bool have, int64_t my_steps, int n)
+__device__ __forceinline__ void narrow_super_step(C* win, C* vbuf, int my_i, int h, bool have, int my_steps, int n)
 {
     const bool act = have && h >= 0 && h < 2 * my_steps;
     const int tt = act ? (int)(h >> 1) : 0;
@@ -364,9 +370,9 @@ __global__ __launch_bounds__(NW * 16) void chase_narrow_kernel(C* __restrict__ b
                 }
             }
             for (int hp = 0; hp < GS; ++hp) {
-                const int64_t h = g * 2 * GS + 2 * hp - 4 * slot;      // this sweep's half step (right, then left)
-                narrow_super_step<C, D, WC, false>(win, vbuf, (int)my_i, h, have, my_steps, (int)n);
-                narrow_super_step<C, D, WC, true>(win, vbuf, (int)my_i, h + 1, have, my_steps, (int)n);
+                const int h = (int)g * 2 * GS + 2 * hp - 4 * slot;      // this sweep's half step (right, then left)
+                narrow_super_step<C, D, WC, false>(win, vbuf, (int)my_i, h, have, (int)my_steps, (int)n);
+                narrow_super_step<C, D, WC, true>(win, vbuf, (int)my_i, h + 1, have, (int)my_steps, (int)n);
             }
             NMARK(1);
             if (want) {
