@@ -3,14 +3,15 @@
 // the CPU with LAPACK and names it the cheapest stage.  Once stages 1-2 run
 // in tens of milliseconds a host solve dominates time-to-singular-values, so
 // the same bisection that the host entry point svb_bdsvals performs is also
-// available on the GPU, one singular value per thread).
+// available on the GPU).
 //
 // Count of singular values below x: with B^T B - x^2 I = L D L^T,
 //   t_1 = -x^2,  D_j = d_j^2 + t_j,  t_{j+1} = -x^2 + e_j^2 * t_j / D_j,
 // the number of negative D_j (the differential stationary qd form of the Sturm
 // sequence: one division per row, n rows).  Squares are taken after scaling by
 // the largest entry, always in fp64.  A first kernel counts at 1024 shared points of
-// [0, bound]; every singular value then starts its bisection from the cell it falls in.
+// [0, bound]; every singular value then starts from the cell it falls in and is refined by
+// multisection (several points per round, one lane each).
 #include "svb_internal.h"
 
 namespace svb {
@@ -122,18 +123,25 @@ __global__ __launch_bounds__(64) void bd_grid_kernel(const double* __restrict__ 
     if (i == 0) gcnt[kGrid] = (int)n;
 }
 
-template <typename C>
-__global__ __launch_bounds__(64) void bd_bisect_kernel(const double* __restrict__ ws, int64_t n,
-                                                        C* __restrict__ sigma, double rel_tol,
-                                                        const int* __restrict__ gcnt)
+// Multisection: P lanes per singular value, each counting at one of P equally spaced interior
+// points of the value's current interval, which shrinks by P + 1 per round (P = 1 is plain
+// bisection).  The Sturm recurrence is one long dependent chain per point and a wave costs the
+// same whether it refines 64 values by 2 or 4 values by 17 per round, so while the compute
+// units have waves to spare the extra points are free and the number of rounds drops.
+template <typename C, int P>
+__global__ __launch_bounds__(64) void bd_multisect_kernel(const double* __restrict__ ws, int64_t n,
+                                                           C* __restrict__ sigma, double rel_tol,
+                                                           const int* __restrict__ gcnt)
 {
-    const int64_t kraw = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;  // ascending index
+    constexpr int VPW = kWave / P;   // values per wave
+    const int lane = threadIdx.x, grp = lane / P, q = lane % P;
+    const int64_t kraw = (int64_t)blockIdx.x * VPW + grp;  // ascending index
     const int64_t k = min(kraw, n - 1);   // surplus lanes repeat the last value: the wave stays whole
     const double scale = ws[0], hi0 = ws[1];
     const double* __restrict__ d2 = ws + 8;
     const double* __restrict__ e2 = d2 + n;
     if (scale != scale) {  // non-finite input: poison the output, the caller maps it to a status
-        if (kraw < n) sigma[n - 1 - k] = (C)NAN;
+        if (kraw < n && q == 0) sigma[n - 1 - k] = (C)NAN;
         return;
     }
     // first interval from the shared partition: gcnt[a] < k+1 <= gcnt[b] with b = a+1
@@ -144,17 +152,28 @@ __global__ __launch_bounds__(64) void bd_bisect_kernel(const double* __restrict_
         else a = m;
     }
     double lo = hi0 * ((double)a / kGrid), hi = b == kGrid ? hi0 : hi0 * ((double)b / kGrid);
+    const double frac = (double)(q + 1) / (P + 1);
     for (int it = 0; it < 200; ++it) {
-        const double mid = 0.5 * (lo + hi);
-        const bool open = (hi - lo > rel_tol * hi + 1e-38 * hi0) && (mid > lo && mid < hi);
+        const double w = hi - lo, mid = 0.5 * (lo + hi);
+        const bool open = (w > rel_tol * hi + 1e-38 * hi0) && (mid > lo && mid < hi);
         if (!__any(open)) break;            // wave-uniform exit: the row hand-over needs every lane
-        const int64_t cnt = sturm_count(d2, e2, n, mid * mid);
+        // this lane's point; rounding may put it on an end of the interval, where the count is known
+        const double x = fmin(fmax(fma(w, frac, lo), lo), hi);
+        const int64_t cnt = sturm_count(d2, e2, n, x * x);
+        const bool above = x >= hi || (x > lo && cnt >= k + 1);   // the value lies below this point
+        // the points of a value are ascending, so its lanes read: below .. below, above .. above
+        const unsigned long long m = __ballot(above) >> (grp * P);
+        const unsigned long long mine = P == 64 ? m : (m & ((1ull << P) - 1ull));
+        const int f = mine ? __builtin_ctzll(mine) : P;          // first point above the value
         if (open) {
-            if (cnt >= k + 1) hi = mid;
-            else lo = mid;
+            // (the same expressions the lanes f - 1 and f evaluated their points with)
+            const double nlo = f == 0 ? lo : fmin(fmax(fma(w, (double)f / (P + 1), lo), lo), hi);
+            const double nhi = f == P ? hi : fmin(fmax(fma(w, (double)(f + 1) / (P + 1), lo), lo), hi);
+            lo = nlo;
+            hi = nhi;
         }
     }
-    if (kraw < n) sigma[n - 1 - k] = (C)(0.5 * (lo + hi) * scale);
+    if (kraw < n && q == 0) sigma[n - 1 - k] = (C)(0.5 * (lo + hi) * scale);
 }
 
 }  // namespace
@@ -169,7 +188,18 @@ int run_bdsvals_dev(int64_t n, const C* d, const C* e, C* sigma, void* work, dou
     hipLaunchKernelGGL((bd_prep_kernel<C>), dim3(1), dim3(kPrepThreads), 0, s, d, e, n, ws);
     int* gcnt = reinterpret_cast<int*>(ws + 8 + 2 * n);
     hipLaunchKernelGGL(bd_grid_kernel, dim3(kGrid / 64), dim3(64), 0, s, ws, n, gcnt);
-    hipLaunchKernelGGL((bd_bisect_kernel<C>), dim3((unsigned)((n + 63) / 64)), dim3(64), 0, s, ws, n, sigma, rel_tol, gcnt);
+    // points per value: as many as keep the launch at about two waves per SIMD
+    int p = env_int("SVB_STAGE3_POINTS", 0);
+    if (p <= 0) p = n <= 8192 ? 16 : (n <= 16384 ? 8 : (n <= 32768 ? 4 : (n <= 65536 ? 2 : 1)));
+    auto launch = [&](auto kern, int pp) {
+        const int vpw = kWave / pp;
+        hipLaunchKernelGGL(kern, dim3((unsigned)((n + vpw - 1) / vpw)), dim3(64), 0, s, ws, n, sigma, rel_tol, gcnt);
+    };
+    if (p >= 16) launch(bd_multisect_kernel<C, 16>, 16);
+    else if (p >= 8) launch(bd_multisect_kernel<C, 8>, 8);
+    else if (p >= 4) launch(bd_multisect_kernel<C, 4>, 4);
+    else if (p >= 2) launch(bd_multisect_kernel<C, 2>, 2);
+    else launch(bd_multisect_kernel<C, 1>, 1);
     return hipGetLastError() == hipSuccess ? SVB_OK : SVB_ERR_DEVICE;
 }
 

@@ -276,6 +276,31 @@ def test_stage3_device_closed_form_and_oracle(dtype, n):
         assert np.all(np.isnan(run(bad, eh)))
 
 
+@pytest.mark.parametrize("points", [1, 2, 4, 8, 16])
+def test_stage3_device_points_per_value(monkeypatch, points):
+    # every multisection width against the oracle's bidiagonal solver, f64 and f32, a size that
+    # leaves the last wave partly filled
+    monkeypatch.setenv("SVB_STAGE3_POINTS", str(points))
+    n = 777
+    for dtype in ("f64", "f32"):
+        tdt = TORCH_DT[dtype]
+        code = svb.SVB_F64 if dtype == "f64" else svb.SVB_F32
+        eps = workloads.EPS[dtype]
+        rc, wb = svb.svb_bdsvals_dev_workspace_bytes(n)
+        work = torch.empty(wb, dtype=torch.uint8, device="cuda")
+        dh = workloads.normal(191 + points, 0, n).astype(workloads.NP_DTYPE[dtype]).astype(np.float64)
+        eh = workloads.normal(192 + points, 0, n - 1).astype(workloads.NP_DTYPE[dtype]).astype(np.float64)
+        d = torch.from_numpy(dh).to(tdt).cuda()
+        e = torch.from_numpy(np.concatenate([eh, [0.0]])).to(tdt).cuda()
+        sig = torch.zeros(n, dtype=tdt, device="cuda")
+        assert svb.svb_bdsvals_dev(code, n, d, e, sig, 0.0, work, wb) == 0
+        torch.cuda.synchronize()
+        s = sig.cpu().numpy().astype(np.float64)
+        ref = oracle.bdsvals(dh, eh)
+        assert np.all(np.diff(s) <= 0)
+        assert np.abs(s - ref).max() <= 64 * eps * ref[0]
+
+
 def test_host_stage3_variant(monkeypatch):
     monkeypatch.setenv("SVB_STAGE3", "host")
     a, info = workloads.make("c2", n=256, nb=32)
