@@ -467,7 +467,7 @@ __global__ __launch_bounds__(ReduceShape<B>::NT) void band_reduce_kernel(C* __re
     C* S = reinterpret_cast<C*>(smem_raw);        // rows c0-B .. c0+B-1 (UG: c0 ..), columns c0 .. c0+B-1: S[row + col*LD]
     C* Vs = S + ((B * LD + 3) & ~3);              // (B + 4) * D
     C* Ts = Vs + (B + 4) * D;                     // D * D
-    __shared__ int sh_s, sh_fail;
+    __shared__ int sh_s, sh_fail, sh_back;   // sh_back: traffic waves whose stores of a block have been acknowledged
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);       // wave-uniform: scalar branches below
     const bool pw = wv == SH::PWV;
@@ -533,12 +533,27 @@ __global__ __launch_bounds__(ReduceShape<B>::NT) void band_reduce_kernel(C* __re
         }
     };
 
+    // A block written back by the traffic waves is published by the last of them to have its
+    // stores acknowledged, not by the panel wave at the next barrier, which comes up to a
+    // panel factorisation later: the successor sweep is waiting for exactly this.
+    auto block_back = [&](int64_t s, int value) {
+        stores_done();
+        if (lane == 0) {
+            const int arrived = atomicAdd(&sh_back, 1);
+            if (arrived == SH::NTW - 1) {
+                sh_back = 0;
+                __hip_atomic_store(&progress[s], value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+    };
+
     // Every single-lane section is followed by a barrier before the next one (no divergent
     // region spans a loop back-edge).
     for (;;) {
         if (lead) {
             sh_s = atomicAdd(&ctrl[0], 1);
             sh_fail = __hip_atomic_load(&ctrl[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            sh_back = 0;
         }
         __syncthreads();
         const int64_t s = sh_s;
@@ -621,7 +636,7 @@ __global__ __launch_bounds__(ReduceShape<B>::NT) void band_reduce_kernel(C* __re
 #pragma unroll
                 for (int q = 0; q < PER; ++q)
                     if (inside(zp, q)) gstore(zp, q, pre[q]);
-                stores_done();
+                block_back(s, 2 * t);   // every block of step t-1 is final
             }
             RMARK(0);
             // UG: every wave's band stores of the previous step (and the panel's) are acknowledged
@@ -632,7 +647,7 @@ __global__ __launch_bounds__(ReduceShape<B>::NT) void band_reduce_kernel(C* __re
             // ---- S2: publish the previous step; the block right of Z (requested or transformed in
             // place from here on) was last touched by the right half of the predecessor's step
             // t+2, whose result is that step's upper block
-            if (t > 0) publish(s, 2 * t);
+            if (UG && t > 0) publish(s, 2 * t);
             wait_for(s, 2 * t + 5, seen1);
             lds_barrier();
             failed = sh_fail != 0;
@@ -689,13 +704,12 @@ __global__ __launch_bounds__(ReduceShape<B>::NT) void band_reduce_kernel(C* __re
 #pragma unroll
                 for (int q = 0; q < PER; ++q)
                     if (inside(ub, q) && ii >= xoff) gstore(ub, q, pre[q]);
-                stores_done();
+                block_back(s, 2 * t + 1);   // U is final
             }
             RMARK(4);
             lds_barrier();
             // the next step's Z (requested below; UG: at the start of that step) has a corner that
             // the left half of the predecessor's step t+2 wrote
-            if (!UG) publish(s, 2 * t + 1);
             wait_for(s, 2 * t + 6, seen2);
             lds_barrier();
             failed = sh_fail != 0;
