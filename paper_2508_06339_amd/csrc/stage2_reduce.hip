@@ -21,8 +21,9 @@
 // whole step final) and a sweep follows its predecessor a little over two steps behind.
 //
 // Per step the workgroup holds the upper block U (rows c0-B .., the previous step's A3) and Z
-// stacked in LDS (2B x B); A3 is requested after the right panel and the next step's Z after
-// the left panel, and they take the place of U and Z once those have been written back, so
+// stacked in LDS (2B x B); a step's Z is requested at its start and A3 at the start of the left
+// panel, as late as the panel factorisations still hide the latency (every request waits for the
+// predecessor sweep), and they take the place of Z and U once those have been written back, so
 // every block is read once and written once per sweep.  One wave factors the panels while the
 // others do that traffic.
 //
@@ -590,6 +591,7 @@ __global__ __launch_bounds__(ReduceShape<B>::NT) void band_reduce_kernel(C* __re
         }
         __syncthreads();
         RMARK(7);
+        int seen_next = 0;   // the predecessor's progress as polled during the previous step's last phase
         for (int t = 0; t < nsteps && !failed; ++t) {
             const int64_t c0 = c00 + (int64_t)t * B;
             const int xoff = (t == 0) ? B - D : 0;
@@ -600,10 +602,18 @@ __global__ __launch_bounds__(ReduceShape<B>::NT) void band_reduce_kernel(C* __re
 #ifdef SVB_CHASE_TIMING
             if (lead) { tlast = wall_clock64(); ++nstep_acc; }
 #endif
+            if (!UG && t > 0) {
+                // this step's Z (requested in S1) has a corner that the left half of the predecessor's
+                // step t+1 wrote
+                wait_for(s, 2 * t + 4, seen_next);
+                lds_barrier();
+                failed = sh_fail != 0;
+                if (failed) break;
+            }
             // ---- S1: right panel (LQ of X)  ||  Z of the previous step back, this step's Z in
             const int ncol = (int)min((int64_t)B, n - c0);                            // columns c0 .. inside the matrix
             const int64_t rho = (t == 0) ? c00 - D : c0 - B;                          // first row of X
-            const int seen1 = poll(s);
+            const int seen1 = UG ? poll(s) : 0;
             if (pw) {
                 if (UG) panel_wave<C, B, D, true>(band + (rho - c0 + ku) + c0 * ldab, 1, ldm1, Vs, Ts, ncol);
                 else panel_wave<C, B, D>(S + xoff, 1, LD, Vs, Ts);
@@ -620,23 +630,18 @@ __global__ __launch_bounds__(ReduceShape<B>::NT) void band_reduce_kernel(C* __re
                 for (int q = 0; q < PER; ++q)
                     if (jj0 + q * JS < B) S[lds0 + q * JS * LD] = inside(zc, q) ? pre[q] : (C)0;
             } else if (traffic && t > 0) {
-                // two passes: LDS first (one wait for the prefetch), then all stores back to back
-                // (loads and stores complete out of order with each other, so a store between
-                // two uses of prefetched values would be waited for every time)
+                // this step's Z is requested, the previous one goes back from LDS meanwhile and is
+                // published, then the new one takes its place
                 const Blk zp = block_at(c0 - B, c0 - B), zc = block_at(c0, c0);
 #pragma unroll
-                for (int q = 0; q < PER; ++q) {
-                    if (jj0 + q * JS < B) {
-                        const int li = ZO + lds0 + q * JS * LD;
-                        const C old = S[li];
-                        S[li] = inside(zc, q) ? pre[q] : (C)0;
-                        pre[q] = old;
-                    }
-                }
+                for (int q = 0; q < PER; ++q) pre[q] = gload(zc, q, true);
 #pragma unroll
                 for (int q = 0; q < PER; ++q)
-                    if (inside(zp, q)) gstore(zp, q, pre[q]);
+                    if (inside(zp, q)) gstore(zp, q, S[ZO + lds0 + q * JS * LD]);
                 block_back(s, 2 * t);   // every block of step t-1 is final
+#pragma unroll
+                for (int q = 0; q < PER; ++q)
+                    if (jj0 + q * JS < B) S[ZO + lds0 + q * JS * LD] = inside(zc, q) ? pre[q] : (C)0;
             }
             RMARK(0);
             // UG: every wave's band stores of the previous step (and the panel's) are acknowledged
@@ -647,18 +652,16 @@ __global__ __launch_bounds__(ReduceShape<B>::NT) void band_reduce_kernel(C* __re
             // ---- S2: publish the previous step; the block right of Z (requested or transformed in
             // place from here on) was last touched by the right half of the predecessor's step
             // t+2, whose result is that step's upper block
-            if (UG && t > 0) publish(s, 2 * t);
-            wait_for(s, 2 * t + 5, seen1);
-            lds_barrier();
-            failed = sh_fail != 0;
-            RMARK(2);
-            if (failed) break;
-            // ---- S3: A3 requested; block reflector onto the rows below X
-            if (!UG && traffic) {
-                const Blk a3 = block_at(c0, c0 + B);
-#pragma unroll
-                for (int q = 0; q < PER; ++q) pre[q] = gload(a3, q, true);
+            if (UG) {
+                if (t > 0) publish(s, 2 * t);
+                wait_for(s, 2 * t + 5, seen1);
+                lds_barrier();
+                failed = sh_fail != 0;
+                if (failed) break;
             }
+            RMARK(2);
+            // ---- S3: block reflector onto the rows below X
+            const int seen3 = UG ? 0 : poll(s);
             if (UG) {
                 // (waves 0 .. 7: the rows of Z, in LDS, four lanes per line; waves 8 .. 15: rows D .. B-1
                 // of U, in the band, eight lanes per line, two rounds; none in the first step, whose X
@@ -685,41 +688,44 @@ __global__ __launch_bounds__(ReduceShape<B>::NT) void band_reduce_kernel(C* __re
             }
             lds_barrier();
             RMARK(3);
-            if (UG) publish(s, 2 * t + 1);   // U was transformed where it lies; the stores are acknowledged
-            // ---- S4: left panel (QR of Z's first D columns)  ||  U back, A3 in
-            const int seen2 = poll(s);
+            if (UG) {
+                publish(s, 2 * t + 1);   // U was transformed where it lies; the stores are acknowledged
+            } else {
+                // the block right of Z (requested in S4) was last touched by the right half of the
+                // predecessor's step t+2, whose result is that step's upper block
+                wait_for(s, 2 * t + 5, seen3);
+                lds_barrier();
+                failed = sh_fail != 0;
+                if (failed) break;
+            }
+            // ---- S4: left panel (QR of Z's first D columns)  ||  A3 requested, U back, A3 in
+            const int seen2 = UG ? poll(s) : 0;
             if (pw) {
                 panel_wave<C, B, D>(S + ZO, LD, 1, Vs, Ts);
             } else if (!UG && traffic) {
                 const Blk ub = block_at(c0 - B, c0), a3 = block_at(c0, c0 + B);
 #pragma unroll
-                for (int q = 0; q < PER; ++q) {
-                    if (jj0 + q * JS < B) {
-                        const int li = lds0 + q * JS * LD;
-                        const C old = S[li];
-                        S[li] = inside(a3, q) ? pre[q] : (C)0;
-                        pre[q] = old;
-                    }
-                }
+                for (int q = 0; q < PER; ++q) pre[q] = gload(a3, q, true);
 #pragma unroll
                 for (int q = 0; q < PER; ++q)
-                    if (inside(ub, q) && ii >= xoff) gstore(ub, q, pre[q]);
+                    if (inside(ub, q) && ii >= xoff) gstore(ub, q, S[lds0 + q * JS * LD]);
                 block_back(s, 2 * t + 1);   // U is final
+#pragma unroll
+                for (int q = 0; q < PER; ++q)
+                    if (jj0 + q * JS < B) S[lds0 + q * JS * LD] = inside(a3, q) ? pre[q] : (C)0;
             }
             RMARK(4);
             lds_barrier();
-            // the next step's Z (requested below; UG: at the start of that step) has a corner that
-            // the left half of the predecessor's step t+2 wrote
-            wait_for(s, 2 * t + 6, seen2);
-            lds_barrier();
-            failed = sh_fail != 0;
-            if (failed) break;
-            RMARK(5);
-            if (!UG && traffic) {
-                const Blk zn = block_at(c0 + B, c0 + B);
-#pragma unroll
-                for (int q = 0; q < PER; ++q) pre[q] = gload(zn, q, true);
+            if (UG) {
+                // the next step's Z (requested at the start of that step) has a corner that the left
+                // half of the predecessor's step t+2 wrote
+                wait_for(s, 2 * t + 6, seen2);
+                lds_barrier();
+                failed = sh_fail != 0;
+                if (failed) break;
             }
+            RMARK(5);
+            seen_next = UG ? 0 : poll(s);
             // ---- S5: block reflector onto the other columns of Z and onto A3
             if (UG) {
                 // lines 0 .. B-1: columns D .. B-1 of Z, in LDS; lines B .. 2B-1: the columns of the
