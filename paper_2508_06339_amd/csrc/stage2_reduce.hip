@@ -602,7 +602,7 @@ __global__ __launch_bounds__(ReduceShape<B>::NT) void band_reduce_kernel(C* __re
 #ifdef SVB_CHASE_TIMING
             if (lead) { tlast = wall_clock64(); ++nstep_acc; }
 #endif
-            if (!UG && t > 0) {
+            if (t > 0) {
                 // this step's Z (requested in S1) has a corner that the left half of the predecessor's
                 // step t+1 wrote
                 wait_for(s, 2 * t + 4, seen_next);
@@ -613,7 +613,6 @@ __global__ __launch_bounds__(ReduceShape<B>::NT) void band_reduce_kernel(C* __re
             // ---- S1: right panel (LQ of X)  ||  Z of the previous step back, this step's Z in
             const int ncol = (int)min((int64_t)B, n - c0);                            // columns c0 .. inside the matrix
             const int64_t rho = (t == 0) ? c00 - D : c0 - B;                          // first row of X
-            const int seen1 = UG ? poll(s) : 0;
             if (pw) {
                 if (UG) panel_wave<C, B, D, true>(band + (rho - c0 + ku) + c0 * ldab, 1, ldm1, Vs, Ts, ncol);
                 else panel_wave<C, B, D>(S + xoff, 1, LD, Vs, Ts);
@@ -626,6 +625,9 @@ __global__ __launch_bounds__(ReduceShape<B>::NT) void band_reduce_kernel(C* __re
 #pragma unroll
                 for (int q = 0; q < PER; ++q)
                     if (inside(zp, q)) gstore(zp, q, S[lds0 + q * JS * LD]);
+                // every block of step t-1 is final (the in-band stores of its last phase were
+                // acknowledged before that phase's barrier)
+                block_back(s, 2 * t);
 #pragma unroll
                 for (int q = 0; q < PER; ++q)
                     if (jj0 + q * JS < B) S[lds0 + q * JS * LD] = inside(zc, q) ? pre[q] : (C)0;
@@ -649,16 +651,6 @@ __global__ __launch_bounds__(ReduceShape<B>::NT) void band_reduce_kernel(C* __re
             if (UG) stores_done();
             lds_barrier();
             RMARK(1);
-            // ---- S2: publish the previous step; the block right of Z (requested or transformed in
-            // place from here on) was last touched by the right half of the predecessor's step
-            // t+2, whose result is that step's upper block
-            if (UG) {
-                if (t > 0) publish(s, 2 * t);
-                wait_for(s, 2 * t + 5, seen1);
-                lds_barrier();
-                failed = sh_fail != 0;
-                if (failed) break;
-            }
             RMARK(2);
             // ---- S3: block reflector onto the rows below X
             const int seen3 = UG ? 0 : poll(s);
@@ -717,15 +709,15 @@ __global__ __launch_bounds__(ReduceShape<B>::NT) void band_reduce_kernel(C* __re
             RMARK(4);
             lds_barrier();
             if (UG) {
-                // the next step's Z (requested at the start of that step) has a corner that the left
-                // half of the predecessor's step t+2 wrote
-                wait_for(s, 2 * t + 6, seen2);
+                // the block right of Z (transformed where it lies in S5) was last touched by the right
+                // half of the predecessor's step t+2, whose result is that step's upper block
+                wait_for(s, 2 * t + 5, seen2);
                 lds_barrier();
                 failed = sh_fail != 0;
                 if (failed) break;
             }
             RMARK(5);
-            seen_next = UG ? 0 : poll(s);
+            seen_next = poll(s);
             // ---- S5: block reflector onto the other columns of Z and onto A3
             if (UG) {
                 // lines 0 .. B-1: columns D .. B-1 of Z, in LDS; lines B .. 2B-1: the columns of the
