@@ -17,8 +17,8 @@
  *   - GPU work is ordered after what the HIP stream passed as `stream` (a
  *     hipStream_t cast to void*, NULL = the default stream) holds at the call,
  *     and that stream waits for it: stage 1 runs on two internal streams that
- *     are forked from and joined back to `stream` with events (the second one
- *     restricted to a subset of the compute units), the rest on `stream`.
+ *     are forked from and joined back to `stream` with events (the panel tree
+ *     on one, the updates it overlaps on the other), the rest on `stream`.
  *   - Return value: an svb_status.  On SVB_ERR_ARG / SVB_ERR_UNSUPPORTED /
  *     SVB_ERR_WORKSPACE nothing has been read or written.
  *   - Supported in this version: m == n, n a positive multiple of nb,
@@ -124,13 +124,14 @@ int svb_gb2bd_workspace_bytes(int64_t n, int nb, size_t* dev_bytes);
 int svb_bdsvals(int64_t n, const double* d, const double* e, double* sigma);
 
 /*
- * Stage 3 on the device: the same bisection as svb_bdsvals, one singular value
- * per GPU thread, for callers that keep the bidiagonal in device memory
+ * Stage 3 on the device: the Sturm counts of svb_bdsvals, each interval refined
+ * by multisection (several lanes per singular value, one point of the interval
+ * each), for callers that keep the bidiagonal in device memory
  * (svb_svdvals uses it unless the environment variable SVB_STAGE3=host is set).
  *   band_dt   SVB_F64 or SVB_F32: type of d, e and sigma.
  *   d_dev, e_dev [dev] in: n and n-1 entries (layout of svb_gb2bd's outputs).
  *   sigma_dev [dev] out: n values, descending.  Non-finite input gives NaNs.
- *   rel_tol   bisection stops at interval width rel_tol * sigma (0 = 2^-52 for
+ *   rel_tol   refinement stops at interval width rel_tol * sigma (0 = 2^-52 for
  *             SVB_F64 and 2^-29 for SVB_F32).
  *   work_dev  [dev] scratch of svb_bdsvals_dev_workspace_bytes(n) bytes.
  * Asynchronous.
