@@ -22,6 +22,7 @@
 #include "svb_internal.h"
 #include "mfma_frag.h"
 #include "mfma_gemm.h"
+#include <hip/hip_ext.h>
 
 namespace svb {
 
@@ -379,10 +380,14 @@ static void launch_fused(T* Cb, int64_t lda, int64_t qlen, const C* V, const C* 
         by = 2.0 * (rows - top) * (double)qlen * sizeof(T);
     }
     if (!credited) fl = by = 0.0;
-    prof_begin(SVB_PROF_FUSED, s, fl, by);
-    hipLaunchKernelGGL(kern, dim3((unsigned)(per * 8)), dim3(G::NT), G::kSmemBytes, s, Cb, lda, qlen, V, Y, ldp,
-                       chunks, g, stride, strips, total, Wb, Tw);
-    prof_end(s);
+    // profiling: the events are the kernel's own start and stop time stamps
+    hipEvent_t ea = nullptr, eb = nullptr;
+    if (prof_take(SVB_PROF_FUSED, fl, by, &ea, &eb))
+        hipExtLaunchKernelGGL(kern, dim3((unsigned)(per * 8)), dim3(G::NT), (uint32_t)G::kSmemBytes, s, ea, eb, 0u, Cb,
+                              lda, qlen, V, Y, ldp, chunks, g, stride, strips, total, Wb, Tw);
+    else
+        hipLaunchKernelGGL(kern, dim3((unsigned)(per * 8)), dim3(G::NT), G::kSmemBytes, s, Cb, lda, qlen, V, Y, ldp,
+                           chunks, g, stride, strips, total, Wb, Tw);
 }
 
 template <typename T, typename C, int NB, int HT, bool LQ, bool TRI>

@@ -444,7 +444,7 @@ template bool panel_blk_serves<double>(int, int);
 template <typename T, typename C>
 void launch_panel_qr(int nb, C* P, int64_t ldp, C* Y, C* Tws, int chunks, int g,
                      C* Pnext, int64_t ldnext, const T* Asrc, int64_t lda, bool lq, C* band, int64_t ldab,
-                     int64_t row0, int64_t col0, hipStream_t s)
+                     int64_t row0, int64_t col0, hipStream_t s, hipEvent_t done, hipEvent_t start)
 {
     const int impl = env_int("SVB_PANEL_IMPL", 2);
     // blocked register-resident kernel (2, default) or the reflector-at-a-time register kernel (1),
@@ -453,13 +453,21 @@ void launch_panel_qr(int nb, C* P, int64_t ldp, C* Y, C* Tws, int chunks, int g,
     // matrix and writes the band itself (Asrc, band: null for the others).
     const bool blk = panel_blk_serves<C>(nb, g);
     if ((blk || (impl != 0 && panel_reg_rows<C>(nb) >= g * nb)) && (g * nb) % 128 == 0) {
-        if (blk) launch_panel_blk<T, C>(nb, P, ldp, Tws, chunks, g, Pnext, ldnext, Asrc, lda, lq, band, ldab, row0, col0, s);
+        // `done` (an event tied to the completion of the level's last kernel) is served only where
+        // the blocked kernel is that last kernel; otherwise it is recorded behind the level
+        const bool tied = done && blk && Y == nullptr;
+        if (blk) launch_panel_blk<T, C>(nb, P, ldp, Tws, chunks, g, Pnext, ldnext, Asrc, lda, lq, band, ldab, row0, col0, s,
+                                        tied ? done : nullptr, tied ? start : nullptr);
         else PanelRegDispatch<C>::run(nb, P, ldp, Tws, chunks, g, Pnext, ldnext, s);
         const int64_t rows = (int64_t)chunks * nb;
-        if (Y == nullptr) return;   // the caller applies T itself
+        if (Y == nullptr) {   // the caller applies T itself
+            if (done && !tied) (void)hipEventRecord(done, s);
+            return;
+        }
         if (nb == 32) launch_panel_y<C, 32>(P, Y, Tws, ldp, rows, g, s);
         else if (nb == 64) launch_panel_y<C, 64>(P, Y, Tws, ldp, rows, g, s);
         else launch_panel_y<C, 128>(P, Y, Tws, ldp, rows, g, s);
+        if (done) (void)hipEventRecord(done, s);
         return;
     }
     const int domains = (chunks + g - 1) / g;
@@ -476,6 +484,7 @@ void launch_panel_qr(int nb, C* P, int64_t ldp, C* Y, C* Tws, int chunks, int g,
         hipLaunchKernelGGL((panel_qr_kernel<C, 128, NT>), dim3(domains), dim3(NT), smem, s, P, ldp, Y, Tws, chunks, g, Pnext, ldnext);
         break;
     }
+    if (done) (void)hipEventRecord(done, s);
 }
 
 // ---------------------------------------------------------------- R -> band
@@ -528,9 +537,9 @@ void launch_band_clear(C* band, int64_t ldab, int64_t n, hipStream_t s)
 template void launch_panel_gather<double, double>(const double*, int64_t, int64_t, int64_t, bool, int64_t, int, double*, int64_t, hipStream_t);
 template void launch_panel_gather<float, float>(const float*, int64_t, int64_t, int64_t, bool, int64_t, int, float*, int64_t, hipStream_t);
 template void launch_panel_gather<__half, float>(const __half*, int64_t, int64_t, int64_t, bool, int64_t, int, float*, int64_t, hipStream_t);
-template void launch_panel_qr<double, double>(int, double*, int64_t, double*, double*, int, int, double*, int64_t, const double*, int64_t, bool, double*, int64_t, int64_t, int64_t, hipStream_t);
-template void launch_panel_qr<float, float>(int, float*, int64_t, float*, float*, int, int, float*, int64_t, const float*, int64_t, bool, float*, int64_t, int64_t, int64_t, hipStream_t);
-template void launch_panel_qr<__half, float>(int, float*, int64_t, float*, float*, int, int, float*, int64_t, const __half*, int64_t, bool, float*, int64_t, int64_t, int64_t, hipStream_t);
+template void launch_panel_qr<double, double>(int, double*, int64_t, double*, double*, int, int, double*, int64_t, const double*, int64_t, bool, double*, int64_t, int64_t, int64_t, hipStream_t, hipEvent_t, hipEvent_t);
+template void launch_panel_qr<float, float>(int, float*, int64_t, float*, float*, int, int, float*, int64_t, const float*, int64_t, bool, float*, int64_t, int64_t, int64_t, hipStream_t, hipEvent_t, hipEvent_t);
+template void launch_panel_qr<__half, float>(int, float*, int64_t, float*, float*, int, int, float*, int64_t, const __half*, int64_t, bool, float*, int64_t, int64_t, int64_t, hipStream_t, hipEvent_t, hipEvent_t);
 template void launch_scatter_r<double>(const double*, int64_t, int, double*, int64_t, int64_t, int64_t, bool, hipStream_t);
 template void launch_scatter_r<float>(const float*, int64_t, int, float*, int64_t, int64_t, int64_t, bool, hipStream_t);
 template void launch_band_clear<double>(double*, int64_t, int64_t, hipStream_t);

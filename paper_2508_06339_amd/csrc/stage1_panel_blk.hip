@@ -22,6 +22,7 @@
 // gives tau = 0 instead of the paper's 10*eps rule.
 #include "svb_internal.h"
 #include "mfma_frag.h"
+#include <hip/hip_ext.h>
 
 namespace svb {
 
@@ -477,7 +478,7 @@ template int panel_blk_rows<double>();
 
 template <typename T, typename C, int NB, int HT, bool TRI>
 static void launch_blk_ht(C* P, int64_t ldp, C* Tws, int chunks, int g, C* Pnext, int64_t ldnext,
-                          const PanelEnds<T, C>& ends, hipStream_t s)
+                          const PanelEnds<T, C>& ends, hipStream_t s, hipEvent_t done, hipEvent_t start)
 {
     using G = PanelBlkGeom<C, NB, HT>;
     auto kern = panel_qr_blk_kernel<T, C, NB, HT, TRI>;
@@ -488,52 +489,58 @@ static void launch_blk_ht(C* P, int64_t ldp, C* Tws, int chunks, int g, C* Pnext
         attr_set = true;
     }
     const int domains = (chunks + g - 1) / g;
-    hipLaunchKernelGGL(kern, dim3(domains), dim3(G::NT), G::kSmemBytes, s, P, ldp, Tws, chunks, g, Pnext, ldnext, ends);
+    // `done` (and `start`): events tied to this launch's own completion (and start): no separate
+    // marker in the stream between this kernel and the next one
+    if (done)
+        hipExtLaunchKernelGGL(kern, dim3(domains), dim3(G::NT), (uint32_t)G::kSmemBytes, s, start, done, 0u, P, ldp,
+                              Tws, chunks, g, Pnext, ldnext, ends);
+    else
+        hipLaunchKernelGGL(kern, dim3(domains), dim3(G::NT), G::kSmemBytes, s, P, ldp, Tws, chunks, g, Pnext, ldnext, ends);
 }
 
 template <typename T, typename C, int NB>
 static void launch_blk(C* P, int64_t ldp, C* Tws, int chunks, int g, C* Pnext, int64_t ldnext,
-                       const PanelEnds<T, C>& ends, hipStream_t s)
+                       const PanelEnds<T, C>& ends, hipStream_t s, hipEvent_t done, hipEvent_t start)
 {
     constexpr int HT = panel_blk_tiles<C>();
     // a panel that does not come from the matrix is a stack of triangular factors; near the top of
     // the tree such a stack is short, and a kernel sized for it (fewer rows per thread in the
     // reflector steps, fewer tiles in the block products) is faster than the full-height one
     if (ends.Asrc) {
-        launch_blk_ht<T, C, NB, HT, false>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, s);
+        launch_blk_ht<T, C, NB, HT, false>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, s, done, start);
         return;
     }
     const int need = (chunks < g ? chunks : g) * NB / 16;   // tiles of the tallest domain
     if constexpr (HT / 4 * 16 >= NB) {
         if (need <= HT / 4) {
-            launch_blk_ht<T, C, NB, HT / 4, true>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, s);
+            launch_blk_ht<T, C, NB, HT / 4, true>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, s, done, start);
             return;
         }
     }
     if constexpr (HT / 2 * 16 >= NB) {
         if (need <= HT / 2) {
-            launch_blk_ht<T, C, NB, HT / 2, true>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, s);
+            launch_blk_ht<T, C, NB, HT / 2, true>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, s, done, start);
             return;
         }
     }
-    launch_blk_ht<T, C, NB, HT, true>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, s);
+    launch_blk_ht<T, C, NB, HT, true>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, s, done, start);
 }
 
 template <typename T, typename C>
 void launch_panel_blk(int nb, C* P, int64_t ldp, C* Tws, int chunks, int g, C* Pnext, int64_t ldnext,
                       const T* Asrc, int64_t lda, bool lq, C* band, int64_t ldab, int64_t row0, int64_t col0,
-                      hipStream_t s)
+                      hipStream_t s, hipEvent_t done, hipEvent_t start)
 {
     const PanelEnds<T, C> ends{Asrc, lda, lq ? 1 : 0, band, ldab, row0, col0};
     switch (nb) {
-    case 32: launch_blk<T, C, 32>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, s); break;
-    case 64: launch_blk<T, C, 64>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, s); break;
-    default: launch_blk<T, C, 128>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, s); break;
+    case 32: launch_blk<T, C, 32>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, s, done, start); break;
+    case 64: launch_blk<T, C, 64>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, s, done, start); break;
+    default: launch_blk<T, C, 128>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, s, done, start); break;
     }
 }
 
-template void launch_panel_blk<float, float>(int, float*, int64_t, float*, int, int, float*, int64_t, const float*, int64_t, bool, float*, int64_t, int64_t, int64_t, hipStream_t);
-template void launch_panel_blk<__half, float>(int, float*, int64_t, float*, int, int, float*, int64_t, const __half*, int64_t, bool, float*, int64_t, int64_t, int64_t, hipStream_t);
-template void launch_panel_blk<double, double>(int, double*, int64_t, double*, int, int, double*, int64_t, const double*, int64_t, bool, double*, int64_t, int64_t, int64_t, hipStream_t);
+template void launch_panel_blk<float, float>(int, float*, int64_t, float*, int, int, float*, int64_t, const float*, int64_t, bool, float*, int64_t, int64_t, int64_t, hipStream_t, hipEvent_t, hipEvent_t);
+template void launch_panel_blk<__half, float>(int, float*, int64_t, float*, int, int, float*, int64_t, const __half*, int64_t, bool, float*, int64_t, int64_t, int64_t, hipStream_t, hipEvent_t, hipEvent_t);
+template void launch_panel_blk<double, double>(int, double*, int64_t, double*, int, int, double*, int64_t, const double*, int64_t, bool, double*, int64_t, int64_t, int64_t, hipStream_t, hipEvent_t, hipEvent_t);
 
 }  // namespace svb

@@ -176,6 +176,15 @@ struct Profiler {
         if (!on) return;
         (void)hipEventRecord(recs.back().b, s);
     }
+    bool take(int kind, double fl, double by, hipEvent_t* a, hipEvent_t* b)
+    {
+        if (!on) return false;
+        Rec r{kind, get(), get(), fl, by};
+        *a = r.a;
+        *b = r.b;
+        recs.push_back(r);
+        return true;
+    }
     void collect()
     {
         for (auto& r : recs) {
@@ -234,13 +243,18 @@ struct Lookahead {
         if (hipStreamCreateWithFlags(&m, hipStreamNonBlocking) != hipSuccess) return false;
         if (!masked_stream(&h, env_int("SVB_HELPER_MASK_BITS", 224))) return false;
         if (!masked_stream(&u, env_int("SVB_UPDATE_MASK_BITS", 256))) return false;
+        // events between the two internal streams order kernels of one device against each other:
+        // no system-scope fence (a cache write-back for the host's and other devices' benefit) is
+        // needed when they are recorded, and it would sit on the critical path of every half-sweep
+        const unsigned kInner = env_int("SVB_EVENT_FENCE", 0) ? hipEventDisableTiming
+                                                              : (hipEventDisableTiming | hipEventDisableSystemFence);
         for (int i = 0; i < 2; ++i) {
-            if (hipEventCreateWithFlags(&crit[i], hipEventDisableTiming) != hipSuccess ||
-                hipEventCreateWithFlags(&rest[i], hipEventDisableTiming) != hipSuccess ||
-                hipEventCreateWithFlags(&udone[i], hipEventDisableTiming) != hipSuccess)
+            if (hipEventCreateWithFlags(&crit[i], kInner) != hipSuccess ||
+                hipEventCreateWithFlags(&rest[i], kInner) != hipSuccess ||
+                hipEventCreateWithFlags(&udone[i], kInner) != hipSuccess)
                 return false;
             for (int L = 0; L < kMaxLevels; ++L)
-                if (hipEventCreateWithFlags(&lvl[i][L], hipEventDisableTiming) != hipSuccess) return false;
+                if (hipEventCreateWithFlags(&lvl[i][L], kInner) != hipSuccess) return false;
         }
         if (hipEventCreateWithFlags(&fork, hipEventDisableTiming) != hipSuccess ||
             hipEventCreateWithFlags(&join, hipEventDisableTiming) != hipSuccess ||
@@ -299,6 +313,9 @@ int ge2gb_pipeline(int64_t n, T* A, int64_t lda, int nb, C* band, int64_t ldab, 
     C* Tb = reinterpret_cast<C*>(work + cv.off_T[0]);
     const bool direct = panel_blk_serves<C>(nb, g);
     const int layout = env_int("SVB_PIPELINE_LAYOUT", 1);
+    // a level's event is tied to the completion of its kernel instead of being recorded behind it
+    // (one marker less in the main stream between two panel levels)
+    const bool ext_events = env_int("SVB_EXT_EVENTS", 1) != 0;
     int hs = 0;
     bool side_pending = false;
     for (int64_t k = 0; k < N; ++k) {
@@ -321,20 +338,32 @@ int ge2gb_pipeline(int64_t n, T* A, int64_t lda, int nb, C* band, int64_t ldab, 
             const bool useT = direct && nb <= 64 && tsum <= (int64_t)cv.t_elems && env_int("SVB_UPDATE_T", 1) != 0;
             const bool split = layout == 0 && qlen > 0;
             T* Cb = lq ? A + (k + 1) * nb + (k + 1) * nb * lda : A + k * nb + (k + 1) * nb * lda;
-            auto panel = [&](int L, hipStream_t st) {
+            // Factors level L on stream st and returns the event that fires when the level is done
+            // (null if none was asked for).  Where the level is a single kernel the event is tied to
+            // that kernel's completion instead of being recorded behind it, and with profiling on the
+            // profiler's own stop event serves: no marker then separates two panel levels.
+            auto panel = [&](int L, hipStream_t st, hipEvent_t done) -> hipEvent_t {
                 const int64_t next_off = lv[L].poff + lv[L].ldp * nb;
                 const int64_t ldnext = (int64_t)lv[L].domains * nb;
                 const bool last = L == nl - 1;
-                g_prof.begin(SVB_PROF_PANEL, st, L == 0 ? 2.0 * (double)len * nb * nb : 0.0, 0.0);
+                const bool single = ext_events && direct && useT;
+                const double fl = L == 0 ? 2.0 * (double)len * nb * nb : 0.0;
+                hipEvent_t ea = nullptr, eb = nullptr;
+                const bool timed = single && prof_take(SVB_PROF_PANEL, fl, 0.0, &ea, &eb);
+                if (!timed) g_prof.begin(SVB_PROF_PANEL, st, fl, 0.0);
                 if (L == 0 && !direct)
                     launch_panel_gather<T, C>(A, lda, row0, col0, lq, len, nb, Vb + lv[0].poff, lv[0].ldp, st);
                 launch_panel_qr<T, C>(nb, Vb + lv[L].poff, lv[L].ldp, useT ? (C*)nullptr : Yb + lv[L].poff,
                                       useT ? Tb + toff[L] : Tb, lv[L].chunks, g,
                                       Vb + next_off, ldnext, (direct && L == 0) ? A + row0 + col0 * lda : nullptr, lda, lq,
-                                      (direct && last) ? band : nullptr, ldab, row0, col0, st);
+                                      (direct && last) ? band : nullptr, ldab, row0, col0, st,
+                                      timed ? eb : (single ? done : nullptr), ea);
                 if (last && !direct)
                     launch_scatter_r<C>(Vb + next_off, ldnext, nb, band, ldab, row0, col0, lq, st);
-                g_prof.end(st);
+                if (!timed) g_prof.end(st);
+                if (timed) return eb;
+                if (done && !single) (void)hipEventRecord(done, st);
+                return done;
             };
             auto update = [&](int L, hipStream_t st) {
                 launch_update_fused<T, C>(nb, lq, Cb, lda, qlen, Vb + lv[L].poff, Yb + lv[L].poff, lv[L].ldp,
@@ -347,23 +376,20 @@ int ge2gb_pipeline(int64_t n, T* A, int64_t lda, int nb, C* band, int64_t ldab, 
                 side_pending = false;
             }
             if (qlen <= 0) {
-                for (int L = 0; L < nl; ++L) panel(L, ms);
+                for (int L = 0; L < nl; ++L) panel(L, ms, nullptr);
             } else if (split) {
                 // every panel on the main stream, every update on the side stream
                 for (int L = 0; L < nl; ++L) {
-                    panel(L, ms);
-                    (void)hipEventRecord(g_la.lvl[set][L], ms);
-                    (void)hipStreamWaitEvent(ss, g_la.lvl[set][L], 0);
+                    (void)hipStreamWaitEvent(ss, panel(L, ms, g_la.lvl[set][L]), 0);
                     update(L, ss);
                 }
                 (void)hipEventRecord(g_la.udone[set], ss);
                 side_pending = true;
             } else {
                 for (int L = 0; L < nl; ++L) {
-                    panel(L, ms);
+                    const hipEvent_t ev = panel(L, ms, L < nl - 1 ? g_la.lvl[set][L] : nullptr);
                     if (L < nl - 1) {
-                        (void)hipEventRecord(g_la.lvl[set][L], ms);
-                        (void)hipStreamWaitEvent(ss, g_la.lvl[set][L], 0);
+                        (void)hipStreamWaitEvent(ss, ev, 0);
                         update(L, ss);
                     }
                 }
@@ -529,6 +555,10 @@ int ge2gb_dispatch(svb_dtype dt, int64_t n, void* A, int64_t lda, int nb, void* 
 
 void prof_begin(int kind, hipStream_t s, double flops, double bytes) { g_prof.begin(kind, s, flops, bytes); }
 void prof_end(hipStream_t s) { g_prof.end(s); }
+bool prof_take(int kind, double flops, double bytes, hipEvent_t* start, hipEvent_t* stop)
+{
+    return g_prof.take(kind, flops, bytes, start, stop);
+}
 
 }  // namespace svb
 

@@ -80,7 +80,7 @@ void launch_panel_gather(const T* A, int64_t lda, int64_t row0, int64_t col0, bo
 template <typename T, typename C>
 void launch_panel_qr(int nb, C* P, int64_t ldp, C* Y, C* Tws, int chunks, int g,
                      C* Pnext, int64_t ldnext, const T* Asrc, int64_t lda, bool lq, C* band, int64_t ldab,
-                     int64_t row0, int64_t col0, hipStream_t s);
+                     int64_t row0, int64_t col0, hipStream_t s, hipEvent_t done = nullptr, hipEvent_t start = nullptr);
 
 // blocked register-resident domain QR (MFMA block reflectors inside the domain); domains of at
 // most panel_blk_rows<C>() rows
@@ -90,7 +90,7 @@ void launch_panel_qr(int nb, C* P, int64_t ldp, C* Y, C* Tws, int chunks, int g,
 template <typename T, typename C>
 void launch_panel_blk(int nb, C* P, int64_t ldp, C* Tws, int chunks, int g, C* Pnext, int64_t ldnext,
                       const T* Asrc, int64_t lda, bool lq, C* band, int64_t ldab, int64_t row0, int64_t col0,
-                      hipStream_t s);
+                      hipStream_t s, hipEvent_t done = nullptr, hipEvent_t start = nullptr);
 template <typename C> int panel_blk_rows();
 // does the blocked kernel serve this (type, nb, chunks per domain)?  Then the first level needs no
 // gathered copy of its panel and the last level no separate scatter of R.
@@ -127,6 +127,10 @@ template <typename C> int fused_update_rows();
 // per-kernel timing hooks (no-ops unless profiling is enabled)
 void prof_begin(int kind, hipStream_t s, double flops, double bytes);
 void prof_end(hipStream_t s);
+// For a single kernel: if profiling is on, hands out a pair of events for a launch that ties them
+// to the kernel itself (hipExtLaunchKernelGGL's start and stop events: the kernel's own time
+// stamps, no marker in the stream before or after it) and returns true.
+bool prof_take(int kind, double flops, double bytes, hipEvent_t* start, hipEvent_t* stop);
 
 // ---- stage 2 -----------------------------------------------------------------
 template <typename C>
