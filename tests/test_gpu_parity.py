@@ -90,6 +90,42 @@ def test_stage1_alternative_kernels(monkeypatch, panel, update, name, n, nb):
     _check(_gpu_sigma(a, nb), oracle.svdvals(a), n, info["dtype"], fro)
 
 
+_VARIANT_CASES = {}
+
+
+def _variant_case(name, n, nb):
+    # workload and oracle result, computed once per case
+    if (name, n, nb) not in _VARIANT_CASES:
+        a, info = workloads.make(name, n=n, nb=nb)
+        _VARIANT_CASES[(name, n, nb)] = (a, info, oracle.svdvals(a))
+    return _VARIANT_CASES[(name, n, nb)]
+
+
+@pytest.mark.parametrize("env", [{"SVB_PIPELINE": "0"}, {"SVB_PIPELINE": "0", "SVB_LOOKAHEAD_MIN_TILES": "1"},
+                                 {"SVB_PIPELINE_LAYOUT": "0"}, {"SVB_UPDATE_T": "0"}, {"SVB_EXT_EVENTS": "0"},
+                                 {"SVB_EVENT_FENCE": "1"}, {"PROFILE": "1"}])
+@pytest.mark.parametrize("name,n,nb", [("c4", 1152, 64), ("c5b", 768, 128), ("c3b", 1024, 32)])
+def test_stage1_driver_variants(monkeypatch, env, name, n, nb):
+    # the stage-1 drivers kept beside the default level pipeline (sequential driver with and without
+    # the split update, every update on the side stream, Y = V T instead of T in the update, level
+    # events recorded behind the kernels, system-scope events), and the default with the library's
+    # per-kernel events on: same singular values
+    for k, v in env.items():
+        if k != "PROFILE":
+            monkeypatch.setenv(k, v)
+    a, info, ref = _variant_case(name, n, nb)
+    fro = 2e-2 if info["dtype"] == "f16" else None
+    if "PROFILE" in env:
+        svb.svb_profile_enable(True)
+    try:
+        s = _gpu_sigma(a, nb)
+        if "PROFILE" in env:
+            assert svb.svb_profile_get(svb.SVB_PROF_FUSED)["launches"] > 0
+    finally:
+        svb.svb_profile_enable(False)
+    _check(s, ref, n, info["dtype"], fro)
+
+
 def test_degenerate_inputs():
     n, nb = 128, 32
     z = np.zeros((n, n), order="F")
