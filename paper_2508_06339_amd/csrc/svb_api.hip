@@ -418,7 +418,6 @@ template <typename T, typename C>
 int ge2gb_impl(int64_t n, T* A, int64_t lda, int nb, C* band, int64_t ldab, unsigned char* work,
                const Carve& cv, hipStream_t caller)
 {
-    int* err = reinterpret_cast<int*>(work + cv.off_err);
     const int g = domain_chunks(sizeof(C) == 8 ? SVB_F64 : SVB_F32, nb);
     // update: 2 = one pass over the trailing matrix per tree level (default, when the domain fits
     // the kernel's registers), 1 = two MFMA kernels with look-ahead, 0 = plain FMA kernels
