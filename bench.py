@@ -85,7 +85,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", default="c4", help="workload name from workloads.CONFIGS")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-n", type=int, default=3072)
+    ap.add_argument("--cpu-sample-n", type=int, default=4096)
     ap.add_argument("--lda-pad", type=int, default=0,
                     help="leading dimension of the matrix handed to the library = n + this many elements")
     ap.add_argument("--gaussian-input", action="store_true",
