@@ -218,7 +218,11 @@ __device__ __forceinline__ void panel_wave(C* P, int64_t sk, int64_t se, C* Vs, 
         if (ss == (C)0) {
             beta = alpha; tau = 0; inv = 0;
         } else {
-            const C nrm = sqrt(alpha * alpha + ss);
+            // (alpha and ss are the same in every lane: a uniform branch.  The refined hardware
+            // square root wants a normal argument; sums near the underflow threshold take the
+            // library routine.)
+            const C x2 = alpha * alpha + ss;
+            const C nrm = x2 < (sizeof(C) == 8 ? (C)1e-290 : (C)1e-30f) ? sqrt(x2) : newton_sqrt(x2);
             beta = alpha >= (C)0 ? -nrm : nrm;
             tau = (beta - alpha) * rrcp(beta);
             inv = rrcp(alpha - beta);
