@@ -80,3 +80,14 @@ def test_bdsvals_random_vs_library_and_edge_cases():
     dd = np.array([3.0, -1.0, 0.0, 2.0])
     assert svb.svb_bdsvals(4, dd, np.zeros(3), z) == 0
     np.testing.assert_allclose(z, [3.0, 2.0, 1.0, 0.0], atol=1e-15)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    # one GPU only: the bench says so and exits before touching a device
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2
+    assert "ONE GPU" in r.stderr
