@@ -9,7 +9,7 @@
 //   t_1 = -x^2,  D_j = d_j^2 + t_j,  t_{j+1} = -x^2 + e_j^2 * t_j / D_j,
 // the number of negative D_j (the differential stationary qd form of the Sturm
 // sequence: one division per row, n rows).  Squares are taken after scaling by
-// the largest entry, always in fp64.  A first kernel counts at 1024 shared points of
+// the largest entry, always in fp64.  A first kernel counts at 4096 shared points of
 // [0, bound]; every singular value then starts from the cell it falls in and is refined by
 // multisection (several points per round, one lane each).
 #include "svb_internal.h"
@@ -66,7 +66,7 @@ __global__ __launch_bounds__(kPrepThreads) void bd_prep_kernel(const C* __restri
     }
 }
 
-constexpr int kGrid = 1024;   // points of the shared first partition of [0, bound]
+constexpr int kGrid = 4096;   // points of the shared first partition of [0, bound]
 
 __device__ __forceinline__ double lane_value(double v, int lane)
 {
@@ -131,7 +131,7 @@ __global__ __launch_bounds__(64) void bd_grid_kernel(const double* __restrict__ 
 template <typename C, int P>
 __global__ __launch_bounds__(64) void bd_multisect_kernel(const double* __restrict__ ws, int64_t n,
                                                            C* __restrict__ sigma, double rel_tol,
-                                                           const int* __restrict__ gcnt)
+                                                           double floor_frac, const int* __restrict__ gcnt)
 {
     constexpr int VPW = kWave / P;   // values per wave
     const int lane = threadIdx.x, grp = lane / P, q = lane % P;
@@ -142,6 +142,10 @@ __global__ __launch_bounds__(64) void bd_multisect_kernel(const double* __restri
     const double* __restrict__ e2 = d2 + n;
     if (scale != scale) {  // non-finite input: poison the output, the caller maps it to a status
         if (kraw < n && q == 0) sigma[n - 1 - k] = (C)NAN;
+        return;
+    }
+    if (hi0 <= 2e-300) {   // all entries are zero (the bound is its own guard term): so are the values
+        if (kraw < n && q == 0) sigma[n - 1 - k] = (C)0;
         return;
     }
     // first interval from the shared partition: gcnt[a] < k+1 <= gcnt[b] with b = a+1
@@ -155,7 +159,8 @@ __global__ __launch_bounds__(64) void bd_multisect_kernel(const double* __restri
     const double frac = (double)(q + 1) / (P + 1);
     for (int it = 0; it < 200; ++it) {
         const double w = hi - lo, mid = 0.5 * (lo + hi);
-        const bool open = (w > rel_tol * hi + 1e-38 * hi0) && (mid > lo && mid < hi);
+        // width relative to the value, or to floor_frac times the bound on the largest value if that is more
+        const bool open = (w > rel_tol * fmax(hi, floor_frac * hi0) + 1e-38 * hi0) && (mid > lo && mid < hi);
         if (!__any(open)) break;            // wave-uniform exit: the row hand-over needs every lane
         // this lane's point; rounding may put it on an end of the interval, where the count is known
         const double x = fmin(fmax(fma(w, frac, lo), lo), hi);
@@ -182,7 +187,8 @@ __global__ __launch_bounds__(64) void bd_multisect_kernel(const double* __restri
 size_t bdsvals_dev_workspace_bytes(int64_t n) { return (size_t)(8 + 2 * n) * sizeof(double) + (size_t)(kGrid + 8) * sizeof(int); }
 
 template <typename C>
-int run_bdsvals_dev(int64_t n, const C* d, const C* e, C* sigma, void* work, double rel_tol, hipStream_t s)
+int run_bdsvals_dev(int64_t n, const C* d, const C* e, C* sigma, void* work, double rel_tol, double floor_frac,
+                    hipStream_t s)
 {
     double* ws = static_cast<double*>(work);
     hipLaunchKernelGGL((bd_prep_kernel<C>), dim3(1), dim3(kPrepThreads), 0, s, d, e, n, ws);
@@ -193,7 +199,8 @@ int run_bdsvals_dev(int64_t n, const C* d, const C* e, C* sigma, void* work, dou
     if (p <= 0) p = n <= 8192 ? 16 : (n <= 16384 ? 8 : (n <= 32768 ? 4 : (n <= 65536 ? 2 : 1)));
     auto launch = [&](auto kern, int pp) {
         const int vpw = kWave / pp;
-        hipLaunchKernelGGL(kern, dim3((unsigned)((n + vpw - 1) / vpw)), dim3(64), 0, s, ws, n, sigma, rel_tol, gcnt);
+        hipLaunchKernelGGL(kern, dim3((unsigned)((n + vpw - 1) / vpw)), dim3(64), 0, s, ws, n, sigma, rel_tol, floor_frac,
+                           gcnt);
     };
     if (p >= 16) launch(bd_multisect_kernel<C, 16>, 16);
     else if (p >= 8) launch(bd_multisect_kernel<C, 8>, 8);
@@ -203,7 +210,7 @@ int run_bdsvals_dev(int64_t n, const C* d, const C* e, C* sigma, void* work, dou
     return hipGetLastError() == hipSuccess ? SVB_OK : SVB_ERR_DEVICE;
 }
 
-template int run_bdsvals_dev<double>(int64_t, const double*, const double*, double*, void*, double, hipStream_t);
-template int run_bdsvals_dev<float>(int64_t, const float*, const float*, float*, void*, double, hipStream_t);
+template int run_bdsvals_dev<double>(int64_t, const double*, const double*, double*, void*, double, double, hipStream_t);
+template int run_bdsvals_dev<float>(int64_t, const float*, const float*, float*, void*, double, double, hipStream_t);
 
 }  // namespace svb

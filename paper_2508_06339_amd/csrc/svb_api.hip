@@ -635,8 +635,8 @@ int svb_bdsvals_dev(svb_dtype band_dt, int64_t n, const void* d_dev, const void*
     if (rel_tol == 0.0) rel_tol = band_dt == SVB_F64 ? 0x1p-52 : 0x1p-29;
     hipStream_t s = (hipStream_t)stream;
     if (band_dt == SVB_F64)
-        return run_bdsvals_dev<double>(n, (const double*)d_dev, (const double*)e_dev, (double*)sigma_dev, work_dev, rel_tol, s);
-    return run_bdsvals_dev<float>(n, (const float*)d_dev, (const float*)e_dev, (float*)sigma_dev, work_dev, rel_tol, s);
+        return run_bdsvals_dev<double>(n, (const double*)d_dev, (const double*)e_dev, (double*)sigma_dev, work_dev, rel_tol, 0.0, s);
+    return run_bdsvals_dev<float>(n, (const float*)d_dev, (const float*)e_dev, (float*)sigma_dev, work_dev, rel_tol, 0.0, s);
 }
 
 int svb_bdsvals(int64_t n, const double* d, const double* e, double* sigma)
@@ -681,11 +681,18 @@ int svb_svdvals(svb_dtype dt, int64_t m, int64_t n, void* A_dev, int64_t lda, vo
     if (rc == SVB_OK && !host3) {
         // stage 3 on the device, then one copy of n values
         void* sig = w + cv.off_sig;
+        // The two reductions leave every singular value with an absolute error of the order of
+        // eps * sigma_max, so the bidiagonal's small values are refined to tol times an eighth of
+        // the bound on sigma_max (2^-3 eps sigma_max in f64, 2^-9 in f32), not to tol times
+        // themselves, which costs them two to three times as many rounds.
         const double tol = dt == SVB_F64 ? 0x1p-52 : 0x1p-29;
+        const double floor_frac = env_int("SVB_STAGE3_RELATIVE", 0) ? 0.0 : 0.125;
         if (dt == SVB_F64)
-            rc = run_bdsvals_dev<double>(n, (const double*)dd, (const double*)de, (double*)sig, w + cv.off_s3, tol, s);
+            rc = run_bdsvals_dev<double>(n, (const double*)dd, (const double*)de, (double*)sig, w + cv.off_s3, tol,
+                                         floor_frac, s);
         else
-            rc = run_bdsvals_dev<float>(n, (const float*)dd, (const float*)de, (float*)sig, w + cv.off_s3, tol, s);
+            rc = run_bdsvals_dev<float>(n, (const float*)dd, (const float*)de, (float*)sig, w + cv.off_s3, tol,
+                                        floor_frac, s);
         if (hipEventCreate(&ev3) == hipSuccess) (void)hipEventRecord(ev3, s);
         if (rc == SVB_OK &&
             (hipMemcpyAsync(S_out_host, sig, (size_t)n * cs, hipMemcpyDeviceToHost, s) != hipSuccess ||

@@ -156,7 +156,9 @@ int host_bdsvals(int64_t n, const double* d, const double* e, double* sigma);
 
 // ---- stage 3 (device) ---------------------------------------------------------
 template <typename C>
-int run_bdsvals_dev(int64_t n, const C* d, const C* e, C* sigma, void* work, double rel_tol, hipStream_t s);
+// interval width on exit: rel_tol * max(sigma, floor_frac * bound on sigma_max)
+int run_bdsvals_dev(int64_t n, const C* d, const C* e, C* sigma, void* work, double rel_tol, double floor_frac,
+                    hipStream_t s);
 size_t bdsvals_dev_workspace_bytes(int64_t n);
 
 int env_int(const char* name, int dflt);
