@@ -455,19 +455,20 @@ static int run_chase_narrow_nw(int64_t n, C* band, int64_t ldab, int64_t ku, int
 template <typename C>
 int run_chase_narrow(int64_t n, C* band, int64_t ldab, int64_t ku, int* ctrl, hipStream_t s)
 {
-    // sweeps per bundle (four per wave)
-    const int nw = env_int("SVB_NARROW_NW", sizeof(C) == 8 ? 16 : 48);
+    // Sweeps per bundle (four per wave) and super-steps per group.  A bundle follows its predecessor
+    // by the chunks the window holds plus two, so the chain per sweep is shortest with as many sweeps
+    // as the window takes and short groups; a group's fixed cost (flag, flush) sets the lower end.
+    // Measured best: 48 sweeps in groups of 4 (f32, 1024-column window), 24 in groups of 4 (f64, 512).
+    const int nw = env_int("SVB_NARROW_NW", sizeof(C) == 8 ? 24 : 48);
+    const int gs = env_int("SVB_NARROW_GS", 4);
     if constexpr (sizeof(C) == 8) {
-        if (nw == 8) return run_chase_narrow_nw<C, 8, 512>(n, band, ldab, ku, ctrl, s);
-        return run_chase_narrow_nw<C, 16, 512>(n, band, ldab, ku, ctrl, s);
+        if (nw == 16) return run_chase_narrow_nw<C, 16, 512>(n, band, ldab, ku, ctrl, s);
+        return run_chase_narrow_nw<C, 24, 512, 4>(n, band, ldab, ku, ctrl, s);
     } else {
-        if (nw == 8) return run_chase_narrow_nw<C, 8, 512>(n, band, ldab, ku, ctrl, s);
-        const int gs = env_int("SVB_NARROW_GS", 8);
-        if (nw == 16 && gs == 16) return run_chase_narrow_nw<C, 16, 1024, 16>(n, band, ldab, ku, ctrl, s);
-        if (nw == 32 && gs == 16) return run_chase_narrow_nw<C, 32, 1024, 16>(n, band, ldab, ku, ctrl, s);
         if (nw == 16) return run_chase_narrow_nw<C, 16, 512>(n, band, ldab, ku, ctrl, s);
         if (nw == 32) return run_chase_narrow_nw<C, 32, 1024>(n, band, ldab, ku, ctrl, s);
-        return run_chase_narrow_nw<C, 48, 1024>(n, band, ldab, ku, ctrl, s);
+        if (gs == 8) return run_chase_narrow_nw<C, 48, 1024>(n, band, ldab, ku, ctrl, s);
+        return run_chase_narrow_nw<C, 48, 1024, 4>(n, band, ldab, ku, ctrl, s);
     }
 }
 
