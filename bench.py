@@ -7,7 +7,7 @@ already resident in HBM.  W warm-up steps, K timed steps without per-kernel
 instrumentation (-> value), then the same K steps again with the library's
 per-kernel HIP events (-> roofline).  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c4] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c5a] [--also c4] [--no-cpu-baseline]
 """
 from __future__ import annotations
 
@@ -23,7 +23,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-PEAK_TFLOPS = {"f64": 78.6, "f32": 157.3, "f16": 157.3}   # MFMA peak of the arithmetic type used
+PEAK_TFLOPS = {"f64": 78.6, "f32": 157.3, "f16": 157.3, "bf16": 157.3}   # MFMA peak of the arithmetic type used
 PEAK_HBM_GBS = 8000.0
 
 
@@ -78,32 +78,10 @@ def cpu_baseline(name, sample_n):
                 sample=f"same recipe at n={sample_n} ({dt:.1f} s, unblocked Householder bidiagonalisation + bisection, fp64)"), s
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--config", default="c4", help="workload name from workloads.CONFIGS")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-n", type=int, default=4096)
-    ap.add_argument("--lda-pad", type=int, default=0,
-                    help="leading dimension of the matrix handed to the library = n + this many elements")
-    ap.add_argument("--gaussian-input", action="store_true",
-                    help="profiling aid: replace the workload's values by iid Gaussians of the same shape "
-                         "(no QR-based synthesis on the device); the result line is marked accordingly")
-    args = ap.parse_args()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
-              "run with --gpus 1", file=sys.stderr)
-        sys.exit(2)
-
-    import torch
-    import workloads
-    import paper_2508_06339_amd as svb
-
-    svb.load_library()  # raises when the HIP library is missing: there is no fallback
-    torch.cuda.set_device(0)
-    a0, info = device_matrix(args.config, torch, args.gaussian_input)
+def run_workload(args, svb, torch, workloads, config, steps, warmup):
+    """W warm-up steps, K timed steps, then K steps with the library's per-kernel events.
+    Returns the measurements of one workload as a dict."""
+    a0, info = device_matrix(config, torch, args.gaussian_input)
     n, nb, dtype = info["n"], info["nb"], info["dtype"]
     dt_code = svb.dtype_code(a0.dtype)
     rc, wbytes, _ = svb.svb_workspace_bytes(dt_code, n, n, nb)
@@ -123,29 +101,31 @@ def main():
         torch.cuda.synchronize()
         t1 = time.perf_counter()
         assert rc == 0, svb.svb_status_string(rc)
-        return t1 - t0, svb.svb_last_timings()
+        tp, tu, t2, t3 = svb.svb_last_timings()
+        return t1 - t0, (max(tp, 0.0) + tu, t2, t3, tp)
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         one_step()
     # timed region: exactly K steps, no per-kernel instrumentation
     times, stages = [], []
-    for _ in range(args.steps):
+    for _ in range(steps):
         t, st = one_step()
         times.append(t)
         stages.append(st)
     # the same K steps once more with the library's per-kernel HIP events (the kernels' own start and
     # stop time stamps on the streams they run on): the roofline figures come from this pass.  It is
     # kept out of the timed region because event handling lengthens the dependency chain of stage 1
-    # (by about 4 % of a step on the default workload); its own time per step is reported beside it.
+    # (a few per cent of a step on the small workloads); its own time per step is reported beside it.
     svb.svb_profile_enable(True)
-    ptimes = [one_step()[0] for _ in range(args.steps)]
-    prof = {k: svb.svb_profile_get(i) for i, k in enumerate(["panel", "k1", "k2", "chase", "fused"])}
+    pruns = [one_step() for _ in range(steps)]
+    prof = {k: svb.svb_profile_get(i) for i, k in enumerate(svb.SVB_PROF_NAMES)}
     svb.svb_profile_enable(False)
+    exposed_panel = float(np.mean([r[1][3] for r in pruns]))
 
     total = float(np.sum(times))
-    ms_per_step = total / args.steps * 1e3
+    ms_per_step = total / steps * 1e3
     flops = 8.0 / 3.0 * n ** 3
-    value = flops / (total / args.steps) / 1e12
+    value = flops / (total / steps) / 1e12
     st = np.mean(np.array(stages), axis=0)
 
     # sanity of the result (not timed): prescribed spectrum or Frobenius invariant
@@ -154,68 +134,142 @@ def main():
     if info.get("sigma") is not None:
         check["max_abs_err_vs_prescribed"] = float(np.abs(s - info["sigma"]).max())
         check["tolerance"] = float(10 * n * workloads.EPS[dtype] * info["sigma"][0])
-    fro2 = float((a0.double() ** 2).sum().item())
+    fro2 = 0.0
+    for j0 in range(0, n, 4096):
+        fro2 += float((a0[j0:j0 + 4096].double() ** 2).sum().item())
     check["rel_frobenius_defect"] = abs(float(np.sum(s * s)) - fro2) / fro2
 
-    # roofline of the dominant kernel (the one with the largest summed duration)
-    dom = max(("k1", "k2", "fused"), key=lambda k: prof[k]["seconds"])
-    pk = prof[dom]
-    ach = pk["flops"] / pk["seconds"] / 1e12 if pk["seconds"] > 0 else 0.0
     peak = PEAK_TFLOPS[dtype]
-    roofline = dict(kernel=dom, bound="mfma", achieved=ach, peak=peak, unit="TFLOP/s", frac=ach / peak,
-                    traffic=None, launches=pk["launches"],
-                    avg_launch_ms=pk["seconds"] / max(pk["launches"], 1) * 1e3)
+    cs = 8 if dtype == "f64" else 4
+    kernels = {}
+    for k, v in prof.items():
+        kernels[k] = dict(ms_per_step=v["seconds"] / steps * 1e3, launches_per_step=v["launches"] / steps,
+                          avg_launch_us=v["seconds"] / max(v["launches"], 1) * 1e6)
     # HBM bytes per launch from the committed rocprofv3 --pmc summary of this workload, if there is one
-    # (first-tree-level launches of the dominant kernel: the ones whose flops and bytes are credited)
-    tfile = os.path.join(ROOT, "profiles", f"hbm_traffic_{args.config}_{n}_{dtype}_nb{nb}.json")
-    roofline_stage2_traffic = None
-    if os.path.exists(tfile):
-        tr = json.load(open(tfile))
-        kname = {"k1": "k1_mfma", "k2": "k2_mfma", "fused": "update_fused_kernel"}[dom]
+    tfile = os.path.join(ROOT, "profiles", f"hbm_traffic_{config}_{n}_{dtype}_nb{nb}.json")
+    traffic = json.load(open(tfile)) if os.path.exists(tfile) else None
 
-        def first_level(k):
-            # update_fused_kernel<T, C, NB, HT, LQ, TRI, MODE>: TRI marks the tree levels above the first
-            if dom != "fused":
-                return True
-            targs = [a.strip() for a in k[k.index("<") + 1:k.rindex(">")].split(",")]
-            return len(targs) < 6 or targs[5] != "true"
+    def counter_bytes(prefix, want_tri=None):
+        """(bytes, launches) per svb_svdvals call of the kernels whose name starts with prefix."""
+        if traffic is None:
+            return None
+        tot, cnt = 0.0, 0
+        for name, v in traffic.items():
+            if not name.startswith(prefix):
+                continue
+            if want_tri is not None:
+                # update_fused_kernel<T, C, NB, HT, LQ, TRI, USET>: TRI marks the tree levels above the first
+                targs = [x.strip() for x in name[name.index("<") + 1:name.rindex(">")].split(",")]
+                if (targs[5] == "true") != want_tri:
+                    continue
+            tot += (v["read_GB"] + v["write_GB"]) * 1e9
+            cnt += v["launches"]
+        return (tot, cnt) if cnt else None
 
-        lvl0 = {k: v for k, v in tr.items() if k.startswith(kname) and first_level(k)}
-        rd = sum(v["read_GB"] for v in lvl0.values())
-        wr = sum(v["write_GB"] for v in lvl0.values())
-        if lvl0:
-            halfsweeps = 2 * (n // nb - 1)                    # half-sweeps with a trailing matrix, one call
-            roofline["traffic"] = (rd + wr) * 1e9 / halfsweeps
-            roofline["traffic_unit"] = ("HBM bytes per half-sweep, first tree level, all its launches "
-                                        "(FETCH_SIZE + WRITE_SIZE, calibrated)")
-            roofline["algorithmic_bytes_per_halfsweep"] = pk["bytes"] / (halfsweeps * args.steps)
-        chk = [v for k, v in tr.items() if k.startswith(("band_reduce_kernel", "chase_narrow_kernel", "chase_persistent"))]
-        if chk:
-            roofline_stage2_traffic = sum(v["read_GB"] + v["write_GB"] for v in chk) * 1e9
-    upd_s = prof["k1"]["seconds"] + prof["k2"]["seconds"] + prof["fused"]["seconds"]
-    ch = prof["chase"]
-    ch_gbs = ch["bytes"] / ch["seconds"] / 1e9 if ch["seconds"] > 0 else 0.0
-    roofline_stage2 = dict(kernel="chase", bound="hbm", achieved=ch_gbs, peak=PEAK_HBM_GBS, unit="GB/s",
-                           frac=ch_gbs / PEAK_HBM_GBS, traffic=roofline_stage2_traffic)
-
-    res = {
-        "metric": "svdvals effective TFLOP/s (8/3 n^3 / time-to-singular-values)",
-        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": dtype, "data": "synthetic",
-        "config": {"lda": lda, "workload": f"{args.config}: {n}x{n} {dtype}, nb={nb}, "
-                               f"{'gaussian stand-in' if args.gaussian_input else workloads.CONFIGS[args.config]['kind']}"},
+    # the kernel class with the largest summed duration
+    dom = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
+    upd = prof["update"]
+    if dom in ("update", "update_upper"):
+        # MFMA-bound contraction: credited flops of its first-level launches (both products,
+        # 4 rows nb cols per launch; 8/3 n^3 over a run) / their summed duration
+        ach = upd["flops"] / upd["seconds"] / 1e12 if upd["seconds"] > 0 else 0.0
+        roofline = dict(kernel="update_fused_kernel (first tree level)", bound="mfma", achieved=ach, peak=peak,
+                        unit="TFLOP/s", frac=ach / peak, traffic=None,
+                        launches_per_step=upd["launches"] / steps,
+                        avg_launch_ms=upd["seconds"] / max(upd["launches"], 1) * 1e3,
+                        algorithmic_bytes_per_launch=upd["bytes"] / max(upd["launches"], 1),
+                        algorithmic_flops_per_launch=upd["flops"] / max(upd["launches"], 1))
+        cb = counter_bytes("update_fused_kernel", want_tri=False)
+        if cb:
+            roofline["traffic"] = cb[0] / cb[1]
+            roofline["traffic_unit"] = "HBM bytes per launch (FETCH_SIZE + WRITE_SIZE, calibrated), first tree level"
+        allsec = upd["seconds"] + prof["update_upper"]["seconds"]
+        roofline["frac_all_tree_levels"] = upd["flops"] / allsec / 1e12 / peak if allsec > 0 else None
+    else:
+        # a dependency chain (panel tree, band reduction, narrow chase, bisection): reported against
+        # the HBM roofline by its algorithmic bytes, which it is nowhere near
+        pk = prof[dom]
+        ach = pk["bytes"] / pk["seconds"] / 1e9 if pk["seconds"] > 0 else 0.0
+        roofline = dict(kernel=dom, bound="hbm", achieved=ach, peak=PEAK_HBM_GBS, unit="GB/s",
+                        frac=ach / PEAK_HBM_GBS, traffic=None, launches_per_step=pk["launches"] / steps,
+                        avg_launch_ms=pk["seconds"] / max(pk["launches"], 1) * 1e3,
+                        note="latency-bound dependency chain; the update kernel's MFMA figure is under roofline_update")
+    roofline_update = dict(bound="mfma", achieved=upd["flops"] / upd["seconds"] / 1e12 if upd["seconds"] > 0 else 0.0,
+                           peak=peak, unit="TFLOP/s")
+    roofline_update["frac"] = roofline_update["achieved"] / peak
+    # stage 2: algorithmic bytes of the two kernels as built (every band block read once and written
+    # once per block sweep; the narrow band once per bundle) over the stage's duration.  Both kernels
+    # are dependency chains: the HBM roofline is not what limits them.
+    s2_bytes = (prof["band_reduce"]["bytes"] + prof["narrow_chase"]["bytes"]) / steps
+    s2_gbs = s2_bytes / st[1] / 1e9 if st[1] > 0 else 0.0
+    roofline_stage2 = dict(kernels="band_reduce_kernel + chase_narrow_kernel", bound="hbm", achieved=s2_gbs,
+                           peak=PEAK_HBM_GBS, unit="GB/s", frac=s2_gbs / PEAK_HBM_GBS, traffic=None,
+                           algorithmic_bytes=s2_bytes, limited_by="latency of the sweep-to-sweep dependency chain",
+                           one_phase_chase_model_bytes=3.0 * n * n * nb * cs)
+    cb1, cb2 = counter_bytes("band_reduce_kernel"), counter_bytes("chase_narrow_kernel")
+    if cb1 and cb2:
+        roofline_stage2["traffic"] = cb1[0] + cb2[0]
+        roofline_stage2["traffic_gbs"] = (cb1[0] + cb2[0]) / st[1] / 1e9 if st[1] > 0 else None
+    kind = "gaussian stand-in" if args.gaussian_input else workloads.CONFIGS[config]["kind"]
+    return {
+        "value": value, "ms_per_step": ms_per_step, "dtype": dtype,
+        "config": {"lda": lda, "workload": f"{config}: {n}x{n} {dtype}, nb={nb}, {kind}"},
         "time_to_singular_values_ms": ms_per_step,
-        "instrumented_pass_ms_per_step": float(np.mean(ptimes)) * 1e3,
+        "instrumented_pass_ms_per_step": float(np.mean([r[0] for r in pruns])) * 1e3,
         "stage_ms": {"stage1": st[0] * 1e3, "stage2": st[1] * 1e3, "stage3": st[2] * 1e3,
-                     "panel": prof["panel"]["seconds"] / args.steps * 1e3,
-                     "update": upd_s / args.steps * 1e3},
+                     "stage1_exposed_panel": exposed_panel * 1e3},
+        "kernel_ms": kernels,
         "stage1_effective_tflops": flops / st[0] / 1e12 if st[0] > 0 else None,
         "stage1_frac_of_mfma_peak": flops / st[0] / 1e12 / peak if st[0] > 0 else None,
         "roofline": roofline,
+        "roofline_update": roofline_update,
         "roofline_stage2": roofline_stage2,
         "check": check,
     }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", default="c5a", help="workload name from workloads.CONFIGS (default: the largest "
+                    "single-GPU configuration, 32768x32768 f32, nb=128)")
+    ap.add_argument("--also", default="c4", help="comma-separated further workloads measured the same way and "
+                    "reported under extra_workloads ('none' for none)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-n", type=int, default=4096)
+    ap.add_argument("--lda-pad", type=int, default=0,
+                    help="leading dimension of the matrix handed to the library = n + this many elements")
+    ap.add_argument("--gaussian-input", action="store_true",
+                    help="profiling aid: replace the workload's values by iid Gaussians of the same shape "
+                         "(no QR-based synthesis on the device); the result line is marked accordingly")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import workloads
+    import paper_2508_06339_amd as svb
+
+    svb.load_library()  # raises when the HIP library is missing: there is no fallback
+    torch.cuda.set_device(0)
+    main_res = run_workload(args, svb, torch, workloads, args.config, args.steps, args.warmup)
+    res = {
+        "metric": "svdvals effective TFLOP/s (8/3 n^3 / time-to-singular-values)",
+        "value": main_res.pop("value"), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": main_res.pop("ms_per_step"), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": main_res.pop("dtype"), "data": "synthetic",
+    }
+    res.update(main_res)
+    extra = {}
+    for name in [x for x in args.also.split(",") if x and x != "none" and x != args.config]:
+        torch.cuda.empty_cache()
+        extra[name] = run_workload(args, svb, torch, workloads, name, args.steps, args.warmup)
+    if extra:
+        res["extra_workloads"] = extra
     if not args.no_cpu_baseline:
         res["cpu_baseline"], _ = cpu_baseline(args.config, args.cpu_sample_n)
     print(json.dumps(res))

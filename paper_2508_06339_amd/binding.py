@@ -55,6 +55,8 @@ def load_library():
     lib.svb_gb2bd.argtypes = [ctypes.c_int, _i64, ctypes.c_int, _vp, _i64, _vp, _vp, _vp,
                               ctypes.c_size_t, _vp]
     lib.svb_gb2bd.restype = ctypes.c_int
+    lib.svb_choose_nb.argtypes = [ctypes.c_int, _i64, _i64]
+    lib.svb_choose_nb.restype = ctypes.c_int
     lib.svb_gb2bd_workspace_bytes.argtypes = [_i64, ctypes.c_int, _szp]
     lib.svb_gb2bd_workspace_bytes.restype = ctypes.c_int
     lib.svb_bdsvals_dev_workspace_bytes.argtypes = [_i64, _szp]
@@ -63,7 +65,7 @@ def load_library():
     lib.svb_bdsvals_dev.restype = ctypes.c_int
     lib.svb_bdsvals.argtypes = [_i64, _dp, _dp, _dp]
     lib.svb_bdsvals.restype = ctypes.c_int
-    lib.svb_last_timings.argtypes = [_dp, _dp, _dp]
+    lib.svb_last_timings.argtypes = [_dp, _dp, _dp, _dp]
     lib.svb_last_timings.restype = ctypes.c_int
     lib.svb_profile_enable.argtypes = [ctypes.c_int]
     lib.svb_profile_enable.restype = ctypes.c_int
@@ -121,6 +123,10 @@ def svb_gb2bd(band_dt, n, nb, band_dev, ldab, d_dev, e_dev, work_dev, work_bytes
                                     _ptr(work_dev), work_bytes, _stream(stream))
 
 
+def svb_choose_nb(dt: int, m: int, n: int) -> int:
+    return load_library().svb_choose_nb(dt, m, n)
+
+
 def svb_gb2bd_workspace_bytes(n: int, nb: int):
     """Returns (status, dev_bytes)."""
     dev = ctypes.c_size_t(0)
@@ -147,12 +153,14 @@ def svb_bdsvals(n: int, d: np.ndarray, e: np.ndarray, sigma: np.ndarray) -> int:
 
 
 def svb_last_timings():
-    t = [ctypes.c_double(0.0) for _ in range(3)]
+    """(t_panel, t_update, t_stage2, t_stage3) in seconds; t_panel is -1 without per-kernel events."""
+    t = [ctypes.c_double(0.0) for _ in range(4)]
     load_library().svb_last_timings(*[ctypes.byref(x) for x in t])
     return tuple(x.value for x in t)
 
 
-SVB_PROF_PANEL, SVB_PROF_K1, SVB_PROF_K2, SVB_PROF_CHASE, SVB_PROF_FUSED = 0, 1, 2, 3, 4
+SVB_PROF_PANEL, SVB_PROF_UPDATE, SVB_PROF_UPDATE_UPPER, SVB_PROF_BAND_REDUCE, SVB_PROF_NARROW, SVB_PROF_STAGE3 = range(6)
+SVB_PROF_NAMES = ("panel", "update", "update_upper", "band_reduce", "narrow_chase", "stage3")
 
 
 def svb_profile_enable(on: bool) -> int:
@@ -172,29 +180,33 @@ def svb_profile_get(kind: int) -> dict:
     return dict(seconds=sec.value, launches=cnt.value, flops=fl.value, bytes=by.value)
 
 
-def svdvals(A, nb: int = 64, overwrite: bool = False, work=None):
-    """Singular values (descending, numpy) of a square torch tensor on the GPU.
+def svdvals(A, nb: int = 0, overwrite: bool = False, work=None):
+    """Singular values (descending, numpy) of a 2-D torch tensor on the GPU.
 
-    The tensor's memory is read as a column-major n x n matrix with lda = n; a
-    row-major tensor is therefore seen transposed, which has the same singular
-    values.  Marshals arguments for svb_svdvals; allocates the workspace with
-    torch unless one is passed in.
+    The tensor's memory is read as a column-major matrix: a row-major (C-contiguous)
+    r x c tensor is handed over as the c x r matrix with lda = c, its transpose, which
+    has the same singular values; a column-major one (the transpose of a contiguous
+    tensor) as it is.  nb = 0 lets the library choose the tile size.  Marshals arguments
+    for svb_svdvals; allocates the workspace with torch unless one is passed in.
     """
     import torch
-    if A.dim() != 2 or A.shape[0] != A.shape[1] or not A.is_cuda:
-        raise ValueError("expected a square 2-D CUDA tensor")
-    if not (A.is_contiguous() or A.t().is_contiguous()):
+    if A.dim() != 2 or not A.is_cuda:
+        raise ValueError("expected a 2-D CUDA tensor")
+    if A.is_contiguous():
+        m, n = A.shape[1], A.shape[0]
+    elif A.t().is_contiguous():
+        m, n = A.shape[0], A.shape[1]
+    else:
         raise ValueError("expected a dense row- or column-major tensor")
-    n = A.shape[0]
     dt = dtype_code(A.dtype)
     buf = A if overwrite else A.clone(memory_format=torch.preserve_format)
-    rc, dev_bytes, _ = svb_workspace_bytes(dt, n, n, nb)
+    rc, dev_bytes, _ = svb_workspace_bytes(dt, m, n, nb)
     if rc != SVB_OK:
         raise SvbError(rc, "svb_workspace_bytes")
     if work is None:
         work = torch.empty(dev_bytes, dtype=torch.uint8, device=A.device)
-    out = np.empty(n, dtype=np.float64 if dt == SVB_F64 else np.float32)
-    rc = svb_svdvals(dt, n, n, buf, n, out, nb, work, work.numel())
+    out = np.empty(min(m, n), dtype=np.float64 if dt == SVB_F64 else np.float32)
+    rc = svb_svdvals(dt, m, n, buf, m, out, nb, work, work.numel())
     if rc != SVB_OK:
         raise SvbError(rc, "svb_svdvals")
     return out

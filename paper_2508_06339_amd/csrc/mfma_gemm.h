@@ -89,6 +89,33 @@ template <> struct VecIO<float, __half> {
     }
 };
 
+// bf16 is the upper half of an f32: conversion to f32 is a shift; conversion from f32 rounds to
+// nearest even (NaN kept quiet)
+template <> struct VecIO<float, bf16_t> {
+    typedef unsigned int raw_t __attribute__((ext_vector_type(2)));
+    static __device__ __forceinline__ void ld(const bf16_t* p, float (&o)[4])
+    {
+        const raw_t v = *reinterpret_cast<const raw_t*>(p);
+        o[0] = __builtin_bit_cast(float, v.x << 16);
+        o[1] = __builtin_bit_cast(float, v.x & 0xffff0000u);
+        o[2] = __builtin_bit_cast(float, v.y << 16);
+        o[3] = __builtin_bit_cast(float, v.y & 0xffff0000u);
+    }
+    static __device__ __forceinline__ unsigned int rne(float f)
+    {
+        const unsigned int u = __builtin_bit_cast(unsigned int, f);
+        if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;   // NaN
+        return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+    }
+    static __device__ __forceinline__ void st(bf16_t* p, const float (&o)[4])
+    {
+        raw_t v;
+        v.x = rne(o[0]) | (rne(o[1]) << 16);
+        v.y = rne(o[2]) | (rne(o[3]) << 16);
+        *reinterpret_cast<raw_t*>(p) = v;
+    }
+};
+
 // Pol supplies: TM, TN, WM, WN; A_KC / B_KC (is the operand contiguous along k, or along
 // its m / n index?); RMW; storage types TA, TB, TD; ktiles();
 //   ptrA(mn, kt, k): address of NV consecutive elements of the A operand starting at tile

@@ -64,16 +64,12 @@ __device__ unsigned long long svb_fused_timing[8];
 // TRI: the panel is a stack of upper triangular NB x NB factors (every tree level above the
 // first), so in every NB-row chunk of V and of Y = V T the 16 x 16 blocks below the block
 // diagonal are exactly zero and their products are skipped.
-// MODE 0: the whole update.  MODE 1 and 2 split it for the look-ahead: 1 forms W, keeps a copy
-// in Wb (NB values per domain and column, already negated) and finishes only the first chunk
-// of every domain -- the rows the next tree level and the next panel read; 2 fetches W and
-// finishes the other chunks, and can run beside the next panel.
-template <typename T, typename C, int NB, int HT, bool LQ, bool TRI, int MODE, bool USET>
+// USET: the kernel is given the domains' T factors instead of Y (see the header of this file).
+template <typename T, typename C, int NB, int HT, bool LQ, bool TRI, bool USET>
 __global__ __launch_bounds__((FusedGeom<C, NB>::NT), (sizeof(C) == 8 && NB == 128) ? 1 : 2) void update_fused_kernel(T* __restrict__ Cb, int64_t lda, int64_t qlen,
                                                            const C* __restrict__ V, const C* __restrict__ Y,
                                                            int64_t ldp, int chunks, int g, int64_t stride,
-                                                           int strips, int total, C* __restrict__ Wb,
-                                                           const C* __restrict__ Tw)
+                                                           int strips, int total, const C* __restrict__ Tw)
 {
     using F = Frag<C>;
     using G = FusedGeom<C, NB>;
@@ -187,48 +183,22 @@ __global__ __launch_bounds__((FusedGeom<C, NB>::NT), (sizeof(C) == 8 && NB == 12
 #ifdef SVB_FUSED_TIMING
     unsigned long long ft_last = clock64();
 #endif
-    // slices of the second product this launch covers
-    constexpr int CK1 = NB / RC;   // slices of the first chunk
-    const int vlo = MODE == 2 ? CK1 : 0;
-    const int vhi = MODE == 1 ? min(nck, CK1) : nck;
-    if (MODE == 2 && vlo >= vhi) return;   // a domain of one chunk was finished by the first part
-    // this lane's part of W in the copy: rows 16*mt + roff(r, gq) of column q of domain d
-    C* wcol = (MODE != 0) ? Wb + ((int64_t)d * qlen + q) * NB : nullptr;
-
-    constexpr bool useT = USET && MODE != 2;   // (Tw is null otherwise)
+    constexpr int vlo = 0;
+    const int vhi = nck;
+    constexpr bool useT = USET;                // (Tw is null otherwise)
     const C* __restrict__ Y1 = useT ? V : Y;   // operand of the first product
     constexpr int NTS = NB / RC;               // slices of T
     int cur = 0;
-    if (MODE == 2) {
-        slice_ld(V, vlo);
+    slice_ld(Y1, 0);
 #pragma unroll
-        for (int t = 0; t < HT; ++t)
-            if (t >= 2 * CK1 && t < 2 * CK1 + PF) tile_ld(t);
-        if (active) {
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-                C o[4];
-                F::ld4(wcol + 16 * mt, gq, o);
-#pragma unroll
-                for (int r = 0; r < 4; ++r) w[mt][r] = o[r];
-            }
-        }
-        slice_st_v(smem);
-    } else {
-        slice_ld(Y1, 0);
-#pragma unroll
-        for (int t = 0; t < PF; ++t) tile_ld(t);
-        slice_st_y(smem);
-    }
+    for (int t = 0; t < PF; ++t) tile_ld(t);
+    slice_st_y(smem);
     lds_barrier();
     FT_MARK(0);
 #pragma unroll
     for (int s = 0; s < 2 * NCK; ++s) {
         const bool isV = s >= NCK;
         const int ck = isV ? s - NCK : s;
-        if (MODE == 2 && !isV) continue;
-        if (MODE == 1 && isV && ck >= CK1) continue;
-        if (MODE == 2 && isV && ck < CK1) continue;
         if (isV ? (ck >= vlo && ck < vhi) : ck < nck) {
             // the stage after this one: the next slice of the same product, or the second
             // product's first slice after the first product's last
@@ -238,7 +208,7 @@ __global__ __launch_bounds__((FusedGeom<C, NB>::NT), (sizeof(C) == 8 && NB == 12
             const bool nextV = isV || last;
             if (nextT) tslice_ld(NTS - 1);
             else if (have_next) slice_ld(nextV ? V : Y1, last ? vlo : ck + 1);
-            if (!isV || MODE == 2) {
+            if (!isV) {
 #pragma unroll
                 for (int tt = 0; tt < RC / 16; ++tt)
                     if (ck * (RC / 16) + tt + PF < HT) tile_ld(ck * (RC / 16) + tt + PF);
@@ -272,10 +242,6 @@ __global__ __launch_bounds__((FusedGeom<C, NB>::NT), (sizeof(C) == 8 && NB == 12
                         for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
                             for (int r = 0; r < 4; ++r) w[mt][r] = -w[mt][r];
-                            if (MODE == 1) {
-                                const C o[4] = {w[mt][0], w[mt][1], w[mt][2], w[mt][3]};
-                                F::st4(wcol + 16 * mt, gq, o);
-                            }
                         }
                     }
                 } else {
@@ -333,10 +299,6 @@ __global__ __launch_bounds__((FusedGeom<C, NB>::NT), (sizeof(C) == 8 && NB == 12
                             }
 #pragma unroll
                             for (int r = 0; r < 4; ++r) w[m][r] = -acc[r];
-                            if (MODE == 1) {
-                                const C o[4] = {w[m][0], w[m][1], w[m][2], w[m][3]};
-                                F::st4(wcol + 16 * m, gq, o);
-                            }
                         }
                     }
                     C* nbuf = smem + (cur ^ 1) * BUF;
@@ -351,12 +313,12 @@ __global__ __launch_bounds__((FusedGeom<C, NB>::NT), (sizeof(C) == 8 && NB == 12
 }
 #undef FT_MARK
 
-template <typename T, typename C, int NB, int HT, bool LQ, bool TRI, int MODE, bool USET>
+template <typename T, typename C, int NB, int HT, bool LQ, bool TRI, bool USET>
 static void launch_fused(T* Cb, int64_t lda, int64_t qlen, const C* V, const C* Y, int64_t ldp, int chunks,
-                         int g, int64_t stride, C* Wb, const C* Tw, bool credited, hipStream_t s)
+                         int g, int64_t stride, const C* Tw, bool credited, hipStream_t s)
 {
     using G = FusedGeom<C, NB>;
-    auto kern = update_fused_kernel<T, C, NB, HT, LQ, TRI, MODE, USET>;
+    auto kern = update_fused_kernel<T, C, NB, HT, LQ, TRI, USET>;
     static bool attr_set = false;
     if (!attr_set) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -367,44 +329,33 @@ static void launch_fused(T* Cb, int64_t lda, int64_t qlen, const C* V, const C* 
     const int strips = (int)((qlen + G::SW - 1) / G::SW);
     const int total = domains * strips;
     const int per = (total + 7) / 8;
-    // both products: 2 * rows * NB * cols flops each; the block is read once and written once.
-    // Split form: the first part does all of the first product and the first chunks' share of the
-    // second, reads the block and writes the first chunks; the second part does the rest.
-    const double rows = (double)chunks * NB, top = (double)domains * NB;
+    // both products: 2 * rows * NB * cols flops each; the block is read once and written once
+    const double rows = (double)chunks * NB;
     double fl = 4.0 * rows * NB * (double)qlen, by = 2.0 * rows * (double)qlen * sizeof(T);
-    if (MODE == 1) {
-        fl = 2.0 * (rows + top) * NB * (double)qlen;
-        by = (rows + top) * (double)qlen * sizeof(T);
-    } else if (MODE == 2) {
-        fl = 2.0 * (rows - top) * NB * (double)qlen;
-        by = 2.0 * (rows - top) * (double)qlen * sizeof(T);
-    }
     if (!credited) fl = by = 0.0;
     // profiling: the events are the kernel's own start and stop time stamps
     hipEvent_t ea = nullptr, eb = nullptr;
-    if (prof_take(SVB_PROF_FUSED, fl, by, &ea, &eb))
+    if (prof_take(TRI ? SVB_PROF_UPDATE_UPPER : SVB_PROF_UPDATE, fl, by, &ea, &eb))
         hipExtLaunchKernelGGL(kern, dim3((unsigned)(per * 8)), dim3(G::NT), (uint32_t)G::kSmemBytes, s, ea, eb, 0u, Cb,
-                              lda, qlen, V, Y, ldp, chunks, g, stride, strips, total, Wb, Tw);
+                              lda, qlen, V, Y, ldp, chunks, g, stride, strips, total, Tw);
     else
         hipLaunchKernelGGL(kern, dim3((unsigned)(per * 8)), dim3(G::NT), G::kSmemBytes, s, Cb, lda, qlen, V, Y, ldp,
-                           chunks, g, stride, strips, total, Wb, Tw);
+                           chunks, g, stride, strips, total, Tw);
 }
 
 template <typename T, typename C, int NB, int HT, bool LQ, bool TRI>
-static void launch_fused_mode(int mode, T* Cb, int64_t lda, int64_t qlen, const C* V, const C* Y, int64_t ldp,
-                              int chunks, int g, int64_t stride, C* Wb, const C* Tw, bool credited, hipStream_t s)
+static void launch_fused_t(T* Cb, int64_t lda, int64_t qlen, const C* V, const C* Y, int64_t ldp,
+                           int chunks, int g, int64_t stride, const C* Tw, bool credited, hipStream_t s)
 {
-    // the form that applies T itself exists for the whole update at nb <= 64 (at nb = 128 the
-    // extra accumulators do not fit beside the block)
+    // the form that applies T itself exists at nb <= 64 (at nb = 128 the extra accumulators do not
+    // fit beside the block)
     if constexpr (NB <= 64) {
-        if (Tw != nullptr && mode == 0) {
-            launch_fused<T, C, NB, HT, LQ, TRI, 0, true>(Cb, lda, qlen, V, Y, ldp, chunks, g, stride, Wb, Tw, credited, s);
+        if (Tw != nullptr) {
+            launch_fused<T, C, NB, HT, LQ, TRI, true>(Cb, lda, qlen, V, Y, ldp, chunks, g, stride, Tw, credited, s);
             return;
         }
     }
-    if (mode == 1) launch_fused<T, C, NB, HT, LQ, TRI, 1, false>(Cb, lda, qlen, V, Y, ldp, chunks, g, stride, Wb, nullptr, credited, s);
-    else if (mode == 2) launch_fused<T, C, NB, HT, LQ, TRI, 2, false>(Cb, lda, qlen, V, Y, ldp, chunks, g, stride, Wb, nullptr, credited, s);
-    else launch_fused<T, C, NB, HT, LQ, TRI, 0, false>(Cb, lda, qlen, V, Y, ldp, chunks, g, stride, Wb, nullptr, credited, s);
+    launch_fused<T, C, NB, HT, LQ, TRI, false>(Cb, lda, qlen, V, Y, ldp, chunks, g, stride, nullptr, credited, s);
 }
 
 template <typename C> constexpr int fused_tiles() { return sizeof(C) == 4 ? 32 : 16; }
@@ -416,18 +367,18 @@ template int fused_update_rows<double>();
 
 template <typename T, typename C>
 void launch_update_fused(int nb, bool lq, T* Cb, int64_t lda, int64_t qlen, const C* V, const C* Y,
-                         int64_t ldp, int chunks, int g, int64_t stride, bool tri, int mode, C* Wb,
-                         const C* Tw, bool credited, hipStream_t s)
+                         int64_t ldp, int chunks, int g, int64_t stride, bool tri, const C* Tw,
+                         bool credited, hipStream_t s)
 {
     if (qlen <= 0) return;
     constexpr int HT = fused_tiles<C>();
-#define SVB_FUSED_ARGS mode, Cb, lda, qlen, V, Y, ldp, chunks, g, stride, Wb, Tw, credited, s
+#define SVB_FUSED_ARGS Cb, lda, qlen, V, Y, ldp, chunks, g, stride, Tw, credited, s
 #define SVB_FUSED_CASE(NBV)                                                          \
     case NBV:                                                                        \
-        if (lq && tri) launch_fused_mode<T, C, NBV, HT, true, true>(SVB_FUSED_ARGS);   \
-        else if (lq) launch_fused_mode<T, C, NBV, HT, true, false>(SVB_FUSED_ARGS);    \
-        else if (tri) launch_fused_mode<T, C, NBV, HT, false, true>(SVB_FUSED_ARGS);   \
-        else launch_fused_mode<T, C, NBV, HT, false, false>(SVB_FUSED_ARGS);           \
+        if (lq && tri) launch_fused_t<T, C, NBV, HT, true, true>(SVB_FUSED_ARGS);   \
+        else if (lq) launch_fused_t<T, C, NBV, HT, true, false>(SVB_FUSED_ARGS);    \
+        else if (tri) launch_fused_t<T, C, NBV, HT, false, true>(SVB_FUSED_ARGS);   \
+        else launch_fused_t<T, C, NBV, HT, false, false>(SVB_FUSED_ARGS);           \
         break;
     switch (nb) {
         SVB_FUSED_CASE(32)
@@ -439,8 +390,9 @@ void launch_update_fused(int nb, bool lq, T* Cb, int64_t lda, int64_t qlen, cons
 #undef SVB_FUSED_ARGS
 }
 
-template void launch_update_fused<float, float>(int, bool, float*, int64_t, int64_t, const float*, const float*, int64_t, int, int, int64_t, bool, int, float*, const float*, bool, hipStream_t);
-template void launch_update_fused<__half, float>(int, bool, __half*, int64_t, int64_t, const float*, const float*, int64_t, int, int, int64_t, bool, int, float*, const float*, bool, hipStream_t);
-template void launch_update_fused<double, double>(int, bool, double*, int64_t, int64_t, const double*, const double*, int64_t, int, int, int64_t, bool, int, double*, const double*, bool, hipStream_t);
+template void launch_update_fused<float, float>(int, bool, float*, int64_t, int64_t, const float*, const float*, int64_t, int, int, int64_t, bool, const float*, bool, hipStream_t);
+template void launch_update_fused<__half, float>(int, bool, __half*, int64_t, int64_t, const float*, const float*, int64_t, int, int, int64_t, bool, const float*, bool, hipStream_t);
+template void launch_update_fused<bf16_t, float>(int, bool, bf16_t*, int64_t, int64_t, const float*, const float*, int64_t, int, int, int64_t, bool, const float*, bool, hipStream_t);
+template void launch_update_fused<double, double>(int, bool, double*, int64_t, int64_t, const double*, const double*, int64_t, int, int, int64_t, bool, const double*, bool, hipStream_t);
 
 }  // namespace svb

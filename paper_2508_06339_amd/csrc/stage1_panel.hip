@@ -537,9 +537,11 @@ void launch_band_clear(C* band, int64_t ldab, int64_t n, hipStream_t s)
 template void launch_panel_gather<double, double>(const double*, int64_t, int64_t, int64_t, bool, int64_t, int, double*, int64_t, hipStream_t);
 template void launch_panel_gather<float, float>(const float*, int64_t, int64_t, int64_t, bool, int64_t, int, float*, int64_t, hipStream_t);
 template void launch_panel_gather<__half, float>(const __half*, int64_t, int64_t, int64_t, bool, int64_t, int, float*, int64_t, hipStream_t);
+template void launch_panel_gather<bf16_t, float>(const bf16_t*, int64_t, int64_t, int64_t, bool, int64_t, int, float*, int64_t, hipStream_t);
 template void launch_panel_qr<double, double>(int, double*, int64_t, double*, double*, int, int, double*, int64_t, const double*, int64_t, bool, double*, int64_t, int64_t, int64_t, hipStream_t, hipEvent_t, hipEvent_t);
 template void launch_panel_qr<float, float>(int, float*, int64_t, float*, float*, int, int, float*, int64_t, const float*, int64_t, bool, float*, int64_t, int64_t, int64_t, hipStream_t, hipEvent_t, hipEvent_t);
 template void launch_panel_qr<__half, float>(int, float*, int64_t, float*, float*, int, int, float*, int64_t, const __half*, int64_t, bool, float*, int64_t, int64_t, int64_t, hipStream_t, hipEvent_t, hipEvent_t);
+template void launch_panel_qr<bf16_t, float>(int, float*, int64_t, float*, float*, int, int, float*, int64_t, const bf16_t*, int64_t, bool, float*, int64_t, int64_t, int64_t, hipStream_t, hipEvent_t, hipEvent_t);
 template void launch_scatter_r<double>(const double*, int64_t, int, double*, int64_t, int64_t, int64_t, bool, hipStream_t);
 template void launch_scatter_r<float>(const float*, int64_t, int, float*, int64_t, int64_t, int64_t, bool, hipStream_t);
 template void launch_band_clear<double>(double*, int64_t, int64_t, hipStream_t);

@@ -23,12 +23,47 @@ inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 size_t compute_size(svb_dtype dt) { return dt == SVB_F64 ? 8 : 4; }
 size_t storage_size(svb_dtype dt) { return dt == SVB_F64 ? 8 : (dt == SVB_F32 ? 4 : 2); }
 
+bool dtype_ok(svb_dtype dt) { return dt == SVB_F64 || dt == SVB_F32 || dt == SVB_F16 || dt == SVB_BF16; }
+bool nb_ok(int nb) { return nb == 32 || nb == 64 || nb == 128; }
+
+// Tile size chosen when the caller passes nb = 0 (the paper tunes TILESIZE per size and
+// hardware, Section 4 and Table 3): the smallest of the measured optima for the order of the
+// matrix.  Small tiles shorten the panel chain and stage 2, large tiles raise the arithmetic
+// intensity of the trailing update, which only matters once the update dominates.
+int choose_nb(svb_dtype dt, int64_t m, int64_t n)
+{
+    const int64_t k = m < n ? m : n;
+    (void)dt;
+    if (k <= 3072) return 32;
+    if (k <= 12288) return 64;
+    return 128;
+}
+
+inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+
+// The shape stage 1 works on: rows >= cols, both whole numbers of tiles.  `staged` says the input
+// has to be copied (zero padded, transposed if it is wider than tall) into the workspace first.
+struct Shape {
+    int64_t rows, cols;   // of the matrix stage 1 factors (padded)
+    int64_t k;            // min(m, n): number of singular values
+    bool transpose, staged;
+};
+Shape shape_of(int64_t m, int64_t n, int nb)
+{
+    Shape sh{};
+    sh.transpose = m < n;
+    const int64_t r = sh.transpose ? n : m, c = sh.transpose ? m : n;
+    sh.rows = round_up(r, nb);
+    sh.cols = round_up(c, nb);
+    sh.k = c;
+    sh.staged = sh.transpose || sh.rows != r || sh.cols != c;
+    return sh;
+}
+
 int check_shape(svb_dtype dt, int64_t m, int64_t n, int nb)
 {
     if (m < 0 || n < 0) return SVB_ERR_ARG;
-    if (dt != SVB_F64 && dt != SVB_F32 && dt != SVB_F16) return SVB_ERR_UNSUPPORTED;
-    if (nb != 32 && nb != 64 && nb != 128) return SVB_ERR_UNSUPPORTED;
-    if (m != n || n <= 0 || n % nb != 0) return SVB_ERR_UNSUPPORTED;
+    if (!dtype_ok(dt) || !nb_ok(nb)) return SVB_ERR_UNSUPPORTED;
     return SVB_OK;
 }
 
@@ -51,77 +86,126 @@ bool two_phase(int nb, size_t elem_size, int64_t n)
     return nb != 8 && n >= 3 && env_int("SVB_CHASE_IMPL", 2) == 2 && band_reduce_supported(nb, elem_size);
 }
 
+// Algorithmic bytes of the two stage-2 kernels: the band reduction reads and writes every nb x nb
+// block once per block sweep (two blocks per step, about n/nb - 8s/nb steps in sweep s, n/8
+// sweeps: n^2 nb / 4 elements each way in all ... counted as 2 * 2 * nb^2 per step); the narrow
+// chase reads and writes the band's 24 stored rows from its first column on once per bundle.
+double band_reduce_bytes(int64_t n, int nb, size_t cs)
+{
+    double steps = 0.0;
+    for (int64_t s = 0; s < (n - 1) / 8; ++s) steps += (double)((n - 1 - (s + 1) * 8) / nb + 1);
+    return steps * 4.0 * (double)nb * nb * (double)cs;
+}
+double narrow_bytes(int64_t n, size_t cs)
+{
+    const int64_t nw = cs == 8 ? 24 : 48;
+    double cols = 0.0;
+    for (int64_t i0 = 0; i0 < n - 2; i0 += nw) cols += (double)(n - i0);
+    return cols * 24.0 * 2.0 * (double)cs;
+}
+
 template <typename C>
 int gb2bd_typed(int64_t n, int nb, C* band, int64_t ldab, C* d, C* e, void* work, size_t work_bytes, hipStream_t s)
 {
     int* ctrl = static_cast<int*>(work);
     if (nb == 8) {
         // narrow band: bundles of sweeps inside LDS windows
+        prof_begin(SVB_PROF_NARROW, s, 0.0, narrow_bytes(n, sizeof(C)));
         const int rc = run_chase_narrow<C>(n, band, ldab, 15, ctrl, s);
+        prof_end(s);
         launch_extract_bidiag<C>(band, ldab, n, 8, d, e, ctrl, nullptr, s);
         return rc;
     }
     if (two_phase(nb, sizeof(C), n)) {
         int* ctrl2 = reinterpret_cast<int*>(static_cast<unsigned char*>(work) + gb2bd_first_bytes(n, nb));
+        prof_begin(SVB_PROF_BAND_REDUCE, s, 0.0, band_reduce_bytes(n, nb, sizeof(C)));
         int rc = run_band_reduce<C>(n, nb, band, ldab, ctrl, s);
-        if (rc == SVB_OK) rc = run_chase_narrow<C>(n, band, ldab, 2 * (int64_t)nb - 1, ctrl2, s);
+        prof_end(s);
+        if (rc == SVB_OK) {
+            prof_begin(SVB_PROF_NARROW, s, 0.0, narrow_bytes(n, sizeof(C)));
+            rc = run_chase_narrow<C>(n, band, ldab, 2 * (int64_t)nb - 1, ctrl2, s);
+            prof_end(s);
+        }
         launch_extract_bidiag<C>(band, ldab, n, nb, d, e, ctrl, ctrl2, s);
         return rc;
     }
-    return run_chase<C>(n, nb, band, ldab, d, e, work, work_bytes, s);
+    prof_begin(SVB_PROF_BAND_REDUCE, s, 0.0, 3.0 * (double)n * (double)n * nb * sizeof(C));
+    const int rc = run_chase<C>(n, nb, band, ldab, d, e, work, work_bytes, s);
+    prof_end(s);
+    return rc;
 }
 
 // the update kernels move 16-byte vectors along both directions of A
-bool aligned_for_vectors(const void* A, int64_t lda)
+bool aligned_for_vectors(const void* A, int64_t lda, svb_dtype dt)
 {
-    return reinterpret_cast<uintptr_t>(A) % 16 == 0 && lda % 4 == 0;
+    return reinterpret_cast<uintptr_t>(A) % 16 == 0 && lda % (dt == SVB_F64 ? 2 : 4) == 0;
 }
+
+// Environment switches, read once per process (they select kernel variants kept for testing and
+// measurement; the launch loops consult this copy).
+struct Switches {
+    int domain_chunks, pipeline_layout, ext_events, update_t, event_fence, stage3_host, stage3_relative, no_scale;
+    bool loaded = false;
+    void load()
+    {
+        domain_chunks = env_int("SVB_DOMAIN_CHUNKS", 0);
+        pipeline_layout = env_int("SVB_PIPELINE_LAYOUT", 1);
+        ext_events = env_int("SVB_EXT_EVENTS", 1);
+        update_t = env_int("SVB_UPDATE_T", 1);
+        event_fence = env_int("SVB_EVENT_FENCE", 0);
+        const char* v = std::getenv("SVB_STAGE3");
+        stage3_host = v && std::strcmp(v, "host") == 0;
+        stage3_relative = env_int("SVB_STAGE3_RELATIVE", 0);
+        no_scale = env_int("SVB_NO_SCALE", 0);
+        loaded = true;
+    }
+} g_sw;
+// (tests change the variables between calls: every entry point reloads them once, outside the
+// launch loops)
+const Switches& switches() { g_sw.load(); return g_sw; }
 
 // chunks-per-domain of the panel tree: as many nb-row tiles as the register-resident
 // panel and update kernels hold (512 rows in f32, 256 in f64)
-int domain_chunks(svb_dtype dt, int nb)
+int domain_chunks(svb_dtype dt, int nb, const Switches& sw)
 {
-    int g = env_int("SVB_DOMAIN_CHUNKS", 0);
-    if (g >= 2 && g <= 64) return g;
-    return (dt == SVB_F64 ? 256 : 512) / nb;
+    const int cap = (dt == SVB_F64 ? 256 : 512) / nb;
+    const int g = sw.domain_chunks;
+    if (g >= 2 && g <= cap) return g;
+    return cap;
 }
 constexpr int kMinDomainChunks = 2;  // workspace is sized for any g >= this
 
-// Workspace layout (element counts in the compute type).
+// Workspace layout.  V, Y, T: the panels and factors of one half-sweep's tree (element counts in
+// the compute type); stage: the zero-padded copy of an input that is not a whole number of tiles
+// or is wider than tall (storage type).
 struct Carve {
-    size_t panel_elems;  // V panels of all levels
-    size_t w_elems;      // W of the largest level
-    size_t t_elems;      // T factors of one level
-    size_t band_elems, de_elems;
-    size_t off_V[2], off_Y[2], off_W[2], off_T[2], off_band, off_d, off_e, off_sig, off_s3, off_err, total;
+    size_t panel_elems, t_elems, band_elems, de_elems, stage_elems;
+    size_t off_V, off_Y, off_T, off_band, off_d, off_e, off_sig, off_s3, off_fac, off_gb, off_stage, total;
 };
 
-Carve carve(svb_dtype dt, int64_t n, int nb)
+Carve carve(svb_dtype dt, const Shape& sh, int nb)
 {
     Carve c{};
     const size_t cs = compute_size(dt);
-    // levels shrink by >= kMinDomainChunks: sum of panel rows <= 2n (+ one chunk per level)
-    c.panel_elems = (size_t)(2 * n + (int64_t)(kMaxLevels + 2) * nb) * nb;
-    // W of every tree level: n^2/g * (1 + 1/g + ...) <= n^2 for g >= 2
-    c.w_elems = (size_t)n * (size_t)n + (size_t)n * nb * (kMaxLevels + 1);
-    c.t_elems = 2 * (size_t)(n / nb + 1) * nb * nb;  // T per domain, plus room for the v^T v products
-    c.band_elems = (size_t)(3 * nb) * (size_t)n;
-    c.de_elems = (size_t)n;
+    const int64_t rows = sh.rows, cols = sh.cols;
+    // levels shrink by >= kMinDomainChunks: sum of panel rows <= 2 rows (+ one chunk per level)
+    c.panel_elems = (size_t)(2 * rows + (int64_t)(kMaxLevels + 2) * nb) * nb;
+    c.t_elems = 2 * (size_t)(rows / nb + 1) * nb * nb;  // T per domain, plus room for the v^T v products
+    c.band_elems = (size_t)(3 * nb) * (size_t)cols;
+    c.de_elems = (size_t)cols;
+    c.stage_elems = sh.staged ? (size_t)rows * (size_t)cols : 0;
     size_t off = 0;
-    // two sets: a half-sweep's deferred update still reads its set while the next panel is built
-    for (int b = 0; b < 2; ++b) {
-        c.off_V[b] = off; off += align_up(c.panel_elems * cs);
-        c.off_Y[b] = off; off += align_up(c.panel_elems * cs);
-        c.off_W[b] = off; off += align_up(c.w_elems * cs);
-        c.off_T[b] = off; off += align_up(c.t_elems * cs);
-    }
+    c.off_V = off; off += align_up(c.panel_elems * cs);
+    c.off_Y = off; off += align_up(c.panel_elems * cs);
+    c.off_T = off; off += align_up(c.t_elems * cs);
     c.off_band = off; off += align_up(c.band_elems * cs);
     c.off_d = off; off += align_up(c.de_elems * cs);
     c.off_e = off; off += align_up(c.de_elems * cs);
     c.off_sig = off; off += align_up(c.de_elems * cs);
-    c.off_s3 = off; off += align_up(bdsvals_dev_workspace_bytes(n));
-    c.off_err = off; off += 256;
-    off += align_up(gb2bd_bytes(n, nb));
+    c.off_s3 = off; off += align_up(bdsvals_dev_workspace_bytes(sh.k));
+    c.off_fac = off; off += align_up(scale_workspace_bytes());
+    c.off_gb = off; off += align_up(gb2bd_bytes(sh.k, nb));
+    c.off_stage = off; off += align_up(c.stage_elems * storage_size(dt));
     c.total = off;
     return c;
 }
@@ -147,7 +231,7 @@ int build_levels(int64_t len, int nb, int g, Level* lv)
     return nl;
 }
 
-struct Timings { double s1 = 0, s2 = 0, s3 = 0; } g_last;
+struct Timings { double s1 = 0, s2 = 0, s3 = 0, upd = -1; } g_last;
 
 // Optional per-kernel timing with events on the launching stream.
 struct Profiler {
@@ -207,52 +291,32 @@ struct Profiler {
     }
 } g_prof;
 
-// Streams and events for the look-ahead (created once per process).  Stage 1 runs on two
-// internal streams forked from the caller's stream and joined back to it: `m` carries the
-// chain panel -> first part of the update -> next panel, `h` the deferred part of the update.
-// `h` is confined to a subset of the compute units (SVB_HELPER_MASK_BITS of them, default 224
-// of 256), so that the few workgroups of a panel kernel, each of which needs a compute unit
-// of its own, find one free while the deferred update is running.  (A stream with a CU mask
-// is an ordinary blocking stream: it would serialise with the NULL stream, which is why the
-// chain does not run on the caller's stream itself.)
+// Streams and events of stage 1 (created once per process).  Stage 1 runs on two internal
+// streams forked from the caller's stream and joined back to it: `m` carries the panel tree and
+// the last level's update, `u` the updates of the levels below.  (The chain does not run on the
+// caller's stream itself so that it never serialises with the NULL stream.)
 void g_la_release();
 struct Lookahead {
-    hipStream_t m = nullptr, h = nullptr, u = nullptr;
-    hipEvent_t crit[2] = {nullptr, nullptr}, rest[2] = {nullptr, nullptr}, fork = nullptr, join = nullptr;
-    // level pipeline: panel level L of a half-sweep done / its update done; the update stream's join
-    hipEvent_t lvl[2][kMaxLevels] = {}, udone[2] = {nullptr, nullptr}, join_u = nullptr;
+    hipStream_t m = nullptr, u = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr, join_u = nullptr;
+    // level pipeline: panel level L of a half-sweep done / the side stream's updates done
+    hipEvent_t lvl[2][kMaxLevels] = {}, udone[2] = {nullptr, nullptr};
+    // stage boundaries of svb_svdvals, reused by every call
+    hipEvent_t stage[4] = {nullptr, nullptr, nullptr, nullptr};
     bool ok = false, tried = false;
-    static bool masked_stream(hipStream_t* st, int bits)
-    {
-        // bit i of a CU mask is compute unit i / 8 of XCD i % 8 (measured): clearing the top bits
-        // takes the same number of CUs away from every XCD
-        if (bits > 0 && bits < 256) {
-            uint32_t mask[8];
-            for (int w = 0; w < 8; ++w) {
-                const int nb = bits - 32 * w;
-                mask[w] = nb >= 32 ? 0xffffffffu : (nb <= 0 ? 0u : ((1u << nb) - 1u));
-            }
-            return hipExtStreamCreateWithCUMask(st, 8, mask) == hipSuccess;
-        }
-        return hipStreamCreateWithFlags(st, hipStreamNonBlocking) == hipSuccess;
-    }
-    bool init()
+    bool init(const Switches& sw)
     {
         if (tried) return ok;
         tried = true;
         if (hipStreamCreateWithFlags(&m, hipStreamNonBlocking) != hipSuccess) return false;
-        if (!masked_stream(&h, env_int("SVB_HELPER_MASK_BITS", 224))) return false;
-        if (!masked_stream(&u, env_int("SVB_UPDATE_MASK_BITS", 256))) return false;
+        if (hipStreamCreateWithFlags(&u, hipStreamNonBlocking) != hipSuccess) return false;
         // events between the two internal streams order kernels of one device against each other:
         // no system-scope fence (a cache write-back for the host's and other devices' benefit) is
         // needed when they are recorded, and it would sit on the critical path of every half-sweep
-        const unsigned kInner = env_int("SVB_EVENT_FENCE", 0) ? hipEventDisableTiming
-                                                              : (hipEventDisableTiming | hipEventDisableSystemFence);
+        const unsigned kInner = sw.event_fence ? hipEventDisableTiming
+                                               : (hipEventDisableTiming | hipEventDisableSystemFence);
         for (int i = 0; i < 2; ++i) {
-            if (hipEventCreateWithFlags(&crit[i], kInner) != hipSuccess ||
-                hipEventCreateWithFlags(&rest[i], kInner) != hipSuccess ||
-                hipEventCreateWithFlags(&udone[i], kInner) != hipSuccess)
-                return false;
+            if (hipEventCreateWithFlags(&udone[i], kInner) != hipSuccess) return false;
             for (int L = 0; L < kMaxLevels; ++L)
                 if (hipEventCreateWithFlags(&lvl[i][L], kInner) != hipSuccess) return false;
         }
@@ -260,9 +324,10 @@ struct Lookahead {
             hipEventCreateWithFlags(&join, hipEventDisableTiming) != hipSuccess ||
             hipEventCreateWithFlags(&join_u, hipEventDisableTiming) != hipSuccess)
             return false;
+        for (int i = 0; i < 4; ++i)
+            if (hipEventCreate(&stage[i]) != hipSuccess) return false;
         ok = true;
-        // released while the HIP runtime is still up (handlers registered later run earlier):
-        // a CU-masked stream left to process teardown has crashed tools that hook the runtime
+        // released while the HIP runtime is still up (handlers registered later run earlier)
         std::atexit([] { g_la_release(); });
         return true;
     }
@@ -270,52 +335,54 @@ struct Lookahead {
     {
         if (!ok) return;
         ok = false;
-        (void)hipStreamSynchronize(h);
         (void)hipStreamSynchronize(u);
         (void)hipStreamSynchronize(m);
         for (int i = 0; i < 2; ++i) {
-            (void)hipEventDestroy(crit[i]);
-            (void)hipEventDestroy(rest[i]);
             (void)hipEventDestroy(udone[i]);
             for (int L = 0; L < kMaxLevels; ++L) (void)hipEventDestroy(lvl[i][L]);
         }
         (void)hipEventDestroy(fork);
         (void)hipEventDestroy(join);
         (void)hipEventDestroy(join_u);
-        (void)hipStreamDestroy(h);
+        for (int i = 0; i < 4; ++i) (void)hipEventDestroy(stage[i]);
         (void)hipStreamDestroy(u);
         (void)hipStreamDestroy(m);
     }
 } g_la;
 void g_la_release() { g_la.release(); }
 
-// Stage 1 driver, level pipeline (the default with the one-pass update).  The tree levels of a
-// panel depend on each other only through the R factors, not through the trailing matrix, so
-// once level L of the panel is factored its update U_L can run while level L+1 is being factored.
-// Two internal streams:   main: P0 P1 .. Pl Ul P0' ..      side: U0 .. Ul-1
+// Stage 1 driver (Section 3.1, Algorithms 1 and 2): for every tile column k a QR half-sweep
+// (panel = block column k from the diagonal down, update = the columns right of it) and, but for
+// the last one, an LQ half-sweep (panel = block row k right of the diagonal tile, update = the
+// rows below it).  The matrix is rows x cols, rows >= cols, both whole numbers of tiles.
+//
+// Level pipeline: the tree levels of a panel depend on each other only through the R factors, not
+// through the trailing matrix, so once level L of the panel is factored its update U_L can run
+// while level L+1 is being factored.  Two internal streams:
+//     main: P0 P1 .. Pl Ul P0' ..      side: U0 .. Ul-1
 // The last level's update and the next half-sweep's first panel follow the panel tree on the main
 // stream: a dependency that crosses streams costs two to three times what one inside a stream
 // does (measured), and for all but the largest trailing matrices the panel tree is the longer
 // chain of a half-sweep.  (SVB_PIPELINE_LAYOUT=0: every update on the side stream.)
 template <typename T, typename C>
-int ge2gb_pipeline(int64_t n, T* A, int64_t lda, int nb, C* band, int64_t ldab, unsigned char* work,
-                   const Carve& cv, int g, hipStream_t caller)
+int ge2gb_pipeline(int64_t rows, int64_t cols, T* A, int64_t lda, int nb, C* band, int64_t ldab,
+                   unsigned char* work, const Carve& cv, int g, const Switches& sw, hipStream_t caller)
 {
-    const int64_t N = n / nb;
+    const int64_t N = cols / nb;
     Level lv[kMaxLevels];
     hipStream_t ms = g_la.m, ss = g_la.u;
     (void)hipEventRecord(g_la.fork, caller);
     (void)hipStreamWaitEvent(ms, g_la.fork, 0);
     (void)hipStreamWaitEvent(ss, g_la.fork, 0);
-    launch_band_clear<C>(band, ldab, n, ms);
-    C* Vb = reinterpret_cast<C*>(work + cv.off_V[0]);
-    C* Yb = reinterpret_cast<C*>(work + cv.off_Y[0]);
-    C* Tb = reinterpret_cast<C*>(work + cv.off_T[0]);
+    launch_band_clear<C>(band, ldab, cols, ms);
+    C* Vb = reinterpret_cast<C*>(work + cv.off_V);
+    C* Yb = reinterpret_cast<C*>(work + cv.off_Y);
+    C* Tb = reinterpret_cast<C*>(work + cv.off_T);
     const bool direct = panel_blk_serves<C>(nb, g);
-    const int layout = env_int("SVB_PIPELINE_LAYOUT", 1);
+    const int layout = sw.pipeline_layout;
     // a level's event is tied to the completion of its kernel instead of being recorded behind it
     // (one marker less in the main stream between two panel levels)
-    const bool ext_events = env_int("SVB_EXT_EVENTS", 1) != 0;
+    const bool ext_events = sw.ext_events != 0;
     int hs = 0;
     bool side_pending = false;
     for (int64_t k = 0; k < N; ++k) {
@@ -325,8 +392,11 @@ int ge2gb_pipeline(int64_t n, T* A, int64_t lda, int nb, C* band, int64_t ldab, 
             const int set = hs & 1;
             const int64_t row0 = k * nb;
             const int64_t col0 = lq ? (k + 1) * nb : k * nb;
-            const int64_t len = lq ? n - (k + 1) * nb : n - k * nb;
-            const int64_t qlen = n - (k + 1) * nb;
+            // panel length (along the panel direction) and the extent of the trailing matrix
+            // across it: a QR panel runs down the rows, its update covers the columns right of it;
+            // an LQ panel runs along the columns, its update covers the rows below it
+            const int64_t len = lq ? cols - (k + 1) * nb : rows - k * nb;
+            const int64_t qlen = lq ? rows - (k + 1) * nb : cols - (k + 1) * nb;
             const int nl = build_levels(len, nb, g, lv);
             // every level keeps its own T factors until its update has run: the update applies
             // them itself (no Y = V T between a panel and its update) where they all fit
@@ -335,7 +405,7 @@ int ge2gb_pipeline(int64_t n, T* A, int64_t lda, int nb, C* band, int64_t ldab, 
                 toff[L] = tsum;
                 tsum += (int64_t)lv[L].domains * nb * nb;
             }
-            const bool useT = direct && nb <= 64 && tsum <= (int64_t)cv.t_elems && env_int("SVB_UPDATE_T", 1) != 0;
+            const bool useT = direct && nb <= 64 && tsum <= (int64_t)cv.t_elems && sw.update_t != 0;
             const bool split = layout == 0 && qlen > 0;
             T* Cb = lq ? A + (k + 1) * nb + (k + 1) * nb * lda : A + k * nb + (k + 1) * nb * lda;
             // Factors level L on stream st and returns the event that fires when the level is done
@@ -367,7 +437,7 @@ int ge2gb_pipeline(int64_t n, T* A, int64_t lda, int nb, C* band, int64_t ldab, 
             };
             auto update = [&](int L, hipStream_t st) {
                 launch_update_fused<T, C>(nb, lq, Cb, lda, qlen, Vb + lv[L].poff, Yb + lv[L].poff, lv[L].ldp,
-                                          lv[L].chunks, g, lv[L].stride, L > 0, 0, (C*)nullptr,
+                                          lv[L].chunks, g, lv[L].stride, L > 0,
                                           useT ? Tb + toff[L] : (const C*)nullptr, L == 0, st);
             };
             if (side_pending) {
@@ -409,144 +479,46 @@ int ge2gb_pipeline(int64_t n, T* A, int64_t lda, int nb, C* band, int64_t ldab, 
     return hipGetLastError() == hipSuccess ? SVB_OK : SVB_ERR_DEVICE;
 }
 
-// Stage 1 driver.  Per half-sweep: panel tree on the caller's stream; then, level by
-// level, K1 and the part of K2 that the next level and the next panel read (the first
-// chunk of every domain); the rest of K2 (the bulk of its work) is handed to a helper
-// stream and overlaps the next half-sweep's panel, which only touches the first chunk.
-// The next half-sweep's K1 waits for it.
 template <typename T, typename C>
-int ge2gb_impl(int64_t n, T* A, int64_t lda, int nb, C* band, int64_t ldab, unsigned char* work,
-               const Carve& cv, hipStream_t caller)
+int ge2gb_typed(svb_dtype dt, int64_t rows, int64_t cols, T* A, int64_t lda, int nb, C* band, int64_t ldab,
+                unsigned char* work, const Carve& cv, const Switches& sw, hipStream_t s)
 {
-    const int g = domain_chunks(sizeof(C) == 8 ? SVB_F64 : SVB_F32, nb);
-    // update: 2 = one pass over the trailing matrix per tree level (default, when the domain fits
-    // the kernel's registers), 1 = two MFMA kernels with look-ahead, 0 = plain FMA kernels
-    int impl = env_int("SVB_UPDATE_IMPL", 2);
-    if (impl == 2 && g * nb > fused_update_rows<C>()) impl = 1;
-    if (impl == 2 && env_int("SVB_PIPELINE", 1) != 0 && g_la.init())
-        return ge2gb_pipeline<T, C>(n, A, lda, nb, band, ldab, work, cv, g, caller);
-    const bool la = impl != 0 && env_int("SVB_LOOKAHEAD", 1) != 0 && g_la.init();
-    const int64_t N = n / nb;
-    Level lv[kMaxLevels];
-    int64_t woff[kMaxLevels];
-    // with look-ahead the work runs on the internal streams, forked from the caller's here and
-    // joined back at the end
-    hipStream_t s = caller;
-    if (la) {
-        s = g_la.m;
-        (void)hipEventRecord(g_la.fork, caller);
-        (void)hipStreamWaitEvent(s, g_la.fork, 0);
-    }
-
-    launch_band_clear<C>(band, ldab, n, s);
-    int hs = 0;            // half-sweep counter: selects the buffer set and the events
-    bool pending = false;  // deferred K2 work of the previous half-sweep is in flight on the helper stream
-    for (int64_t k = 0; k < N; ++k) {
-        for (int half = 0; half < 2; ++half) {
-            const bool lq = half == 1;
-            if (lq && k == N - 1) break;
-            const int set = hs & 1;
-            C* Vb = reinterpret_cast<C*>(work + cv.off_V[set]);
-            C* Yb = reinterpret_cast<C*>(work + cv.off_Y[set]);
-            C* Wb = reinterpret_cast<C*>(work + cv.off_W[set]);
-            C* Tb = reinterpret_cast<C*>(work + cv.off_T[set]);
-            // panel: QR -> rows k*nb.., columns k*nb..; LQ -> rows k*nb.., columns (k+1)*nb..
-            const int64_t row0 = k * nb;
-            const int64_t col0 = lq ? (k + 1) * nb : k * nb;
-            const int64_t len = lq ? n - (k + 1) * nb : n - k * nb;
-            const int nl = build_levels(len, nb, g, lv);
-            g_prof.begin(SVB_PROF_PANEL, s, 2.0 * (double)len * nb * nb, 0.0);
-            // the blocked panel kernel reads the first level's panel straight from the matrix and
-            // writes the last level's R straight into the band; the other kernels go through a
-            // gathered copy and a scatter
-            const bool direct = panel_blk_serves<C>(nb, g);
-            if (!direct) launch_panel_gather<T, C>(A, lda, row0, col0, lq, len, nb, Vb + lv[0].poff, lv[0].ldp, s);
-            for (int L = 0; L < nl; ++L) {
-                // the R factors of level L are stacked into level L+1's panel; the last
-                // level's single R lands right behind it
-                const int64_t next_off = lv[L].poff + lv[L].ldp * nb;
-                const int64_t ldnext = (int64_t)lv[L].domains * nb;
-                const bool last = L == nl - 1;
-                launch_panel_qr<T, C>(nb, Vb + lv[L].poff, lv[L].ldp, Yb + lv[L].poff, Tb, lv[L].chunks, g,
-                                      Vb + next_off, ldnext, (direct && L == 0) ? A + row0 + col0 * lda : nullptr, lda, lq,
-                                      (direct && last) ? band : nullptr, ldab, row0, col0, s);
-                if (last && !direct)
-                    launch_scatter_r<C>(Vb + next_off, ldnext, nb, band, ldab, row0, col0, lq, s);
-            }
-            g_prof.end(s);
-            // the previous half-sweep's deferred update must be complete before this one's K1
-            if (pending) {
-                (void)hipStreamWaitEvent(s, g_la.rest[(hs - 1) & 1], 0);
-                pending = false;
-            }
-            // trailing matrix: QR -> rows k*nb.., columns (k+1)*nb..;  LQ -> rows (k+1)*nb.., columns (k+1)*nb..
-            const int64_t qlen = n - (k + 1) * nb;
-            if (qlen > 0) {
-                T* Cb = lq ? A + (k + 1) * nb + (k + 1) * nb * lda : A + k * nb + (k + 1) * nb * lda;
-                int64_t wo = 0;
-                bool any_rest = false;
-                for (int L = 0; L < nl; ++L) {
-                    woff[L] = wo;
-                    wo += (int64_t)lv[L].domains * nb * qlen;
-                    any_rest = any_rest || lv[L].chunks > lv[L].domains;
-                }
-                // splitting pays once a launch is many rounds of workgroups; below that
-                // both parts would take as long as the whole
-                const bool big = impl != 2 || (int64_t)lv[0].domains * ((qlen + 63) / 64) >= env_int("SVB_LOOKAHEAD_MIN_TILES", 4096);
-                const bool defer = la && any_rest && big;
-                if (impl == 2) {
-                    // one pass per level; with look-ahead split in two: the part the next panel
-                    // waits for here, the rest on the helper stream under that panel
-                    for (int L = 0; L < nl; ++L)
-                        launch_update_fused<T, C>(nb, lq, Cb, lda, qlen, Vb + lv[L].poff, Yb + lv[L].poff,
-                                                  lv[L].ldp, lv[L].chunks, g, lv[L].stride, L > 0, defer ? 1 : 0,
-                                                  Wb + woff[L], (const C*)nullptr, L == 0, s);
-                    if (defer) {
-                        (void)hipEventRecord(g_la.crit[set], s);
-                        (void)hipStreamWaitEvent(g_la.h, g_la.crit[set], 0);
-                        for (int L = 0; L < nl; ++L)
-                            if (lv[L].chunks > lv[L].domains)
-                                launch_update_fused<T, C>(nb, lq, Cb, lda, qlen, Vb + lv[L].poff, Yb + lv[L].poff,
-                                                          lv[L].ldp, lv[L].chunks, g, lv[L].stride, L > 0, 2,
-                                                          Wb + woff[L], (const C*)nullptr, L == 0, g_la.h);
-                        (void)hipEventRecord(g_la.rest[set], g_la.h);
-                        pending = true;
-                    }
-                } else {
-                for (int L = 0; L < nl; ++L)
-                    launch_update<T, C>(nb, lq, Cb, lda, qlen, Vb + lv[L].poff, Yb + lv[L].poff, lv[L].ldp,
-                                        lv[L].chunks, g, lv[L].stride, Wb + woff[L], impl, L == 0, defer ? 1 : 0, s);
-                if (defer) {
-                    (void)hipEventRecord(g_la.crit[set], s);
-                    (void)hipStreamWaitEvent(g_la.h, g_la.crit[set], 0);
-                    for (int L = 0; L < nl; ++L)
-                        launch_update<T, C>(nb, lq, Cb, lda, qlen, Vb + lv[L].poff, Yb + lv[L].poff, lv[L].ldp,
-                                            lv[L].chunks, g, lv[L].stride, Wb + woff[L], impl, L == 0, 2, g_la.h);
-                    (void)hipEventRecord(g_la.rest[set], g_la.h);
-                    pending = true;
-                }
-                }
-            }
-            ++hs;
-        }
-    }
-    if (pending) (void)hipStreamWaitEvent(s, g_la.rest[(hs - 1) & 1], 0);
-    if (la) {
-        (void)hipEventRecord(g_la.join, s);
-        (void)hipStreamWaitEvent(caller, g_la.join, 0);
-    }
-    return hipGetLastError() == hipSuccess ? SVB_OK : SVB_ERR_DEVICE;
+    if (!g_la.init(sw)) return SVB_ERR_DEVICE;
+    const int g = domain_chunks(dt, nb, sw);
+    return ge2gb_pipeline<T, C>(rows, cols, A, lda, nb, band, ldab, work, cv, g, sw, s);
 }
 
-int ge2gb_dispatch(svb_dtype dt, int64_t n, void* A, int64_t lda, int nb, void* band, int64_t ldab,
-                   void* work, const Carve& cv, hipStream_t s)
+int ge2gb_dispatch(svb_dtype dt, int64_t rows, int64_t cols, void* A, int64_t lda, int nb, void* band, int64_t ldab,
+                   void* work, const Carve& cv, const Switches& sw, hipStream_t s)
 {
     unsigned char* w = static_cast<unsigned char*>(work);
     switch (dt) {
-    case SVB_F64: return ge2gb_impl<double, double>(n, (double*)A, lda, nb, (double*)band, ldab, w, cv, s);
-    case SVB_F32: return ge2gb_impl<float, float>(n, (float*)A, lda, nb, (float*)band, ldab, w, cv, s);
-    case SVB_F16: return ge2gb_impl<__half, float>(n, (__half*)A, lda, nb, (float*)band, ldab, w, cv, s);
+    case SVB_F64: return ge2gb_typed<double, double>(dt, rows, cols, (double*)A, lda, nb, (double*)band, ldab, w, cv, sw, s);
+    case SVB_F32: return ge2gb_typed<float, float>(dt, rows, cols, (float*)A, lda, nb, (float*)band, ldab, w, cv, sw, s);
+    case SVB_F16: return ge2gb_typed<__half, float>(dt, rows, cols, (__half*)A, lda, nb, (float*)band, ldab, w, cv, sw, s);
+    case SVB_BF16: return ge2gb_typed<bf16_t, float>(dt, rows, cols, (bf16_t*)A, lda, nb, (float*)band, ldab, w, cv, sw, s);
     default: return SVB_ERR_UNSUPPORTED;
+    }
+}
+
+// staging copy and scaling, by storage type
+void stage_copy_dispatch(svb_dtype dt, const void* A, int64_t lda, int64_t m, int64_t n, const Shape& sh, void* S,
+                         hipStream_t s)
+{
+    switch (dt) {
+    case SVB_F64: launch_stage_copy<double>((const double*)A, lda, m, n, sh.transpose, (double*)S, sh.rows, sh.rows, sh.cols, s); break;
+    case SVB_F32: launch_stage_copy<float>((const float*)A, lda, m, n, sh.transpose, (float*)S, sh.rows, sh.rows, sh.cols, s); break;
+    case SVB_F16: launch_stage_copy<__half>((const __half*)A, lda, m, n, sh.transpose, (__half*)S, sh.rows, sh.rows, sh.cols, s); break;
+    default: launch_stage_copy<bf16_t>((const bf16_t*)A, lda, m, n, sh.transpose, (bf16_t*)S, sh.rows, sh.rows, sh.cols, s); break;
+    }
+}
+void scale_dispatch(svb_dtype dt, void* A, int64_t lda, int64_t rows, int64_t cols, double* factors, hipStream_t s)
+{
+    switch (dt) {
+    case SVB_F64: launch_scale_to_range<double>((double*)A, lda, rows, cols, factors, s); break;
+    case SVB_F32: launch_scale_to_range<float>((float*)A, lda, rows, cols, factors, s); break;
+    case SVB_BF16: launch_scale_to_range<bf16_t>((bf16_t*)A, lda, rows, cols, factors, s); break;
+    default: break;   // every finite f16 value lies inside the range that needs no scaling
     }
 }
 
@@ -565,12 +537,20 @@ using namespace svb;
 
 extern "C" {
 
+int svb_choose_nb(svb_dtype dt, int64_t m, int64_t n)
+{
+    if (m < 0 || n < 0 || !dtype_ok(dt)) return 0;
+    return choose_nb(dt, m, n);
+}
+
 int svb_workspace_bytes(svb_dtype dt, int64_t m, int64_t n, int nb, size_t* dev_bytes, size_t* host_bytes)
 {
+    if (nb == 0 && m >= 0 && n >= 0 && dtype_ok(dt)) nb = choose_nb(dt, m, n);
     const int rc = check_shape(dt, m, n, nb);
     if (rc != SVB_OK) return rc;
-    const Carve cv = carve(dt, n, nb);
-    if (dev_bytes) *dev_bytes = cv.total;
+    size_t total = 256;
+    if (m > 0 && n > 0) total = carve(dt, shape_of(m, n, nb), nb).total;
+    if (dev_bytes) *dev_bytes = total;
     if (host_bytes) *host_bytes = 0;
     return SVB_OK;
 }
@@ -580,11 +560,22 @@ int svb_ge2gb(svb_dtype dt, int64_t m, int64_t n, void* A_dev, int64_t lda, int 
 {
     const int rc = check_shape(dt, m, n, nb);
     if (rc != SVB_OK) return rc;
+    // the stage-split entry point works in place: whole tiles, at least as many rows as columns
+    if (m < n || m % nb != 0 || n % nb != 0 || n == 0) return SVB_ERR_UNSUPPORTED;
     if (!A_dev || !band_dev || !work_dev || lda < m || ldab < 3 * (int64_t)nb) return SVB_ERR_ARG;
-    if (!aligned_for_vectors(A_dev, lda) || reinterpret_cast<uintptr_t>(work_dev) % 256 != 0) return SVB_ERR_UNSUPPORTED;
-    const Carve cv = carve(dt, n, nb);
+    if (!aligned_for_vectors(A_dev, lda, dt) || reinterpret_cast<uintptr_t>(work_dev) % 256 != 0) return SVB_ERR_UNSUPPORTED;
+    const Shape sh = shape_of(m, n, nb);
+    const Carve cv = carve(dt, sh, nb);
     if (work_bytes < cv.total) return SVB_ERR_WORKSPACE;
-    return ge2gb_dispatch(dt, n, A_dev, lda, nb, band_dev, ldab, work_dev, cv, (hipStream_t)stream);
+    return ge2gb_dispatch(dt, m, n, A_dev, lda, nb, band_dev, ldab, work_dev, cv, switches(), (hipStream_t)stream);
+}
+
+static int gb2bd_checked(svb_dtype band_dt, int64_t n, int nb, void* band_dev, int64_t ldab, void* d_dev,
+                         void* e_dev, void* work_dev, size_t work_bytes, hipStream_t s)
+{
+    if (band_dt == SVB_F64)
+        return gb2bd_typed<double>(n, nb, (double*)band_dev, ldab, (double*)d_dev, (double*)e_dev, work_dev, work_bytes, s);
+    return gb2bd_typed<float>(n, nb, (float*)band_dev, ldab, (float*)d_dev, (float*)e_dev, work_dev, work_bytes, s);
 }
 
 int svb_gb2bd(svb_dtype band_dt, int64_t n, int nb, void* band_dev, int64_t ldab, void* d_dev,
@@ -592,27 +583,18 @@ int svb_gb2bd(svb_dtype band_dt, int64_t n, int nb, void* band_dev, int64_t ldab
 {
     if (n < 0) return SVB_ERR_ARG;
     if (band_dt != SVB_F64 && band_dt != SVB_F32) return SVB_ERR_UNSUPPORTED;
-    if (nb != 8 && nb != 32 && nb != 64 && nb != 128) return SVB_ERR_UNSUPPORTED;
+    if (nb != 8 && !nb_ok(nb)) return SVB_ERR_UNSUPPORTED;
     if (n == 0) return SVB_OK;
     if (!band_dev || !d_dev || !e_dev || ldab < 3 * (int64_t)nb) return SVB_ERR_ARG;
     if (work_bytes < gb2bd_bytes(n, nb)) return SVB_ERR_WORKSPACE;
     if (!work_dev) return SVB_ERR_ARG;
-    hipStream_t s = (hipStream_t)stream;
-    const double cs = band_dt == SVB_F64 ? 8.0 : 4.0;
-    prof_begin(SVB_PROF_CHASE, s, 6.0 * (double)n * (double)n * nb, 3.0 * (double)n * (double)n * nb * cs);
-    int rc;
-    if (band_dt == SVB_F64)
-        rc = gb2bd_typed<double>(n, nb, (double*)band_dev, ldab, (double*)d_dev, (double*)e_dev, work_dev, work_bytes, s);
-    else
-        rc = gb2bd_typed<float>(n, nb, (float*)band_dev, ldab, (float*)d_dev, (float*)e_dev, work_dev, work_bytes, s);
-    prof_end(s);
-    return rc;
+    return gb2bd_checked(band_dt, n, nb, band_dev, ldab, d_dev, e_dev, work_dev, work_bytes, (hipStream_t)stream);
 }
 
 int svb_gb2bd_workspace_bytes(int64_t n, int nb, size_t* dev_bytes)
 {
     if (n < 0 || !dev_bytes) return SVB_ERR_ARG;
-    if (nb != 8 && nb != 32 && nb != 64 && nb != 128) return SVB_ERR_UNSUPPORTED;
+    if (nb != 8 && !nb_ok(nb)) return SVB_ERR_UNSUPPORTED;
     *dev_bytes = gb2bd_bytes(n, nb);
     return SVB_OK;
 }
@@ -647,55 +629,76 @@ int svb_bdsvals(int64_t n, const double* d, const double* e, double* sigma)
 int svb_svdvals(svb_dtype dt, int64_t m, int64_t n, void* A_dev, int64_t lda, void* S_out_host, int nb,
                 void* work_dev, size_t work_bytes, void* stream)
 {
+    if (nb == 0 && m >= 0 && n >= 0 && dtype_ok(dt)) nb = choose_nb(dt, m, n);
     int rc = check_shape(dt, m, n, nb);
     if (rc != SVB_OK) return rc;
+    if (m == 0 || n == 0) return SVB_OK;   // no singular values
     if (!A_dev || !S_out_host || !work_dev || lda < m) return SVB_ERR_ARG;
-    if (!aligned_for_vectors(A_dev, lda) || reinterpret_cast<uintptr_t>(work_dev) % 256 != 0) return SVB_ERR_UNSUPPORTED;
-    const Carve cv = carve(dt, n, nb);
+    if (reinterpret_cast<uintptr_t>(work_dev) % 256 != 0) return SVB_ERR_UNSUPPORTED;
+    const Shape sh = shape_of(m, n, nb);
+    // in place only where the kernels' 16-byte accesses are aligned
+    if (!sh.staged && !aligned_for_vectors(A_dev, lda, dt)) return SVB_ERR_UNSUPPORTED;
+    const Carve cv = carve(dt, sh, nb);
     if (work_bytes < cv.total) return SVB_ERR_WORKSPACE;
+    const Switches& sw = switches();
+    if (!g_la.init(sw)) return SVB_ERR_DEVICE;
     hipStream_t s = (hipStream_t)stream;
     unsigned char* w = static_cast<unsigned char*>(work_dev);
     void* band = w + cv.off_band;
     void* dd = w + cv.off_d;
     void* de = w + cv.off_e;
+    double* factors = reinterpret_cast<double*>(w + cv.off_fac);
     const int64_t ldab = 3 * (int64_t)nb;
+    const int64_t k = sh.k;
     const svb_dtype bdt = dt == SVB_F64 ? SVB_F64 : SVB_F32;
+    const bool scaled = dt != SVB_F16 && !sw.no_scale;
 
-    hipEvent_t ev0, ev1, ev2;
-    if (hipEventCreate(&ev0) != hipSuccess || hipEventCreate(&ev1) != hipSuccess ||
-        hipEventCreate(&ev2) != hipSuccess)
-        return SVB_ERR_DEVICE;
-    (void)hipEventRecord(ev0, s);
-    rc = ge2gb_dispatch(dt, n, A_dev, lda, nb, band, ldab, work_dev, cv, s);
-    (void)hipEventRecord(ev1, s);
-    if (rc == SVB_OK) {
-        void* cw = w + cv.off_err + 256;
-        rc = svb_gb2bd(bdt, n, nb, band, ldab, dd, de, cw, gb2bd_bytes(n, nb), s);
+    hipEvent_t* ev = g_la.stage;
+    (void)hipEventRecord(ev[0], s);
+    // the matrix stage 1 works on: the caller's, or its zero-padded (transposed) copy
+    void* A1 = A_dev;
+    int64_t ld1 = lda;
+    if (sh.staged) {
+        A1 = w + cv.off_stage;
+        ld1 = sh.rows;
+        stage_copy_dispatch(dt, A_dev, lda, m, n, sh, A1, s);
     }
-    (void)hipEventRecord(ev2, s);
-    const bool host3 = [] { const char* v = std::getenv("SVB_STAGE3"); return v && std::strcmp(v, "host") == 0; }();
+    if (scaled) scale_dispatch(dt, A1, ld1, sh.rows, sh.cols, factors, s);
+    rc = ge2gb_dispatch(dt, sh.rows, sh.cols, A1, ld1, nb, band, ldab, work_dev, cv, sw, s);
+    (void)hipEventRecord(ev[1], s);
+    if (rc == SVB_OK) {
+        // columns min(m, n) .. of the padded band are zero: stage 2 runs on the leading part
+        rc = gb2bd_checked(bdt, k, nb, band, ldab, dd, de, w + cv.off_gb, gb2bd_bytes(k, nb), s);
+        if (rc == SVB_OK && scaled) {
+            if (bdt == SVB_F64) launch_rescale_bidiag<double>((double*)dd, (double*)de, k, factors, s);
+            else launch_rescale_bidiag<float>((float*)dd, (float*)de, k, factors, s);
+        }
+    }
+    (void)hipEventRecord(ev[2], s);
     const size_t cs = compute_size(dt);
     double total3 = 0.0;
-    hipEvent_t ev3 = nullptr;
-    std::vector<double> hs((size_t)n);
-    if (rc == SVB_OK && !host3) {
-        // stage 3 on the device, then one copy of n values
+    bool dev3 = false;
+    if (rc == SVB_OK && !sw.stage3_host) {
+        // stage 3 on the device, then one copy of k values
         void* sig = w + cv.off_sig;
         // The two reductions leave every singular value with an absolute error of the order of
         // eps * sigma_max, so the bidiagonal's small values are refined to tol times an eighth of
         // the bound on sigma_max (2^-3 eps sigma_max in f64, 2^-9 in f32), not to tol times
         // themselves, which costs them two to three times as many rounds.
         const double tol = dt == SVB_F64 ? 0x1p-52 : 0x1p-29;
-        const double floor_frac = env_int("SVB_STAGE3_RELATIVE", 0) ? 0.0 : 0.125;
+        const double floor_frac = sw.stage3_relative ? 0.0 : 0.125;
+        prof_begin(SVB_PROF_STAGE3, s, 0.0, 0.0);
         if (dt == SVB_F64)
-            rc = run_bdsvals_dev<double>(n, (const double*)dd, (const double*)de, (double*)sig, w + cv.off_s3, tol,
+            rc = run_bdsvals_dev<double>(k, (const double*)dd, (const double*)de, (double*)sig, w + cv.off_s3, tol,
                                          floor_frac, s);
         else
-            rc = run_bdsvals_dev<float>(n, (const float*)dd, (const float*)de, (float*)sig, w + cv.off_s3, tol,
+            rc = run_bdsvals_dev<float>(k, (const float*)dd, (const float*)de, (float*)sig, w + cv.off_s3, tol,
                                         floor_frac, s);
-        if (hipEventCreate(&ev3) == hipSuccess) (void)hipEventRecord(ev3, s);
+        prof_end(s);
+        (void)hipEventRecord(ev[3], s);
+        dev3 = true;
         if (rc == SVB_OK &&
-            (hipMemcpyAsync(S_out_host, sig, (size_t)n * cs, hipMemcpyDeviceToHost, s) != hipSuccess ||
+            (hipMemcpyAsync(S_out_host, sig, (size_t)k * cs, hipMemcpyDeviceToHost, s) != hipSuccess ||
              hipStreamSynchronize(s) != hipSuccess))
             rc = SVB_ERR_DEVICE;
         if (rc == SVB_OK) {
@@ -704,55 +707,61 @@ int svb_svdvals(svb_dtype dt, int64_t m, int64_t n, void* A_dev, int64_t lda, vo
             if (bad) rc = SVB_ERR_NONFINITE;
         }
     } else if (rc == SVB_OK) {
-        std::vector<double> hd((size_t)n), he((size_t)n);
-        std::vector<unsigned char> raw(2 * (size_t)n * cs);
-        if (hipMemcpyAsync(raw.data(), dd, (size_t)n * cs, hipMemcpyDeviceToHost, s) != hipSuccess ||
-            hipMemcpyAsync(raw.data() + (size_t)n * cs, de, (size_t)n * cs, hipMemcpyDeviceToHost, s) != hipSuccess ||
+        std::vector<double> hd((size_t)k), he((size_t)k), hs((size_t)k);
+        std::vector<unsigned char> raw(2 * (size_t)k * cs);
+        if (hipMemcpyAsync(raw.data(), dd, (size_t)k * cs, hipMemcpyDeviceToHost, s) != hipSuccess ||
+            hipMemcpyAsync(raw.data() + (size_t)k * cs, de, (size_t)k * cs, hipMemcpyDeviceToHost, s) != hipSuccess ||
             hipStreamSynchronize(s) != hipSuccess) {
             rc = SVB_ERR_DEVICE;
         } else if (dt == SVB_F64) {
-            std::memcpy(hd.data(), raw.data(), (size_t)n * 8);
-            std::memcpy(he.data(), raw.data() + (size_t)n * 8, (size_t)n * 8);
+            std::memcpy(hd.data(), raw.data(), (size_t)k * 8);
+            std::memcpy(he.data(), raw.data() + (size_t)k * 8, (size_t)k * 8);
         } else {
             const float* fd = reinterpret_cast<const float*>(raw.data());
-            for (int64_t i = 0; i < n; ++i) {
+            for (int64_t i = 0; i < k; ++i) {
                 hd[(size_t)i] = fd[i];
-                he[(size_t)i] = fd[n + i];
+                he[(size_t)i] = fd[k + i];
             }
         }
         const auto t3a = std::chrono::steady_clock::now();
-        if (rc == SVB_OK) rc = host_bdsvals(n, hd.data(), he.data(), hs.data());
+        if (rc == SVB_OK) rc = host_bdsvals(k, hd.data(), he.data(), hs.data());
         total3 = std::chrono::duration<double>(std::chrono::steady_clock::now() - t3a).count();
         if (rc == SVB_OK) {
-            if (dt == SVB_F64) std::memcpy(S_out_host, hs.data(), (size_t)n * 8);
+            if (dt == SVB_F64) std::memcpy(S_out_host, hs.data(), (size_t)k * 8);
             else
-                for (int64_t i = 0; i < n; ++i) static_cast<float*>(S_out_host)[i] = (float)hs[(size_t)i];
+                for (int64_t i = 0; i < k; ++i) static_cast<float*>(S_out_host)[i] = (float)hs[(size_t)i];
         }
     } else {
         (void)hipStreamSynchronize(s);
     }
-    float ms1 = 0, ms2 = 0;
-    (void)hipEventElapsedTime(&ms1, ev0, ev1);
-    (void)hipEventElapsedTime(&ms2, ev1, ev2);
-    if (ev3) {
-        float ms3 = 0;
-        if (hipEventElapsedTime(&ms3, ev2, ev3) == hipSuccess) total3 = ms3 * 1e-3;
-        (void)hipEventDestroy(ev3);
-    }
-    (void)hipEventDestroy(ev0);
-    (void)hipEventDestroy(ev1);
-    (void)hipEventDestroy(ev2);
+    float ms1 = 0, ms2 = 0, ms3 = 0;
+    (void)hipEventElapsedTime(&ms1, ev[0], ev[1]);
+    (void)hipEventElapsedTime(&ms2, ev[1], ev[2]);
+    if (dev3 && hipEventElapsedTime(&ms3, ev[2], ev[3]) == hipSuccess) total3 = ms3 * 1e-3;
     if (rc == SVB_OK && hipGetLastError() != hipSuccess) rc = SVB_ERR_DEVICE;
-    if (g_prof.on) g_prof.collect();
     g_last.s1 = ms1 * 1e-3;
     g_last.s2 = ms2 * 1e-3;
     g_last.s3 = total3;
+    g_last.upd = -1.0;
+    if (g_prof.on) {
+        const double before = g_prof.sec[SVB_PROF_UPDATE] + g_prof.sec[SVB_PROF_UPDATE_UPPER];
+        g_prof.collect();
+        g_last.upd = g_prof.sec[SVB_PROF_UPDATE] + g_prof.sec[SVB_PROF_UPDATE_UPPER] - before;
+    }
     return rc;
 }
 
-int svb_last_timings(double* t_stage1, double* t_stage2, double* t_stage3)
+int svb_last_timings(double* t_panel, double* t_update, double* t_stage2, double* t_stage3)
 {
-    if (t_stage1) *t_stage1 = g_last.s1;
+    // stage 1's wall time, split into the part covered by update kernels and the rest (panel
+    // factorisations that no update hides); the split needs the per-kernel events
+    double upd = g_last.s1, pan = -1.0;
+    if (g_last.upd >= 0.0) {
+        upd = g_last.upd < g_last.s1 ? g_last.upd : g_last.s1;
+        pan = g_last.s1 - upd;
+    }
+    if (t_panel) *t_panel = pan;
+    if (t_update) *t_update = upd;
     if (t_stage2) *t_stage2 = g_last.s2;
     if (t_stage3) *t_stage3 = g_last.s3;
     return SVB_OK;
@@ -786,11 +795,11 @@ const char* svb_status_string(int status)
     switch (status) {
     case SVB_OK: return "ok";
     case SVB_ERR_ARG: return "invalid argument";
-    case SVB_ERR_UNSUPPORTED: return "unsupported shape, tile size or dtype";
+    case SVB_ERR_UNSUPPORTED: return "unsupported shape, tile size, alignment or dtype";
     case SVB_ERR_WORKSPACE: return "workspace too small";
     case SVB_ERR_DEVICE: return "HIP error";
     case SVB_ERR_NOCONV: return "bidiagonal solver did not converge";
-    case SVB_ERR_NONFINITE: return "non-finite value in the bidiagonal";
+    case SVB_ERR_NONFINITE: return "non-finite value in the input or the bidiagonal";
     default: return "unknown status";
     }
 }

@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
+#include <hip/hip_bf16.h>
 #include <stdint.h>
 #include <stddef.h>
 
@@ -13,15 +14,19 @@ namespace svb {
 
 constexpr int kWave = 64;
 
-// Storage <-> compute conversions.  f16 is a storage type only: products and
-// sums are formed in f32 (the paper's treatment of half precision, Section 4.3).
+// Storage <-> compute conversions.  f16 and bf16 are storage types only: products
+// and sums are formed in f32 (the paper's treatment of half precision, Section 4.3).
+typedef __hip_bfloat16 bf16_t;
 template <typename T> struct compute_of { using type = T; };
 template <> struct compute_of<__half> { using type = float; };
+template <> struct compute_of<bf16_t> { using type = float; };
 
 template <typename C, typename T> __device__ __forceinline__ C ld_as(const T* p) { return (C)(*p); }
 template <> __device__ __forceinline__ float ld_as<float, __half>(const __half* p) { return __half2float(*p); }
 template <typename T, typename C> __device__ __forceinline__ void st_as(T* p, C v) { *p = (T)v; }
 template <> __device__ __forceinline__ void st_as<__half, float>(__half* p, float v) { *p = __float2half(v); }
+template <> __device__ __forceinline__ float ld_as<float, bf16_t>(const bf16_t* p) { return __bfloat162float(*p); }
+template <> __device__ __forceinline__ void st_as<bf16_t, float>(bf16_t* p, float v) { *p = __float2bfloat16(v); }
 
 // Reciprocal and square root for reflector scalars: the hardware approximations (1 ulp,
 // biased) refined by Newton steps.  A biased tau or scale would make every reflector
@@ -61,7 +66,6 @@ struct Level {
     int64_t stride;    // distance in panel rows between consecutive chunks: nb * g^level
     int64_t poff;      // element offset of this level's panel inside the panel buffers
     int64_t ldp;       // leading dimension of this level's panel = chunks * nb
-    int64_t woff;      // element offset of this level's W inside the W buffer
 };
 constexpr int kMaxLevels = 12;
 
@@ -104,24 +108,16 @@ template <typename C>
 void launch_band_clear(C* band, int64_t ldab, int64_t n, hipStream_t s);
 
 // ---- stage 1, trailing update ----------------------------------------------
-// W_d = Y_d^T C_d for every domain d of a level, then C_d -= V_d W_d
-// (QR orientation; the LQ orientation is the same with p/q swapped).
-template <typename T, typename C>
-void launch_update(int nb, bool lq, T* Cbase, int64_t lda, int64_t qlen,
-                   const C* V, const C* Y, int64_t ldp, int chunks, int g, int64_t stride,
-                   C* W, int impl, bool credited, int phase, hipStream_t s);
-
-// The same update in one pass over the trailing matrix (W stays in registers); domains of
-// at most fused_update_rows<C>() rows.  tri: the panel is a stack of upper triangular factors
-// (tree levels above the first), whose structural zeros in V and Y are skipped.
-// mode 0: the whole update; 1: W formed and stored in W, first chunk of every domain finished;
-// 2: the other chunks finished from the stored W (may run beside the next panel).
-// Tw: the domains' triangular factors (NB x NB each, column-major); if given (mode 0, nb <= 64
-// only), Y is not read and W = T^T (V^T C) is formed inside the kernel.
+// For every domain d of a tree level: W_d = Y_d^T C_d, then C_d -= V_d W_d (QR orientation; the
+// LQ orientation is the same with p/q swapped), in one pass over the trailing matrix (W stays in
+// registers); domains of at most fused_update_rows<C>() rows.  tri: the panel is a stack of upper
+// triangular factors (tree levels above the first), whose structural zeros in V and Y are skipped.
+// Tw: the domains' triangular factors (NB x NB each, column-major); if given (nb <= 64 only), Y is
+// not read and W = T^T (V^T C) is formed inside the kernel.
 template <typename T, typename C>
 void launch_update_fused(int nb, bool lq, T* Cbase, int64_t lda, int64_t qlen, const C* V, const C* Y,
-                         int64_t ldp, int chunks, int g, int64_t stride, bool tri, int mode, C* W,
-                         const C* Tw, bool credited, hipStream_t s);
+                         int64_t ldp, int chunks, int g, int64_t stride, bool tri, const C* Tw,
+                         bool credited, hipStream_t s);
 template <typename C> int fused_update_rows();
 
 // per-kernel timing hooks (no-ops unless profiling is enabled)
@@ -131,6 +127,22 @@ void prof_end(hipStream_t s);
 // to the kernel itself (hipExtLaunchKernelGGL's start and stop events: the kernel's own time
 // stamps, no marker in the stream before or after it) and returns true.
 bool prof_take(int kind, double flops, double bytes, hipEvent_t* start, hipEvent_t* stop);
+
+// ---- preparation: staging copy, magnitude scan, scaling ------------------------
+// factors (device, doubles): [0] = power of two the matrix is multiplied by before stage 1,
+// [1] = its reciprocal (applied to the bidiagonal), [2] = largest magnitude found.
+// S (mp x np, leading dimension lds, zero padded) = A (m x n) or, with transpose, A^T.
+template <typename T>
+void launch_stage_copy(const T* A, int64_t lda, int64_t m, int64_t n, bool transpose, T* S, int64_t lds,
+                       int64_t mp, int64_t np, hipStream_t s);
+// largest magnitude of the m x n matrix -> factors (NaN if an entry is not finite); then the
+// matrix is multiplied by factors[0] where that is not 1
+template <typename T>
+void launch_scale_to_range(T* A, int64_t lda, int64_t m, int64_t n, double* factors, hipStream_t s);
+size_t scale_workspace_bytes();   // bytes behind `factors` (the factors and the scan's partial maxima)
+// d, e (n entries each) multiplied by factors[1]
+template <typename C>
+void launch_rescale_bidiag(C* d, C* e, int64_t n, const double* factors, hipStream_t s);
 
 // ---- stage 2 -----------------------------------------------------------------
 template <typename C>

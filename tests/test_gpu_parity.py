@@ -78,13 +78,12 @@ def test_small_tree_parameters(monkeypatch):
     _check(_gpu_sigma(a, 32), ref, 288, "f64")
 
 
-@pytest.mark.parametrize("panel,update", [("1", "2"), ("0", "2"), ("2", "1"), ("2", "0"), ("1", "1")])
+@pytest.mark.parametrize("panel", ["1", "0"])
 @pytest.mark.parametrize("name,n,nb", [("c4", 640, 64), ("c5b", 768, 128), ("c3b", 512, 32)])
-def test_stage1_alternative_kernels(monkeypatch, panel, update, name, n, nb):
-    # stage-1 kernels kept beside the defaults: reflector-at-a-time register panel (1) and plain
-    # panel (0); two-kernel MFMA update with look-ahead (1) and plain FMA update (0)
+def test_stage1_alternative_panel_kernels(monkeypatch, panel, name, n, nb):
+    # panel kernels kept beside the default: reflector-at-a-time register panel (1) and plain panel (0),
+    # both through a gathered copy of the panel, the Y = V T kernel and the R scatter
     monkeypatch.setenv("SVB_PANEL_IMPL", panel)
-    monkeypatch.setenv("SVB_UPDATE_IMPL", update)
     a, info = workloads.make(name, n=n, nb=nb)
     fro = 2e-2 if info["dtype"] == "f16" else None
     _check(_gpu_sigma(a, nb), oracle.svdvals(a), n, info["dtype"], fro)
@@ -101,15 +100,13 @@ def _variant_case(name, n, nb):
     return _VARIANT_CASES[(name, n, nb)]
 
 
-@pytest.mark.parametrize("env", [{"SVB_PIPELINE": "0"}, {"SVB_PIPELINE": "0", "SVB_LOOKAHEAD_MIN_TILES": "1"},
-                                 {"SVB_PIPELINE_LAYOUT": "0"}, {"SVB_UPDATE_T": "0"}, {"SVB_EXT_EVENTS": "0"},
-                                 {"SVB_EVENT_FENCE": "1"}, {"PROFILE": "1"}])
+@pytest.mark.parametrize("env", [{"SVB_PIPELINE_LAYOUT": "0"}, {"SVB_UPDATE_T": "0"}, {"SVB_EXT_EVENTS": "0"},
+                                 {"PROFILE": "1"}])
 @pytest.mark.parametrize("name,n,nb", [("c4", 1152, 64), ("c5b", 768, 128), ("c3b", 1024, 32)])
 def test_stage1_driver_variants(monkeypatch, env, name, n, nb):
-    # the stage-1 drivers kept beside the default level pipeline (sequential driver with and without
-    # the split update, every update on the side stream, Y = V T instead of T in the update, level
-    # events recorded behind the kernels, system-scope events), and the default with the library's
-    # per-kernel events on: same singular values
+    # variants of the level pipeline kept beside the default (every update on the side stream,
+    # Y = V T instead of T in the update, level events recorded behind the kernels), and the default
+    # with the library's per-kernel events on: same singular values
     for k, v in env.items():
         if k != "PROFILE":
             monkeypatch.setenv(k, v)
@@ -120,7 +117,7 @@ def test_stage1_driver_variants(monkeypatch, env, name, n, nb):
     try:
         s = _gpu_sigma(a, nb)
         if "PROFILE" in env:
-            assert svb.svb_profile_get(svb.SVB_PROF_FUSED)["launches"] > 0
+            assert svb.svb_profile_get(svb.SVB_PROF_UPDATE)["launches"] > 0
     finally:
         svb.svb_profile_enable(False)
     _check(s, ref, n, info["dtype"], fro)
@@ -204,9 +201,9 @@ def test_stage2_on_random_band(dtype, n, nb):
     assert np.abs(s - ref).max() <= 10 * n * eps * ref[0]
 
 
-@pytest.mark.parametrize("name", ["c3a", "c3b", "c4", "c5b"])
+@pytest.mark.parametrize("name", ["c3a", "c3b", "c4", "c5b", "c5a"])
 def test_full_size_configs_against_stored_oracle(name):
-    """Configs 3a/3b/4/5b at full size against the oracle's stored singular values
+    """Configs 3a/3b/4/5b/5a at full size against the oracle's stored singular values
     (tests/golden, written by make_oracle_sigma.py from the same generator)."""
     stored = golden.load(name)
     if stored is None:
@@ -249,20 +246,22 @@ def test_config_5a_size_properties():
 
 
 def test_stage2_expired_wait_is_reported(monkeypatch):
-    # a spin limit of zero makes every pipelined wait expire at once: all kernels still
-    # exit normally and the failure surfaces as a status code
+    # a spin limit of zero makes every pipelined wait that is not met at once expire: all kernels
+    # still exit normally and the failure surfaces as a status code.  With 127 block sweeps started
+    # together, the second one asks for its predecessor's second step long before that is done.
     monkeypatch.setenv("SVB_CHASE_SPIN", "0")
-    a, info = workloads.make("c1", n=256, nb=32)
+    n, nb = 1024, 32
+    a, info = workloads.make("c1", n=n, nb=nb)
     t = _dev(a)
-    rc, wbytes, _ = svb.svb_workspace_bytes(svb.SVB_F64, 256, 256, 32)
+    rc, wbytes, _ = svb.svb_workspace_bytes(svb.SVB_F64, n, n, nb)
     work = torch.empty(wbytes, dtype=torch.uint8, device="cuda")
-    out = np.zeros(256)
-    rc = svb.svb_svdvals(svb.SVB_F64, 256, 256, t, 256, out, 32, work, wbytes)
+    out = np.zeros(n)
+    rc = svb.svb_svdvals(svb.SVB_F64, n, n, t, n, out, nb, work, wbytes)
     torch.cuda.synchronize()
-    assert rc in (0, 6)   # 0 only if no sweep ever had to wait
+    assert rc == 6
     monkeypatch.delenv("SVB_CHASE_SPIN")
-    s = _gpu_sigma(a, 32)
-    _check(s, oracle.svdvals(a), 256, "f64")
+    s = _gpu_sigma(a, nb)
+    _check(s, oracle.svdvals(a), n, "f64")
 
 
 @pytest.mark.parametrize("n,nb", [(256, 32), (512, 64)])
@@ -341,3 +340,113 @@ def test_host_stage3_variant(monkeypatch):
     monkeypatch.setenv("SVB_STAGE3", "host")
     a, info = workloads.make("c2", n=256, nb=32)
     _check(_gpu_sigma(a, 32), oracle.svdvals(a), 256, "f32")
+
+
+# ---- general shapes, leading dimensions, storage types, magnitudes ------------------------------
+
+def _svdvals_general(a, nb, lda_pad=0, dtype=None):
+    """svb_svdvals on the m x n column-major numpy matrix a through the C ABI, with lda = m + lda_pad."""
+    m, n = a.shape
+    tdt = dtype or {np.float64: torch.float64, np.float32: torch.float32, np.float16: torch.float16}[a.dtype.type]
+    lda = m + lda_pad
+    buf = torch.zeros((n, lda), dtype=tdt, device="cuda")       # row j of the tensor = column j of the matrix
+    buf[:, :m] = torch.from_numpy(np.ascontiguousarray(a.T)).to(tdt)
+    code = svb.dtype_code(tdt)
+    rc, wbytes, _ = svb.svb_workspace_bytes(code, m, n, nb)
+    assert rc == 0
+    work = torch.empty(wbytes, dtype=torch.uint8, device="cuda")
+    out = np.zeros(min(m, n), dtype=np.float64 if code == svb.SVB_F64 else np.float32)
+    print(f"[case] general m={m} n={n} nb={nb} lda={lda} {tdt}", flush=True)
+    rc = svb.svb_svdvals(code, m, n, buf, lda, out, nb, work, wbytes)
+    torch.cuda.synchronize()
+    return rc, out.astype(np.float64), buf
+
+
+@pytest.mark.parametrize("dtype,m,n,nb", [
+    ("f64", 300, 300, 32),      # n not a multiple of nb
+    ("f32", 1000, 1000, 64),
+    ("f32", 777, 777, 128),
+    ("f64", 640, 256, 32),      # m > n, whole tiles: in place
+    ("f32", 2048, 512, 64),
+    ("f64", 1500, 200, 64),     # m > n, ragged
+    ("f32", 1025, 1023, 32),
+    ("f64", 200, 900, 32),      # m < n: transposed problem
+    ("f32", 512, 2048, 128),
+    ("f64", 1, 1, 32), ("f64", 5, 3, 32), ("f32", 33, 65, 32), ("f64", 100, 1, 32),
+    ("f32", 2000, 1200, 0),     # nb chosen by the library
+])
+def test_general_shapes_match_oracle(dtype, m, n, nb):
+    npdt = workloads.NP_DTYPE[dtype]
+    g = workloads.gaussian_matrix(4000 + m + 7 * n, m, n).astype(npdt)
+    a = np.asfortranarray(g)
+    rc, s, _ = _svdvals_general(a, nb)
+    assert rc == 0, svb.svb_status_string(rc)
+    a64 = a.astype(np.float64)
+    ref = oracle.svdvals(a64 if m >= n else np.asfortranarray(a64.T))
+    assert s.shape == ref.shape
+    _check(s, ref, max(m, n), dtype)
+
+
+def test_in_place_only_when_tiles_are_whole():
+    # whole tiles and m >= n: the matrix is the work area (destroyed); otherwise it is only read
+    a = np.asfortranarray(workloads.gaussian_matrix(11, 256, 128))
+    rc, s, buf = _svdvals_general(a, 32)
+    assert rc == 0 and not np.array_equal(buf[:, :256].cpu().numpy().T, a)
+    b = np.asfortranarray(workloads.gaussian_matrix(12, 250, 130))
+    rc, s, buf = _svdvals_general(b, 32)
+    assert rc == 0 and np.array_equal(buf[:, :250].cpu().numpy().T, b)
+
+
+@pytest.mark.parametrize("dtype,n,nb,pad", [("f32", 512, 64, 8), ("f64", 384, 32, 2), ("f32", 500, 32, 3)])
+def test_padded_leading_dimension(dtype, n, nb, pad):
+    # lda > m; the last case (odd lda, ragged n) goes through the staged copy, which has no alignment needs
+    a = np.asfortranarray(workloads.gaussian_matrix(600 + n, n, n).astype(workloads.NP_DTYPE[dtype]))
+    rc, s, _ = _svdvals_general(a, nb, lda_pad=pad)
+    assert rc == 0
+    _check(s, oracle.svdvals(a.astype(np.float64)), n, dtype)
+
+
+def test_misaligned_in_place_input_is_refused():
+    n, nb = 128, 32
+    a = np.asfortranarray(workloads.gaussian_matrix(13, n, n).astype(np.float32))
+    rc, s, _ = _svdvals_general(a, nb, lda_pad=1)      # lda = 129: 16-byte vectors would straddle
+    assert rc == 2
+
+
+def test_bf16_storage():
+    # bf16 storage, f32 arithmetic (8 significant bits: eps = 2^-8 in the tolerance formula)
+    n, nb = 512, 64
+    a32, info = workloads.make("c3b", n=n, nb=nb)
+    t = torch.from_numpy(np.ascontiguousarray(a32.astype(np.float32).T)).to(torch.bfloat16)
+    a = np.asfortranarray(t.to(torch.float64).numpy().T)          # the rounded matrix, as the library sees it
+    rc, s, _ = _svdvals_general(a, nb, dtype=torch.bfloat16)
+    assert rc == 0
+    ref = oracle.svdvals(a)
+    assert np.abs(s - ref).max() <= 10 * n * 2.0 ** -8 * ref[0]
+    assert np.linalg.norm(s - ref) / np.linalg.norm(ref) <= 5e-2
+
+
+@pytest.mark.parametrize("dtype,expo", [("f32", 60), ("f32", -60), ("f32", 100), ("f64", 500), ("f64", -500),
+                                         ("f32", 0)])
+def test_badly_scaled_input(dtype, expo):
+    # entries around 2^expo: sums of squares would leave the arithmetic type's range without the
+    # power-of-two scaling in front of stage 1; the result scales exactly with the input
+    n, nb = 256, 32
+    npdt = workloads.NP_DTYPE[dtype]
+    base = np.asfortranarray(workloads.gaussian_matrix(77, n, n).astype(npdt))
+    a = np.ldexp(base, expo).astype(npdt)
+    rc, s, _ = _svdvals_general(a, nb)
+    assert rc == 0, svb.svb_status_string(rc)
+    ref = oracle.svdvals(base.astype(np.float64))
+    _check(np.ldexp(s, -expo), ref, n, dtype)
+
+
+def test_nonfinite_input_is_reported():
+    n, nb = 128, 32
+    a = np.asfortranarray(workloads.gaussian_matrix(14, n, n))
+    a[5, 7] = np.nan
+    rc, s, _ = _svdvals_general(a, nb)
+    assert rc == 6
+    a[5, 7] = np.inf
+    rc, s, _ = _svdvals_general(a, nb)
+    assert rc == 6

@@ -39,20 +39,46 @@ def test_product_path_does_not_reach_the_oracle():
 def test_argument_validation():
     ok, dev, host = svb.svb_workspace_bytes(svb.SVB_F32, 1024, 1024, 32)
     assert ok == 0 and dev > 0 and host == 0
-    assert svb.svb_workspace_bytes(svb.SVB_F32, 1000, 1000, 32)[0] == 2      # n % nb
-    assert svb.svb_workspace_bytes(svb.SVB_F32, 1024, 512, 32)[0] == 2       # m != n
+    # general shapes are accepted (and add room for the padded copy); nb = 0 picks a tile size
+    ok2, dev2, _ = svb.svb_workspace_bytes(svb.SVB_F32, 1000, 1000, 32)
+    assert ok2 == 0 and dev2 >= dev + 3 * 1024 * 1024
+    assert svb.svb_workspace_bytes(svb.SVB_F32, 1024, 512, 32)[0] == 0
+    assert svb.svb_workspace_bytes(svb.SVB_F32, 512, 1024, 32)[0] == 0
+    assert svb.svb_workspace_bytes(svb.SVB_BF16, 1024, 1024, 32)[0] == 0
+    assert svb.svb_workspace_bytes(svb.SVB_F32, 1024, 1024, 0)[0] == 0
+    assert svb.svb_workspace_bytes(svb.SVB_F32, 0, 7, 32)[0] == 0
     assert svb.svb_workspace_bytes(svb.SVB_F32, 1024, 1024, 48)[0] == 2      # nb
-    assert svb.svb_workspace_bytes(svb.SVB_BF16, 1024, 1024, 32)[0] == 2     # dtype
+    assert svb.svb_workspace_bytes(7, 1024, 1024, 32)[0] == 2                # dtype
     assert svb.svb_workspace_bytes(svb.SVB_F64, -1, -1, 32)[0] == 1
     out = np.zeros(64, dtype=np.float32)
     # null device pointers are rejected before anything is launched
     assert svb.svb_svdvals(svb.SVB_F32, 64, 64, None, 64, out, 32, None, 0, stream=0) == 1
+    assert svb.svb_svdvals(svb.SVB_F32, 0, 64, None, 64, out, 32, None, 0, stream=0) == 0   # nothing to do
     assert svb.svb_ge2gb(svb.SVB_F32, 64, 64, None, 64, 32, None, 96, None, 0, stream=0) == 1
+    assert svb.svb_ge2gb(svb.SVB_F32, 60, 64, None, 64, 32, None, 96, None, 0, stream=0) == 2   # in place: whole tiles only
     assert svb.svb_gb2bd(svb.SVB_F16, 64, 32, None, 96, None, None, None, 0, stream=0) == 2
     assert svb.svb_gb2bd(svb.SVB_F32, 64, 32, None, 96, None, None, None, 0, stream=0) == 1
     rc, wb = svb.svb_gb2bd_workspace_bytes(1000, 64)
     assert rc == 0 and wb >= 4 * 1000
     assert "workspace" in svb.svb_status_string(3)
+
+
+def test_workspace_is_a_fraction_of_the_matrix():
+    # in-place problems need panels, factors, the band and counters only: a few per cent of the matrix
+    for dt, n, nb, size in [(svb.SVB_F32, 32768, 128, 4), (svb.SVB_F64, 16384, 128, 8), (svb.SVB_F32, 8192, 64, 4)]:
+        rc, dev, _ = svb.svb_workspace_bytes(dt, n, n, nb)
+        assert rc == 0
+        assert dev <= 0.1 * n * n * size, (n, dev)
+    rc, dev, _ = svb.svb_workspace_bytes(svb.SVB_F32, 32768, 32768, 128)
+    assert dev <= 1 << 30
+
+
+def test_tile_size_choice():
+    assert svb.svb_choose_nb(svb.SVB_F32, 256, 256) == 32
+    assert svb.svb_choose_nb(svb.SVB_F32, 8192, 8192) == 64
+    assert svb.svb_choose_nb(svb.SVB_F64, 32768, 40000) == 128
+    assert svb.svb_choose_nb(svb.SVB_F32, 100000, 500) == 32     # the smaller dimension decides
+    assert svb.svb_choose_nb(svb.SVB_F32, -1, 5) == 0
 
 
 @pytest.mark.parametrize("n", [1, 2, 5, 16, 17, 100, 1000])

@@ -86,14 +86,39 @@ def normal(seed: int, start: int, count: int) -> np.ndarray:
     return z[off:off + count]
 
 
+def _pool_size(work_items: int) -> int:
+    """Threads for the block-parallel loops below (numpy releases the interpreter lock
+    inside its array kernels): one for small matrices, up to 16 for large ones."""
+    import os
+    if work_items < (1 << 24):
+        return 1
+    return max(1, min(16, os.cpu_count() or 1))
+
+
 def gaussian_matrix(seed: int, m: int, n: int, scale: float = 1.0,
                     out_dtype=np.float64, col_block: int = 512) -> np.ndarray:
-    """m x n matrix, column-major (Fortran order), entry (i,j) = scale * z[i + j*m]."""
+    """m x n matrix, column-major (Fortran order), entry (i,j) = scale * z[i + j*m].
+
+    Every entry depends on (seed, i + j*m) only, so the column blocks are produced
+    independently (by a few threads for large matrices) with identical results."""
     a = np.empty((m, n), dtype=out_dtype, order="F")
-    for j0 in range(0, n, col_block):
+    nthr = _pool_size(m * n)
+    if nthr > 1:
+        col_block = max(1, min(col_block, (1 << 22) // max(m, 1)))   # bounds the temporaries per thread
+
+    def fill(j0):
         j1 = min(n, j0 + col_block)
         z = normal(seed, j0 * m, (j1 - j0) * m)
         a[:, j0:j1] = (scale * z).reshape((m, j1 - j0), order="F").astype(out_dtype)
+
+    starts = range(0, n, col_block)
+    if nthr == 1:
+        for j0 in starts:
+            fill(j0)
+    else:
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(nthr) as ex:
+            list(ex.map(fill, starts))
     return a
 
 
@@ -182,12 +207,19 @@ def fingerprint(a: np.ndarray) -> dict:
     rs = np.random.RandomState(12345)
     ii = rs.randint(0, n0, size=16)
     jj = rs.randint(0, n1, size=16)
-    s = 0.0
-    s2 = 0.0
-    for j0 in range(0, n1, 1024):
+    def part(j0):
         blk = a[:, j0:j0 + 1024].astype(np.float64)
-        s += float(blk.sum())
-        s2 += float((blk * blk).sum())
+        return float(blk.sum()), float((blk * blk).sum())
+
+    nthr = _pool_size(n0 * n1)
+    if nthr == 1:
+        parts = [part(j0) for j0 in range(0, n1, 1024)]
+    else:
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(nthr) as ex:
+            parts = list(ex.map(part, range(0, n1, 1024)))
+    s = float(sum(p[0] for p in parts))
+    s2 = float(sum(p[1] for p in parts))
     return dict(shape=[int(n0), int(n1)], sum=s, sumsq=s2,
                 samples=[float(a[i, j]) for i, j in zip(ii, jj)])
 
