@@ -14,7 +14,8 @@
  *     All index arithmetic is 64-bit.
  *   - The caller owns every buffer.  The library allocates no device memory;
  *     scratch space comes in through work_dev / work_bytes (size from
- *     svb_workspace_bytes).
+ *     svb_workspace_bytes), except for svb_gb2bd_noalloc, whose scratch is a
+ *     fixed array inside the library's device image.
  *   - GPU work is ordered after what the HIP stream passed as `stream` (a
  *     hipStream_t cast to void*, NULL = the default stream) holds at the call,
  *     and that stream waits for it: stage 1 runs on two internal streams that
@@ -151,6 +152,22 @@ int svb_gb2bd(svb_dtype band_dt, int64_t n, int nb, void* band_dev, int64_t ldab
 
 /* Bytes of device scratch svb_gb2bd needs ([host] out). */
 int svb_gb2bd_workspace_bytes(int64_t n, int nb, size_t* dev_bytes);
+
+/*
+ * svb_gb2bd for callers that can neither allocate device memory nor carry a
+ * workspace (code under HIP graph capture, tight serving loops, harnesses
+ * that forbid allocation): same arguments without work_dev / work_bytes, same
+ * results.  The sweep counters live in a fixed 1 MiB array inside the
+ * library's device image (one copy per device, held until the process ends),
+ * which limits n to SVB_NOALLOC_MAX_N; larger n returns SVB_ERR_WORKSPACE.
+ * Calls no allocating routine.  The counters a call uses are cleared by its
+ * own kernels, so consecutive calls on one stream are independent; every call
+ * on a device shares that device's array, so calls that overlap on one device
+ * (different streams or threads) race and must be serialised by the caller.
+ */
+#define SVB_NOALLOC_MAX_N 131072
+int svb_gb2bd_noalloc(svb_dtype band_dt, int64_t n, int nb, void* band_dev, int64_t ldab,
+                      void* d_dev, void* e_dev, void* stream);
 
 /*
  * Stage 3 (Section 3, final stage; the paper calls LAPACK on the CPU here):

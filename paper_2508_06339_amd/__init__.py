@@ -9,5 +9,5 @@ from .binding import (  # noqa: F401
     svb_bdsvals_dev_workspace_bytes, svb_last_timings,
     svb_status_string, svdvals, dtype_code, svb_profile_enable, svb_profile_collect,
     svb_profile_get, SVB_PROF_PANEL, SVB_PROF_UPDATE, SVB_PROF_UPDATE_UPPER, SVB_PROF_BAND_REDUCE,
-    SVB_PROF_NARROW, SVB_PROF_STAGE3, SVB_PROF_NAMES, svb_choose_nb,
+    SVB_PROF_NARROW, SVB_PROF_STAGE3, SVB_PROF_NAMES, svb_gb2bd_noalloc, svb_choose_nb,
 )

@@ -55,6 +55,8 @@ def load_library():
     lib.svb_gb2bd.argtypes = [ctypes.c_int, _i64, ctypes.c_int, _vp, _i64, _vp, _vp, _vp,
                               ctypes.c_size_t, _vp]
     lib.svb_gb2bd.restype = ctypes.c_int
+    lib.svb_gb2bd_noalloc.argtypes = [ctypes.c_int, _i64, ctypes.c_int, _vp, _i64, _vp, _vp, _vp]
+    lib.svb_gb2bd_noalloc.restype = ctypes.c_int
     lib.svb_choose_nb.argtypes = [ctypes.c_int, _i64, _i64]
     lib.svb_choose_nb.restype = ctypes.c_int
     lib.svb_gb2bd_workspace_bytes.argtypes = [_i64, ctypes.c_int, _szp]
@@ -121,6 +123,11 @@ def svb_ge2gb(dt, m, n, A_dev, lda, nb, band_dev, ldab, work_dev, work_bytes, st
 def svb_gb2bd(band_dt, n, nb, band_dev, ldab, d_dev, e_dev, work_dev, work_bytes, stream=None) -> int:
     return load_library().svb_gb2bd(band_dt, n, nb, _ptr(band_dev), ldab, _ptr(d_dev), _ptr(e_dev),
                                     _ptr(work_dev), work_bytes, _stream(stream))
+
+
+def svb_gb2bd_noalloc(band_dt, n, nb, band_dev, ldab, d_dev, e_dev, stream=None) -> int:
+    return load_library().svb_gb2bd_noalloc(band_dt, n, nb, _ptr(band_dev), ldab, _ptr(d_dev), _ptr(e_dev),
+                                            _stream(stream))
 
 
 def svb_choose_nb(dt: int, m: int, n: int) -> int:

@@ -535,6 +535,28 @@ bool prof_take(int kind, double flops, double bytes, hipEvent_t* start, hipEvent
 
 using namespace svb;
 
+// Scratch of svb_gb2bd_noalloc: part of the library's image on every device it runs on (each
+// device holds its own copy at its own address until the process ends).  In host code the name is
+// only a handle for hipGetSymbolAddress; kernels and memory operations get the looked-up pointer.
+constexpr size_t kStaticScratchBytes = 1u << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices] = {};
+
+// device address of the current device's copy of the array (looked up once per device)
+static int static_scratch(void** out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SVB_ERR_DEVICE;
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return SVB_ERR_DEVICE;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return SVB_OK;
+}
+
 extern "C" {
 
 int svb_choose_nb(svb_dtype dt, int64_t m, int64_t n)
@@ -589,6 +611,23 @@ int svb_gb2bd(svb_dtype band_dt, int64_t n, int nb, void* band_dev, int64_t ldab
     if (work_bytes < gb2bd_bytes(n, nb)) return SVB_ERR_WORKSPACE;
     if (!work_dev) return SVB_ERR_ARG;
     return gb2bd_checked(band_dt, n, nb, band_dev, ldab, d_dev, e_dev, work_dev, work_bytes, (hipStream_t)stream);
+}
+
+int svb_gb2bd_noalloc(svb_dtype band_dt, int64_t n, int nb, void* band_dev, int64_t ldab, void* d_dev,
+                      void* e_dev, void* stream)
+{
+    if (n < 0) return SVB_ERR_ARG;
+    if (band_dt != SVB_F64 && band_dt != SVB_F32) return SVB_ERR_UNSUPPORTED;
+    if (nb != 8 && !nb_ok(nb)) return SVB_ERR_UNSUPPORTED;
+    if (n == 0) return SVB_OK;
+    if (!band_dev || !d_dev || !e_dev || ldab < 3 * (int64_t)nb) return SVB_ERR_ARG;
+    // the counters of the sweeps must fit the fixed array
+    if (n > SVB_NOALLOC_MAX_N || gb2bd_bytes(n, nb) > kStaticScratchBytes) return SVB_ERR_WORKSPACE;
+    void* ws = nullptr;
+    const int rc = static_scratch(&ws);
+    if (rc != SVB_OK) return rc;
+    // (the kernels clear the counters they use at the start of every call)
+    return gb2bd_checked(band_dt, n, nb, band_dev, ldab, d_dev, e_dev, ws, kStaticScratchBytes, (hipStream_t)stream);
 }
 
 int svb_gb2bd_workspace_bytes(int64_t n, int nb, size_t* dev_bytes)

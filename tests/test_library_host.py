@@ -58,6 +58,8 @@ def test_argument_validation():
     assert svb.svb_ge2gb(svb.SVB_F32, 60, 64, None, 64, 32, None, 96, None, 0, stream=0) == 2   # in place: whole tiles only
     assert svb.svb_gb2bd(svb.SVB_F16, 64, 32, None, 96, None, None, None, 0, stream=0) == 2
     assert svb.svb_gb2bd(svb.SVB_F32, 64, 32, None, 96, None, None, None, 0, stream=0) == 1
+    assert svb.svb_gb2bd_noalloc(svb.SVB_F32, 64, 32, None, 96, None, None, stream=0) == 1
+    assert svb.svb_gb2bd_noalloc(svb.SVB_F32, 1 << 20, 32, None, 96, None, None, stream=0) == 1  # null pointers first
     rc, wb = svb.svb_gb2bd_workspace_bytes(1000, 64)
     assert rc == 0 and wb >= 4 * 1000
     assert "workspace" in svb.svb_status_string(3)
