@@ -371,6 +371,14 @@ void launch_update_fused(int nb, bool lq, T* Cb, int64_t lda, int64_t qlen, cons
                          bool credited, hipStream_t s)
 {
     if (qlen <= 0) return;
+    if constexpr (sizeof(C) == 4) {
+        // nb = 128: the kernel built on the 32 x 32 x 2 instruction (SVB_UPDATE_MFMA32=0 keeps this file's)
+        static const bool wide = env_int("SVB_UPDATE_MFMA32", 1) != 0;
+        if (nb == 128 && Tw == nullptr && g * nb <= 512 && qlen % 32 == 0 && wide) {
+            launch_update_fused32<T>(lq, Cb, lda, qlen, V, Y, ldp, chunks, g, stride, tri, credited, s);
+            return;
+        }
+    }
     constexpr int HT = fused_tiles<C>();
 #define SVB_FUSED_ARGS Cb, lda, qlen, V, Y, ldp, chunks, g, stride, Tw, credited, s
 #define SVB_FUSED_CASE(NBV)                                                          \
