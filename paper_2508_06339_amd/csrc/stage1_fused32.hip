@@ -338,6 +338,7 @@ __device__ __forceinline__ void fused32_body(T* __restrict__ Cb, int64_t lda, in
             const float* buf = smem + cur * kBuf + rh * kYHalf;
             const int t = s >> 1, h8 = (s & 1) * 8;
             const int tl = TRI ? t % 4 : 0;            // block row of this tile inside its chunk
+            __builtin_amdgcn_s_setprio(1);   // the wave inside its products goes first
             if (FULL || (active && rh * kHalf + 32 * t < R)) {
 #pragma unroll
                 for (int mt = 0; mt < 4; ++mt) {
@@ -352,6 +353,7 @@ __device__ __forceinline__ void fused32_body(T* __restrict__ Cb, int64_t lda, in
                     }
                 }
             }
+            __builtin_amdgcn_s_setprio(0);
             float* nbuf = smem + (cur ^ 1) * kBuf;
             if (!last) piece_st_y(nbuf);
             else piece_st_v(nbuf);
@@ -402,6 +404,7 @@ __device__ __forceinline__ void fused32_body(T* __restrict__ Cb, int64_t lda, in
             const int t = s >> 1, jh = s & 1;
             const int tl = TRI ? t % 4 : 0;
             const bool mine = FULL || (active && rh * kHalf + 32 * t < R);
+            __builtin_amdgcn_s_setprio(1);   // the wave inside its products goes first
             if (mine) {
 #pragma unroll
                 for (int ml = 0; ml < 2; ++ml) {
@@ -418,6 +421,7 @@ __device__ __forceinline__ void fused32_body(T* __restrict__ Cb, int64_t lda, in
                 }
                 if (jh == 1) tile32_store<T, LQ>(make_rsrc(tile_base(rh * kHalf + 32 * t)), lane_off, rowb, c[t]);
             }
+            __builtin_amdgcn_s_setprio(0);
             if (!last) {
                 piece_st_v(smem + (cur ^ 1) * kBuf);
                 lds_barrier();

@@ -27,16 +27,19 @@ bool dtype_ok(svb_dtype dt) { return dt == SVB_F64 || dt == SVB_F32 || dt == SVB
 bool nb_ok(int nb) { return nb == 32 || nb == 64 || nb == 128; }
 
 // Tile size chosen when the caller passes nb = 0 (the paper tunes TILESIZE per size and
-// hardware, Section 4 and Table 3): the smallest of the measured optima for the order of the
-// matrix.  Small tiles shorten the panel chain and stage 2, large tiles raise the arithmetic
-// intensity of the trailing update, which only matters once the update dominates.
+// hardware, Section 4 and Table 3).  From timings of svb_svdvals on MI355X at orders 1024 .. 24576:
+// small tiles shorten the panel chain and stage 2, large tiles raise the arithmetic intensity of
+// the trailing update, which only pays once the update dominates.  In f32 arithmetic nb = 64 is
+// fastest from order 1024 up to about 20000 (16384: 365 ms against 410 ms at nb = 128), nb = 128
+// beyond (24576: 842 ms against 854 ms); in f64, where a register-resident domain holds half as
+// many rows, nb = 32 up to about 6000 (6144: 120 ms against 123 ms at nb = 64) and nb = 64 beyond
+// (16384: 619 ms against 922 ms at nb = 128).
 int choose_nb(svb_dtype dt, int64_t m, int64_t n)
 {
     const int64_t k = m < n ? m : n;
-    (void)dt;
-    if (k <= 3072) return 32;
-    if (k <= 12288) return 64;
-    return 128;
+    if (dt == SVB_F64) return k <= 7168 ? 32 : 64;
+    if (k < 1024) return 32;
+    return k <= 20480 ? 64 : 128;
 }
 
 inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
