@@ -43,8 +43,13 @@ def device_matrix(name, torch, gaussian=False, n_override=None):
         # counter-collection runs only: same shape and dtype, iid N(0,1/n) drawn on the device
         gen = torch.Generator(device="cuda")
         gen.manual_seed(workloads.config_seed(cfg["seed_id"]))
-        a = torch.randn(n, n, dtype=torch.float32, device="cuda", generator=gen) / float(np.sqrt(n))
-        return a.to(tdt), dict(name=name, n=n, nb=cfg["nb"], dtype=cfg["dtype"], seed=0, sigma=None)
+        # (a view of a slightly larger allocation: counter collection has crashed on allocations of
+        # exactly 4 GiB)
+        a = torch.empty(n, n + 16, dtype=tdt, device="cuda")[:, :n]
+        for j0 in range(0, n, 4096):   # in blocks: no single launch touches more than 1 GiB
+            blk = torch.randn(min(4096, n - j0), n, dtype=torch.float32, device="cuda", generator=gen)
+            a[j0:j0 + 4096] = (blk / float(np.sqrt(n))).to(tdt)
+        return a, dict(name=name, n=n, nb=cfg["nb"], dtype=cfg["dtype"], seed=0, sigma=None)
     if cfg["kind"] == "iid":
         a, info = workloads.make(name, n=n)
         return torch.from_numpy(np.ascontiguousarray(a.T)).cuda(), info
@@ -96,7 +101,8 @@ def run_workload(args, svb, torch, workloads, config, steps, warmup):
     stream = torch.cuda.current_stream().cuda_stream
 
     def one_step():
-        a.copy_(a0)                      # stage 1 destroys its input; the refresh is not timed
+        for j0 in range(0, n, 8192):     # stage 1 destroys its input; the refresh (in blocks) is not timed
+            a[j0:j0 + 8192].copy_(a0[j0:j0 + 8192])
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         rc = svb.svb_svdvals(dt_code, n, n, abuf, lda, out, nb, work, wbytes, stream)
@@ -147,9 +153,22 @@ def run_workload(args, svb, torch, workloads, config, steps, warmup):
     for k, v in prof.items():
         kernels[k] = dict(ms_per_step=v["seconds"] / steps * 1e3, launches_per_step=v["launches"] / steps,
                           avg_launch_us=v["seconds"] / max(v["launches"], 1) * 1e6)
-    # HBM bytes per launch from the committed rocprofv3 --pmc summary of this workload, if there is one
+    # HBM bytes from the committed rocprofv3 --pmc summary of this workload, if there is one.  Where the
+    # counters could only be collected on the workload's recipe at another order (the file name says
+    # so), the measured ratio of counter bytes to algorithmic bytes is applied to this run's
+    # algorithmic bytes.
+    import glob
     tfile = os.path.join(ROOT, "profiles", f"hbm_traffic_{config}_{n}_{dtype}_nb{nb}.json")
-    traffic = json.load(open(tfile)) if os.path.exists(tfile) else None
+    traffic, traffic_src = None, None
+    if os.path.exists(tfile):
+        traffic, traffic_src = json.load(open(tfile)), "counters on this workload"
+    else:
+        alt = sorted(glob.glob(os.path.join(ROOT, "profiles", f"hbm_traffic_{config}-recipe_*_{dtype}_nb{nb}.json")))
+        if alt:
+            traffic = json.load(open(alt[-1]))
+            traffic_src = ("counter-to-algorithmic byte ratio measured on " + traffic["_meta"]["workload"] +
+                           ", applied to this run's algorithmic bytes")
+    exact_traffic = traffic is not None and traffic_src.startswith("counters")
 
     def counter_bytes(prefix, want_tri=None):
         """(bytes, launches) per svb_svdvals call of the kernels whose name starts with prefix."""
@@ -160,9 +179,11 @@ def run_workload(args, svb, torch, workloads, config, steps, warmup):
             if not name.startswith(prefix):
                 continue
             if want_tri is not None:
-                # update_fused_kernel<T, C, NB, HT, LQ, TRI, USET>: TRI marks the tree levels above the first
+                # update_fused_kernel<T, C, NB, HT, LQ, TRI, USET> / update_fused32_kernel<T, LQ, TRI>:
+                # TRI marks the tree levels above the first
                 targs = [x.strip() for x in name[name.index("<") + 1:name.rindex(">")].split(",")]
-                if (targs[5] == "true") != want_tri:
+                tri = targs[2] if name.startswith("update_fused32") else targs[5]
+                if (tri == "true") != want_tri:
                     continue
             tot += (v["read_GB"] + v["write_GB"]) * 1e9
             cnt += v["launches"]
@@ -185,10 +206,16 @@ def run_workload(args, svb, torch, workloads, config, steps, warmup):
                         avg_launch_ms=upd["seconds"] / max(upd["launches"], 1) * 1e3,
                         algorithmic_bytes_per_launch=upd["bytes"] / max(upd["launches"], 1),
                         algorithmic_flops_per_launch=upd["flops"] / max(upd["launches"], 1))
-        cb = counter_bytes("update_fused_kernel", want_tri=False)
-        if cb:
+        cb = counter_bytes("update_fused", want_tri=False)
+        if cb and exact_traffic:
             roofline["traffic"] = cb[0] / cb[1]
+        elif cb and "update_first_level_algorithmic_GB" in traffic["_meta"]:
+            ratio = cb[0] / (traffic["_meta"]["update_first_level_algorithmic_GB"] * 1e9)
+            roofline["traffic"] = ratio * roofline["algorithmic_bytes_per_launch"]
+            roofline["traffic_to_algorithmic_ratio"] = ratio
+        if cb:
             roofline["traffic_unit"] = "HBM bytes per launch (FETCH_SIZE + WRITE_SIZE, calibrated), first tree level"
+            roofline["traffic_source"] = traffic_src
         allsec = upd["seconds"] + prof["update_upper"]["seconds"]
         roofline["frac_all_tree_levels"] = upd["flops"] / allsec / 1e12 / peak if allsec > 0 else None
     else:
@@ -214,8 +241,12 @@ def run_workload(args, svb, torch, workloads, config, steps, warmup):
                            one_phase_chase_model_bytes=3.0 * n * n * nb * cs)
     cb1, cb2 = counter_bytes("band_reduce_kernel"), counter_bytes("chase_narrow_kernel")
     if cb1 and cb2:
-        roofline_stage2["traffic"] = cb1[0] + cb2[0]
-        roofline_stage2["traffic_gbs"] = (cb1[0] + cb2[0]) / st[1] / 1e9 if st[1] > 0 else None
+        t2 = cb1[0] + cb2[0]
+        if not exact_traffic:
+            t2 = t2 / (traffic["_meta"]["stage2_algorithmic_GB"] * 1e9) * s2_bytes
+        roofline_stage2["traffic"] = t2
+        roofline_stage2["traffic_gbs"] = t2 / st[1] / 1e9 if st[1] > 0 else None
+        roofline_stage2["traffic_source"] = traffic_src
     kind = "gaussian stand-in" if args.gaussian_input else workloads.CONFIGS[config]["kind"]
     return {
         "value": value, "ms_per_step": ms_per_step, "dtype": dtype,

@@ -92,7 +92,8 @@ def _pool_size(work_items: int) -> int:
     import os
     if work_items < (1 << 24):
         return 1
-    return max(1, min(16, os.cpu_count() or 1))
+    limit = int(os.environ.get("SVB_GEN_THREADS", "16"))   # 1: no thread pool (e.g. under a profiler)
+    return max(1, min(limit, os.cpu_count() or 1))
 
 
 def gaussian_matrix(seed: int, m: int, n: int, scale: float = 1.0,
