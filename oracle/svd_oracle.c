@@ -15,9 +15,9 @@
  *
  *   1. unblocked Golub-Kahan Householder bidiagonalisation (one column
  *      reflector from the left, one row reflector from the right, per step);
- *      this is the "classic Householder QR, which operates row-by-row
- *      instead of tile-by-tile" that Section 3.2 says the tiled algorithm
- *      restructures, with the 8/3 n^3 flop count the benchmark credits;
+ *      this is the classic, untiled Householder algorithm that the tiled
+ *      algorithm of Section 3.2 restructures, with the 8/3 n^3 flop count
+ *      the benchmark credits;
  *   2. the singular values of the bidiagonal by bisection with Sturm counts
  *      on the Golub-Kahan tridiagonal (zero diagonal, off-diagonals
  *      |d_1|,|e_1|,|d_2|,...), whose eigenvalues are +-sigma_i.  (The paper

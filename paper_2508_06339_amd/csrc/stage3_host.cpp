@@ -1,6 +1,6 @@
-// Stage 3 on the host (paper Section 3, final stage: "reduction from
-// bidiagonal form to singular values ... existing CPU implementations"; the
-// paper calls LAPACK, this library carries its own solver).
+// Stage 3 on the host (paper Section 3, final stage: bidiagonal to singular
+// values, which the paper leaves to a CPU library, LAPACK; this library
+// carries its own solver).
 //
 // Bisection on the Golub-Kahan tridiagonal (order 2n, zero diagonal,
 // off-diagonals |d1|,|e1|,|d2|,...; its positive eigenvalues are the singular
