@@ -434,6 +434,16 @@ static void launch_panel_y(const C* V, C* Y, const C* Tws, int64_t ldp, int64_t 
                        Tws, ldp, rows, g);
 }
 
+template <typename C>
+void launch_panel_y_nb(int nb, const C* V, C* Y, const C* Tws, int64_t ldp, int64_t rows, int g, hipStream_t s)
+{
+    if (nb == 32) launch_panel_y<C, 32>(V, Y, Tws, ldp, rows, g, s);
+    else if (nb == 64) launch_panel_y<C, 64>(V, Y, Tws, ldp, rows, g, s);
+    else launch_panel_y<C, 128>(V, Y, Tws, ldp, rows, g, s);
+}
+template void launch_panel_y_nb<float>(int, const float*, float*, const float*, int64_t, int64_t, int, hipStream_t);
+template void launch_panel_y_nb<double>(int, const double*, double*, const double*, int64_t, int64_t, int, hipStream_t);
+
 template <typename C> bool panel_blk_serves(int nb, int g)
 {
     return env_int("SVB_PANEL_IMPL", 2) == 2 && panel_blk_rows<C>() >= g * nb && (g * nb) % 128 == 0;

@@ -118,15 +118,62 @@ template <typename T, typename C> struct PanelEnds {
     C* band; int64_t ldab, row0, col0;
 };
 
+// Hand-over of R between the levels of a panel tree that run at the same time (Section 3.1:
+// the tile below is annihilated against the triangle above it -- here a stack of triangles
+// against each other).  A domain's R is upper triangular, so its rows 16b .. 16b+15 are final as
+// soon as the domain's block step b is done, and block step b of the level above needs exactly
+// those rows of its stacked factors and nothing below them.  A domain therefore publishes R tile
+// row by tile row (flag = base + number of block steps done), and the level above fetches tile
+// row b of every chunk right before its own block step b: it runs one block step behind the level
+// below instead of a whole level behind.
+// The R tiles travel through device-scope accesses (written through to, and read from, the
+// memory level all compute dies share), as the flags do: no cache write-back or invalidate.
+struct TreeSync {
+    const int* in_flags;   // flags of the level below, indexed by its domain (null: panel complete in memory)
+    int* out_flag;         // this domain's flag (null: R is written when the domain is done)
+    int base;              // value of a flag before the first block step of this half-sweep
+    int spin_limit;        // polls before a wait gives up and raises *err
+    int* err;
+};
+__device__ __forceinline__ int flag_ld(const int* p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void flag_st(int* p, int v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// the four entries a lane holds of a 16 x 16 tile of a work panel, through device-scope accesses
+template <typename C>
+__device__ __forceinline__ typename Frag<C>::acc_t frag_load_dev(const C* P, int64_t ldp, int64_t p0, int64_t q, int gq)
+{
+    typename Frag<C>::acc_t c;
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+        c[r] = __hip_atomic_load(&P[p0 + Frag<C>::roff(r, gq) + q * ldp], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return c;
+}
+template <typename C>
+__device__ __forceinline__ void frag_store_dev(C* P, int64_t ldp, int64_t p0, int64_t q, int gq,
+                                               const typename Frag<C>::acc_t& c)
+{
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+        __hip_atomic_store(&P[p0 + Frag<C>::roff(r, gq) + q * ldp], c[r], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // TRI: the panel is a stack of upper triangular NB x NB factors (tree levels above the first).
 // Block b's reflectors are then exactly zero in every 16-row tile that lies below block row b
 // of its chunk, and both products skip those tiles.
-template <typename T, typename C, int NB, int HT, bool TRI>
-__global__ __launch_bounds__(NB * 4) void panel_qr_blk_kernel(C* __restrict__ P, int64_t ldp,
-                                                              C* __restrict__ Tws, int chunks, int g,
-                                                              C* __restrict__ Pnext, int64_t ldnext,
-                                                              PanelEnds<T, C> ends)
+// PIN: the stacked factors arrive tile row by tile row from domains of the level below that are
+// still running (TreeSync); d: the domain this workgroup factors.
+template <typename T, typename C, int NB, int HT, bool TRI, bool PIN>
+__device__ __forceinline__ void panel_blk_body(C* __restrict__ P, int64_t ldp,
+                                               C* __restrict__ Tws, int chunks, int g,
+                                               C* __restrict__ Pnext, int64_t ldnext,
+                                               const PanelEnds<T, C>& ends, const int d, const TreeSync& sy)
 {
+    static_assert(!PIN || TRI, "only stacks of triangular factors arrive piecewise");
     using F = Frag<C>;
     using G = PanelBlkGeom<C, NB, HT>;
     typedef typename F::acc_t acc_t;
@@ -145,7 +192,6 @@ __global__ __launch_bounds__(NB * 4) void panel_qr_blk_kernel(C* __restrict__ P,
     C* Tb = sm + G::oTb;
     C* taus = sm + G::oTau;
 
-    const int d = blockIdx.x;
     const int nch = min(g, chunks - d * g);
     const int ntile = nch * NB / 16;              // 16-row tiles that exist (the rest reads as zero)
     C* Pd = P + (int64_t)d * g * NB;
@@ -164,7 +210,7 @@ __global__ __launch_bounds__(NB * 4) void panel_qr_blk_kernel(C* __restrict__ P,
     acc_t c[HT];
 #pragma unroll
     for (int t = 0; t < HT; ++t) {
-        if (t < ntile) {
+        if (!PIN && t < ntile) {
             if (ends.Asrc) {
                 const int64_t p0 = (int64_t)d * g * NB + 16 * t;
                 c[t] = ends.lq ? frag_load<T, C, true>(ends.Asrc, ends.lda, p0, mycol, gq)
@@ -181,6 +227,26 @@ __global__ __launch_bounds__(NB * 4) void panel_qr_blk_kernel(C* __restrict__ P,
 
     PT_MARK(0);
     for (int b = 0; b < NW; ++b) {
+        if constexpr (PIN) {
+            // ---- 0. tile row b of every stacked factor, once the domain below has published it
+            if (tid < nch) {
+                const int need = sy.base + b + 1;
+                int spins = 0;
+                while (flag_ld(&sy.in_flags[d * g + tid]) < need) {
+                    if (++spins > sy.spin_limit) {
+                        atomicExch(sy.err, 1);
+                        break;
+                    }
+                    __builtin_amdgcn_s_sleep(1);
+                }
+            }
+            __syncthreads();
+            if (wave >= b) {
+#pragma unroll
+                for (int t = 0; t < HT; ++t)
+                    if (t % NW == b && t < ntile) c[t] = frag_load_dev<C>(Pd, ldp, 16 * t, mycol, gq);
+            }
+        }
         // ---- 1. the owner's columns (rows 16b ..) to LDS
         if (wave == b) {
 #pragma unroll
@@ -414,7 +480,17 @@ __global__ __launch_bounds__(NB * 4) void panel_qr_blk_kernel(C* __restrict__ P,
                 F::st4(&Zs[i * LDZ + 16 * wave], gq, o);
             }
         }
+        if (sy.out_flag) {
+            // rows 16b .. 16b+15 of R are final (no later block touches them): hand them over
+            if (wave >= b) {
+#pragma unroll
+                for (int t = 0; t < NW; ++t)
+                    if (t == b) frag_store_dev<C>(Rd, ldnext, 16 * t, mycol, gq, c[t]);
+            }
+            __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): the stores have been acknowledged
+        }
         __syncthreads();
+        if (sy.out_flag && tid == 0) flag_st(sy.out_flag, sy.base + b + 1);
         PT_MARK(6);
 
         // ---- T[wave, b] = - sum_{w2 = wave}^{b-1} T[wave, w2] Z_w2
@@ -453,7 +529,7 @@ __global__ __launch_bounds__(NB * 4) void panel_qr_blk_kernel(C* __restrict__ P,
                     }
                 }
             }
-        } else {
+        } else if (!sy.out_flag) {
             acc_t v;
 #pragma unroll
             for (int r = 0; r < 4; ++r) v[r] = (t <= wave) ? c[t][r] : (C)0;
@@ -476,9 +552,111 @@ template <typename C> int panel_blk_rows() { return panel_blk_tiles<C>() * 16; }
 template int panel_blk_rows<float>();
 template int panel_blk_rows<double>();
 
+// One tree level: workgroup d factors domain d.  out_flags (may be null): the domains' hand-over
+// flags for a level above that runs at the same time (TreeSync).
+template <typename T, typename C, int NB, int HT, bool TRI>
+__global__ __launch_bounds__(NB * 4) void panel_qr_blk_kernel(C* __restrict__ P, int64_t ldp,
+                                                              C* __restrict__ Tws, int chunks, int g,
+                                                              C* __restrict__ Pnext, int64_t ldnext,
+                                                              PanelEnds<T, C> ends, int* out_flags, int flag_base)
+{
+    const int d = blockIdx.x;
+    const TreeSync sy{nullptr, out_flags ? out_flags + d : nullptr, flag_base, 0, nullptr};
+    panel_blk_body<T, C, NB, HT, TRI, false>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, d, sy);
+}
+
+// Every tree level above the first in one launch, running beside the first level's kernel.  A
+// workgroup draws a ticket; tickets are numbered level by level, so the domains a workgroup waits
+// for hold smaller tickets and are already running or done.
+template <typename C, int NB>
+__global__ __launch_bounds__(NB * 4) void panel_tree_kernel(PanelTreeArgs<C> a)
+{
+    constexpr int HT = panel_blk_tiles<C>();
+    __shared__ int sh_ticket;
+    if (threadIdx.x == 0) sh_ticket = atomicAdd(a.ticket, 1);
+    __syncthreads();
+    const int tk = sh_ticket;
+    if (tk >= a.total) return;
+    int L = 0;
+    while (L + 1 < a.nl && tk >= a.lv[L + 1].first) ++L;
+    const PanelTreeLevel<C>& lv = a.lv[L];
+    const int d = tk - lv.first;
+    const bool last = L == a.nl - 1;
+    const TreeSync sy{a.flags + lv.flags_in, last ? nullptr : a.flags + lv.flags_out + d, a.flag_base, a.spin_limit,
+                      a.err};
+    const PanelEnds<C, C> ends{nullptr, 0, a.lq, last ? a.band : nullptr, a.ldab, a.row0, a.col0};
+    // a short stack near the top of the tree runs the body sized for it (fewer rows per thread in
+    // the reflector steps, fewer tiles in the block products)
+    if constexpr (HT / 4 * 16 >= NB) {
+        if (lv.tiles <= HT / 4) {
+            panel_blk_body<C, C, NB, HT / 4, true, true>(lv.P, lv.ldp, lv.Tws, lv.chunks, a.g, lv.Pnext, lv.ldnext, ends, d, sy);
+            return;
+        }
+    }
+    if constexpr (HT / 2 * 16 >= NB) {
+        if (lv.tiles <= HT / 2) {
+            panel_blk_body<C, C, NB, HT / 2, true, true>(lv.P, lv.ldp, lv.Tws, lv.chunks, a.g, lv.Pnext, lv.ldnext, ends, d, sy);
+            return;
+        }
+    }
+    panel_blk_body<C, C, NB, HT, true, true>(lv.P, lv.ldp, lv.Tws, lv.chunks, a.g, lv.Pnext, lv.ldnext, ends, d, sy);
+}
+
+__global__ void fill_int_kernel(int* p, int n, int v)
+{
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) p[i] = v;
+}
+// a raised error flag of the panel tree (an expired wait) becomes a NaN in the band, which the
+// later stages carry into the result's status
+template <typename C> __global__ void tree_err_kernel(const int* err, C* band_entry)
+{
+    if (*err) *band_entry = (C)NAN;
+}
+
+void launch_fill_int(int* p, int n, int v, hipStream_t s)
+{
+    if (n > 0) hipLaunchKernelGGL(fill_int_kernel, dim3((unsigned)((n + 255) / 256 < 64 ? (n + 255) / 256 : 64)), dim3(256), 0, s, p, n, v);
+}
+template <typename C> void launch_tree_err(const int* err, C* band_entry, hipStream_t s)
+{
+    hipLaunchKernelGGL(tree_err_kernel<C>, dim3(1), dim3(1), 0, s, err, band_entry);
+}
+template void launch_tree_err<float>(const int*, float*, hipStream_t);
+template void launch_tree_err<double>(const int*, double*, hipStream_t);
+
+template <typename C, int NB>
+static void launch_tree_nb(const PanelTreeArgs<C>& a, hipStream_t s, hipEvent_t start, hipEvent_t done)
+{
+    using G = PanelBlkGeom<C, NB, panel_blk_tiles<C>()>;
+    auto kern = panel_tree_kernel<C, NB>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  (int)G::kSmemBytes);
+        attr_set = true;
+    }
+    if (done)
+        hipExtLaunchKernelGGL(kern, dim3((unsigned)a.total), dim3(G::NT), (uint32_t)G::kSmemBytes, s, start, done, 0u, a);
+    else
+        hipLaunchKernelGGL(kern, dim3((unsigned)a.total), dim3(G::NT), G::kSmemBytes, s, a);
+}
+
+template <typename C>
+void launch_panel_tree(int nb, const PanelTreeArgs<C>& a, hipStream_t s, hipEvent_t start, hipEvent_t done)
+{
+    switch (nb) {
+    case 32: launch_tree_nb<C, 32>(a, s, start, done); break;
+    case 64: launch_tree_nb<C, 64>(a, s, start, done); break;
+    default: launch_tree_nb<C, 128>(a, s, start, done); break;
+    }
+}
+template void launch_panel_tree<float>(int, const PanelTreeArgs<float>&, hipStream_t, hipEvent_t, hipEvent_t);
+template void launch_panel_tree<double>(int, const PanelTreeArgs<double>&, hipStream_t, hipEvent_t, hipEvent_t);
+
 template <typename T, typename C, int NB, int HT, bool TRI>
 static void launch_blk_ht(C* P, int64_t ldp, C* Tws, int chunks, int g, C* Pnext, int64_t ldnext,
-                          const PanelEnds<T, C>& ends, hipStream_t s, hipEvent_t done, hipEvent_t start)
+                          const PanelEnds<T, C>& ends, int* out_flags, int flag_base, hipStream_t s, hipEvent_t done,
+                          hipEvent_t start)
 {
     using G = PanelBlkGeom<C, NB, HT>;
     auto kern = panel_qr_blk_kernel<T, C, NB, HT, TRI>;
@@ -493,55 +671,57 @@ static void launch_blk_ht(C* P, int64_t ldp, C* Tws, int chunks, int g, C* Pnext
     // marker in the stream between this kernel and the next one
     if (done)
         hipExtLaunchKernelGGL(kern, dim3(domains), dim3(G::NT), (uint32_t)G::kSmemBytes, s, start, done, 0u, P, ldp,
-                              Tws, chunks, g, Pnext, ldnext, ends);
+                              Tws, chunks, g, Pnext, ldnext, ends, out_flags, flag_base);
     else
-        hipLaunchKernelGGL(kern, dim3(domains), dim3(G::NT), G::kSmemBytes, s, P, ldp, Tws, chunks, g, Pnext, ldnext, ends);
+        hipLaunchKernelGGL(kern, dim3(domains), dim3(G::NT), G::kSmemBytes, s, P, ldp, Tws, chunks, g, Pnext, ldnext,
+                           ends, out_flags, flag_base);
 }
 
 template <typename T, typename C, int NB>
 static void launch_blk(C* P, int64_t ldp, C* Tws, int chunks, int g, C* Pnext, int64_t ldnext,
-                       const PanelEnds<T, C>& ends, hipStream_t s, hipEvent_t done, hipEvent_t start)
+                       const PanelEnds<T, C>& ends, int* out_flags, int flag_base, hipStream_t s, hipEvent_t done,
+                       hipEvent_t start)
 {
     constexpr int HT = panel_blk_tiles<C>();
     // a panel that does not come from the matrix is a stack of triangular factors; near the top of
     // the tree such a stack is short, and a kernel sized for it (fewer rows per thread in the
     // reflector steps, fewer tiles in the block products) is faster than the full-height one
     if (ends.Asrc) {
-        launch_blk_ht<T, C, NB, HT, false>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, s, done, start);
+        launch_blk_ht<T, C, NB, HT, false>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, out_flags, flag_base, s, done, start);
         return;
     }
     const int need = (chunks < g ? chunks : g) * NB / 16;   // tiles of the tallest domain
     if constexpr (HT / 4 * 16 >= NB) {
         if (need <= HT / 4) {
-            launch_blk_ht<T, C, NB, HT / 4, true>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, s, done, start);
+            launch_blk_ht<T, C, NB, HT / 4, true>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, out_flags, flag_base, s, done, start);
             return;
         }
     }
     if constexpr (HT / 2 * 16 >= NB) {
         if (need <= HT / 2) {
-            launch_blk_ht<T, C, NB, HT / 2, true>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, s, done, start);
+            launch_blk_ht<T, C, NB, HT / 2, true>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, out_flags, flag_base, s, done, start);
             return;
         }
     }
-    launch_blk_ht<T, C, NB, HT, true>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, s, done, start);
+    launch_blk_ht<T, C, NB, HT, true>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, out_flags, flag_base, s, done, start);
 }
 
 template <typename T, typename C>
 void launch_panel_blk(int nb, C* P, int64_t ldp, C* Tws, int chunks, int g, C* Pnext, int64_t ldnext,
                       const T* Asrc, int64_t lda, bool lq, C* band, int64_t ldab, int64_t row0, int64_t col0,
-                      hipStream_t s, hipEvent_t done, hipEvent_t start)
+                      hipStream_t s, hipEvent_t done, hipEvent_t start, int* out_flags, int flag_base)
 {
     const PanelEnds<T, C> ends{Asrc, lda, lq ? 1 : 0, band, ldab, row0, col0};
     switch (nb) {
-    case 32: launch_blk<T, C, 32>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, s, done, start); break;
-    case 64: launch_blk<T, C, 64>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, s, done, start); break;
-    default: launch_blk<T, C, 128>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, s, done, start); break;
+    case 32: launch_blk<T, C, 32>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, out_flags, flag_base, s, done, start); break;
+    case 64: launch_blk<T, C, 64>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, out_flags, flag_base, s, done, start); break;
+    default: launch_blk<T, C, 128>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, out_flags, flag_base, s, done, start); break;
     }
 }
 
-template void launch_panel_blk<float, float>(int, float*, int64_t, float*, int, int, float*, int64_t, const float*, int64_t, bool, float*, int64_t, int64_t, int64_t, hipStream_t, hipEvent_t, hipEvent_t);
-template void launch_panel_blk<__half, float>(int, float*, int64_t, float*, int, int, float*, int64_t, const __half*, int64_t, bool, float*, int64_t, int64_t, int64_t, hipStream_t, hipEvent_t, hipEvent_t);
-template void launch_panel_blk<bf16_t, float>(int, float*, int64_t, float*, int, int, float*, int64_t, const bf16_t*, int64_t, bool, float*, int64_t, int64_t, int64_t, hipStream_t, hipEvent_t, hipEvent_t);
-template void launch_panel_blk<double, double>(int, double*, int64_t, double*, int, int, double*, int64_t, const double*, int64_t, bool, double*, int64_t, int64_t, int64_t, hipStream_t, hipEvent_t, hipEvent_t);
+template void launch_panel_blk<float, float>(int, float*, int64_t, float*, int, int, float*, int64_t, const float*, int64_t, bool, float*, int64_t, int64_t, int64_t, hipStream_t, hipEvent_t, hipEvent_t, int*, int);
+template void launch_panel_blk<__half, float>(int, float*, int64_t, float*, int, int, float*, int64_t, const __half*, int64_t, bool, float*, int64_t, int64_t, int64_t, hipStream_t, hipEvent_t, hipEvent_t, int*, int);
+template void launch_panel_blk<bf16_t, float>(int, float*, int64_t, float*, int, int, float*, int64_t, const bf16_t*, int64_t, bool, float*, int64_t, int64_t, int64_t, hipStream_t, hipEvent_t, hipEvent_t, int*, int);
+template void launch_panel_blk<double, double>(int, double*, int64_t, double*, int, int, double*, int64_t, const double*, int64_t, bool, double*, int64_t, int64_t, int64_t, hipStream_t, hipEvent_t, hipEvent_t, int*, int);
 
 }  // namespace svb

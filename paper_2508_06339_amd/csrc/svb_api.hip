@@ -147,12 +147,13 @@ bool aligned_for_vectors(const void* A, int64_t lda, svb_dtype dt)
 // Environment switches, read once per process (they select kernel variants kept for testing and
 // measurement; the launch loops consult this copy).
 struct Switches {
-    int domain_chunks, pipeline_layout, ext_events, update_t, event_fence, stage3_host, stage3_relative, no_scale;
+    int domain_chunks, pipeline_layout, tree_spin, ext_events, update_t, event_fence, stage3_host, stage3_relative, no_scale;
     bool loaded = false;
     void load()
     {
         domain_chunks = env_int("SVB_DOMAIN_CHUNKS", 0);
-        pipeline_layout = env_int("SVB_PIPELINE_LAYOUT", 1);
+        pipeline_layout = env_int("SVB_PIPELINE_LAYOUT", 2);
+        tree_spin = env_int("SVB_TREE_SPIN", 1 << 22);
         ext_events = env_int("SVB_EXT_EVENTS", 1);
         update_t = env_int("SVB_UPDATE_T", 1);
         event_fence = env_int("SVB_EVENT_FENCE", 0);
@@ -177,13 +178,14 @@ int domain_chunks(svb_dtype dt, int nb, const Switches& sw)
     return cap;
 }
 constexpr int kMinDomainChunks = 2;  // workspace is sized for any g >= this
+constexpr size_t kTreeHead = 4;      // ints in front of the tickets of the panel tree's control block
 
 // Workspace layout.  V, Y, T: the panels and factors of one half-sweep's tree (element counts in
 // the compute type); stage: the zero-padded copy of an input that is not a whole number of tiles
 // or is wider than tall (storage type).
 struct Carve {
-    size_t panel_elems, t_elems, band_elems, de_elems, stage_elems;
-    size_t off_V, off_Y, off_T, off_band, off_d, off_e, off_sig, off_s3, off_fac, off_gb, off_stage, total;
+    size_t panel_elems, t_elems, band_elems, de_elems, stage_elems, tree_ints;
+    size_t off_V, off_Y, off_T, off_band, off_d, off_e, off_sig, off_s3, off_fac, off_gb, off_tree, off_stage, total;
 };
 
 Carve carve(svb_dtype dt, const Shape& sh, int nb)
@@ -197,6 +199,8 @@ Carve carve(svb_dtype dt, const Shape& sh, int nb)
     c.band_elems = (size_t)(3 * nb) * (size_t)cols;
     c.de_elems = (size_t)cols;
     c.stage_elems = sh.staged ? (size_t)rows * (size_t)cols : 0;
+    // panel tree hand-over: error flag, one ticket counter per half-sweep, one flag per domain
+    c.tree_ints = kTreeHead + 2 * (size_t)(cols / nb) + 2 + (size_t)(rows / nb) + kMaxLevels + 2;
     size_t off = 0;
     c.off_V = off; off += align_up(c.panel_elems * cs);
     c.off_Y = off; off += align_up(c.panel_elems * cs);
@@ -208,6 +212,7 @@ Carve carve(svb_dtype dt, const Shape& sh, int nb)
     c.off_s3 = off; off += align_up(bdsvals_dev_workspace_bytes(sh.k));
     c.off_fac = off; off += align_up(scale_workspace_bytes());
     c.off_gb = off; off += align_up(gb2bd_bytes(sh.k, nb));
+    c.off_tree = off; off += align_up(c.tree_ints * sizeof(int));
     c.off_stage = off; off += align_up(c.stage_elems * storage_size(dt));
     c.total = off;
     return c;
@@ -378,6 +383,11 @@ int ge2gb_pipeline(int64_t rows, int64_t cols, T* A, int64_t lda, int nb, C* ban
     (void)hipStreamWaitEvent(ms, g_la.fork, 0);
     (void)hipStreamWaitEvent(ss, g_la.fork, 0);
     launch_band_clear<C>(band, ldab, cols, ms);
+    // control block of the panel tree: error flag, a ticket counter per half-sweep, a flag per domain
+    int* const tree_err = reinterpret_cast<int*>(work + cv.off_tree);
+    int* const tree_tickets = tree_err + kTreeHead;
+    int* const tree_flags = tree_tickets + 2 * N + 2;
+    launch_fill_int(tree_err, (int)cv.tree_ints, 0, ms);
     C* Vb = reinterpret_cast<C*>(work + cv.off_V);
     C* Yb = reinterpret_cast<C*>(work + cv.off_Y);
     C* Tb = reinterpret_cast<C*>(work + cv.off_T);
@@ -443,6 +453,70 @@ int ge2gb_pipeline(int64_t rows, int64_t cols, T* A, int64_t lda, int nb, C* ban
                                           lv[L].chunks, g, lv[L].stride, L > 0,
                                           useT ? Tb + toff[L] : (const C*)nullptr, L == 0, st);
             };
+            if (layout == 2 && direct && nl > 1 && tsum <= (int64_t)cv.t_elems) {
+                // Tree in two launches that run side by side: the first level on the main stream, every
+                // level above it in one kernel on the side stream, each level one block step behind the
+                // level below (TreeSync in stage1_panel_blk.hip).  Every update follows on the main
+                // stream: U0 needs the first level only, the others wait for the side stream.
+                int foff[kMaxLevels], fsum = 0;
+                for (int L = 0; L < nl; ++L) {
+                    foff[L] = fsum;
+                    fsum += lv[L].domains;
+                }
+                const int base = (hs + 1) * 64;
+                (void)hipEventRecord(g_la.lvl[set][0], ms);   // behind the previous half-sweep's last update
+                (void)hipStreamWaitEvent(ss, g_la.lvl[set][0], 0);
+                {
+                    hipEvent_t ea = nullptr, eb = nullptr;
+                    const bool timed = prof_take(SVB_PROF_PANEL, 2.0 * (double)len * nb * nb, 0.0, &ea, &eb);
+                    launch_panel_blk<T, C>(nb, Vb + lv[0].poff, lv[0].ldp, Tb + toff[0], lv[0].chunks, g,
+                                           Vb + lv[0].poff + lv[0].ldp * nb, (int64_t)lv[0].domains * nb,
+                                           A + row0 + col0 * lda, lda, lq, nullptr, ldab, row0, col0, ms,
+                                           timed ? eb : nullptr, ea, tree_flags + foff[0], base);
+                    if (!useT)
+                        launch_panel_y_nb<C>(nb, Vb + lv[0].poff, Yb + lv[0].poff, Tb + toff[0], lv[0].ldp,
+                                             (int64_t)lv[0].chunks * nb, g, ms);
+                }
+                PanelTreeArgs<C> ta{};
+                int first = 0;
+                for (int L = 1; L < nl; ++L) {
+                    PanelTreeLevel<C>& t = ta.lv[L - 1];
+                    t.P = Vb + lv[L].poff;
+                    t.Tws = Tb + toff[L];
+                    t.Pnext = Vb + lv[L].poff + lv[L].ldp * nb;
+                    t.ldp = lv[L].ldp;
+                    t.ldnext = (int64_t)lv[L].domains * nb;
+                    t.chunks = lv[L].chunks;
+                    t.tiles = (lv[L].chunks < g ? lv[L].chunks : g) * nb / 16;
+                    t.first = first;
+                    first += lv[L].domains;
+                    t.flags_in = foff[L - 1];
+                    t.flags_out = foff[L];
+                }
+                ta.nl = nl - 1; ta.total = first; ta.g = g; ta.lq = lq ? 1 : 0;
+                ta.ticket = tree_tickets + hs; ta.flags = tree_flags; ta.err = tree_err;
+                ta.flag_base = base; ta.spin_limit = sw.tree_spin;
+                ta.band = band; ta.ldab = ldab; ta.row0 = row0; ta.col0 = col0;
+                hipEvent_t ea = nullptr, eb = nullptr;
+                const bool timed = prof_take(SVB_PROF_PANEL, 0.0, 0.0, &ea, &eb);
+                const bool tied = useT && (timed || ext_events);   // the tree is the side stream's last kernel
+                hipEvent_t upper_done = timed ? eb : g_la.lvl[set][1];
+                launch_panel_tree<C>(nb, ta, ss, ea, (tied || timed) ? upper_done : nullptr);
+                if (!useT)
+                    for (int L = 1; L < nl; ++L)
+                        launch_panel_y_nb<C>(nb, Vb + lv[L].poff, Yb + lv[L].poff, Tb + toff[L], lv[L].ldp,
+                                             (int64_t)lv[L].chunks * nb, g, ss);
+                if (!tied) {
+                    upper_done = g_la.lvl[set][1];
+                    (void)hipEventRecord(upper_done, ss);
+                }
+                if (qlen > 0) update(0, ms);
+                (void)hipStreamWaitEvent(ms, upper_done, 0);
+                if (qlen > 0)
+                    for (int L = 1; L < nl; ++L) update(L, ms);
+                ++hs;
+                continue;
+            }
             if (side_pending) {
                 // the previous half-sweep left its last update on the side stream
                 (void)hipStreamWaitEvent(ms, g_la.udone[(hs - 1) & 1], 0);
@@ -475,6 +549,7 @@ int ge2gb_pipeline(int64_t rows, int64_t cols, T* A, int64_t lda, int nb, C* ban
             ++hs;
         }
     }
+    launch_tree_err<C>(tree_err, band + (2 * nb - 1), ms);
     (void)hipEventRecord(g_la.join, ms);
     (void)hipEventRecord(g_la.join_u, ss);
     (void)hipStreamWaitEvent(caller, g_la.join, 0);

@@ -94,8 +94,37 @@ void launch_panel_qr(int nb, C* P, int64_t ldp, C* Y, C* Tws, int chunks, int g,
 template <typename T, typename C>
 void launch_panel_blk(int nb, C* P, int64_t ldp, C* Tws, int chunks, int g, C* Pnext, int64_t ldnext,
                       const T* Asrc, int64_t lda, bool lq, C* band, int64_t ldab, int64_t row0, int64_t col0,
-                      hipStream_t s, hipEvent_t done = nullptr, hipEvent_t start = nullptr);
+                      hipStream_t s, hipEvent_t done = nullptr, hipEvent_t start = nullptr,
+                      int* out_flags = nullptr, int flag_base = 0);
 template <typename C> int panel_blk_rows();
+// Y = V T for every domain of a level (T: nb x nb per domain)
+template <typename C>
+void launch_panel_y_nb(int nb, const C* V, C* Y, const C* Tws, int64_t ldp, int64_t rows, int g, hipStream_t s);
+
+// Every tree level above the first in one launch that runs beside the first level's kernel
+// (launch_panel_blk with out_flags): a domain hands its R to the level above 16 rows at a time, as
+// its block steps complete, and the level above follows one block step behind.
+template <typename C> struct PanelTreeLevel {
+    C* P; C* Tws; C* Pnext;   // the level's panel (stacked R factors, V on return), its T factors, the next level's panel
+    int64_t ldp, ldnext;
+    int chunks;               // nb-row factors stacked at this level
+    int tiles;                // 16-row tiles of its tallest domain
+    int first;                // ticket of its first domain
+    int flags_in, flags_out;  // offsets of the flags of the level below / of this level
+};
+template <typename C> struct PanelTreeArgs {
+    PanelTreeLevel<C> lv[kMaxLevels];
+    int nl, total, g, lq;     // levels in this launch, workgroups, chunks per domain, orientation
+    int* ticket;              // zero on entry
+    int* flags;
+    int* err;
+    int flag_base, spin_limit;
+    C* band; int64_t ldab, row0, col0;   // where the last level's R goes
+};
+template <typename C>
+void launch_panel_tree(int nb, const PanelTreeArgs<C>& a, hipStream_t s, hipEvent_t start, hipEvent_t done);
+void launch_fill_int(int* p, int n, int v, hipStream_t s);
+template <typename C> void launch_tree_err(const int* err, C* band_entry, hipStream_t s);
 // does the blocked kernel serve this (type, nb, chunks per domain)?  Then the first level needs no
 // gathered copy of its panel and the last level no separate scatter of R.
 template <typename C> bool panel_blk_serves(int nb, int g);

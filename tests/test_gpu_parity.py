@@ -100,12 +100,13 @@ def _variant_case(name, n, nb):
     return _VARIANT_CASES[(name, n, nb)]
 
 
-@pytest.mark.parametrize("env", [{"SVB_PIPELINE_LAYOUT": "0"}, {"SVB_UPDATE_T": "0"}, {"SVB_EXT_EVENTS": "0"},
-                                 {"PROFILE": "1"}])
+@pytest.mark.parametrize("env", [{"SVB_PIPELINE_LAYOUT": "0"}, {"SVB_PIPELINE_LAYOUT": "1"}, {"SVB_UPDATE_T": "0"},
+                                 {"SVB_EXT_EVENTS": "0"}, {"PROFILE": "1"}])
 @pytest.mark.parametrize("name,n,nb", [("c4", 1152, 64), ("c5b", 768, 128), ("c3b", 1024, 32)])
 def test_stage1_driver_variants(monkeypatch, env, name, n, nb):
-    # variants of the level pipeline kept beside the default (every update on the side stream,
-    # Y = V T instead of T in the update, level events recorded behind the kernels), and the default
+    # variants of the level pipeline kept beside the default (one launch per tree level with every
+    # update on the side stream, or with the last one on the main stream; Y = V T instead of T in
+    # the update, level events recorded behind the kernels), and the default
     # with the library's per-kernel events on: same singular values
     for k, v in env.items():
         if k != "PROFILE":
@@ -260,6 +261,25 @@ def test_stage2_expired_wait_is_reported(monkeypatch):
     torch.cuda.synchronize()
     assert rc == 6
     monkeypatch.delenv("SVB_CHASE_SPIN")
+    s = _gpu_sigma(a, nb)
+    _check(s, oracle.svdvals(a), n, "f64")
+
+
+def test_panel_tree_expired_wait_is_reported(monkeypatch):
+    # The levels of a panel tree above the first run beside the first level and wait for its
+    # block steps.  A spin limit of zero makes every wait that is not met at once expire: the
+    # kernels still exit normally and the failure surfaces as a status code.
+    monkeypatch.setenv("SVB_TREE_SPIN", "0")
+    n, nb = 1024, 32
+    a, info = workloads.make("c1", n=n, nb=nb)
+    t = _dev(a)
+    rc, wbytes, _ = svb.svb_workspace_bytes(svb.SVB_F64, n, n, nb)
+    work = torch.empty(wbytes, dtype=torch.uint8, device="cuda")
+    out = np.zeros(n)
+    rc = svb.svb_svdvals(svb.SVB_F64, n, n, t, n, out, nb, work, wbytes)
+    torch.cuda.synchronize()
+    assert rc == 6
+    monkeypatch.delenv("SVB_TREE_SPIN")
     s = _gpu_sigma(a, nb)
     _check(s, oracle.svdvals(a), n, "f64")
 
