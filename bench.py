@@ -90,6 +90,8 @@ def run_workload(args, svb, torch, workloads, config, steps, warmup):
     Returns the measurements of one workload as a dict."""
     a0, info = device_matrix(config, torch, args.gaussian_input, args.n if config == args.config else None)
     n, nb, dtype = info["n"], info["nb"], info["dtype"]
+    if args.nb >= 0 and config == args.config:
+        nb = args.nb if args.nb > 0 else svb.svb_choose_nb(svb.dtype_code(a0.dtype), n, n)
     dt_code = svb.dtype_code(a0.dtype)
     rc, wbytes, _ = svb.svb_workspace_bytes(dt_code, n, n, nb)
     assert rc == 0, svb.svb_status_string(rc)
@@ -280,6 +282,8 @@ def main():
     ap.add_argument("--n", type=int, default=0,
                     help="profiling aid: the workload's recipe at another order n (a multiple of its nb); "
                          "the workload line shows the order used")
+    ap.add_argument("--nb", type=int, default=-1,
+                    help="profiling aid: tile size instead of the workload's (0: the library chooses)")
     ap.add_argument("--lda-pad", type=int, default=0,
                     help="leading dimension of the matrix handed to the library = n + this many elements")
     ap.add_argument("--gaussian-input", action="store_true",

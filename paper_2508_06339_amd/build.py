@@ -11,7 +11,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsvb.so")
-SOURCES = ["svb_api.hip", "stage0_prep.hip", "stage1_panel.hip", "stage1_panel_blk.hip", "stage1_fused.hip", "stage1_fused32.hip", "stage2_chase.hip", "stage2_narrow.hip", "stage2_reduce.hip", "stage3_device.hip",
+SOURCES = ["svb_api.hip", "stage0_prep.hip", "stage1_panel.hip", "stage1_panel_blk.hip", "stage1_fused.hip", "stage1_fused32.hip", "stage1_fused16.hip", "stage2_chase.hip", "stage2_narrow.hip", "stage2_reduce.hip", "stage3_device.hip",
            "stage3_host.cpp"]
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",
          # hipcc -O3 forms packed-fp32 instructions by itself; keep them off

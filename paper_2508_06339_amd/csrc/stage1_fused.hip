@@ -368,9 +368,17 @@ template int fused_update_rows<double>();
 template <typename T, typename C>
 void launch_update_fused(int nb, bool lq, T* Cb, int64_t lda, int64_t qlen, const C* V, const C* Y,
                          int64_t ldp, int chunks, int g, int64_t stride, bool tri, const C* Tw,
-                         bool credited, hipStream_t s)
+                         bool credited, hipStream_t s, bool half_ops)
 {
     if (qlen <= 0) return;
+    if constexpr (sizeof(T) == 2) {
+        // f16 / bf16 storage: both products on the 16-bit matrix instructions (half_ops = false keeps
+        // the f32-operand kernels below)
+        if (half_ops && g * nb <= 512) {
+            launch_update_fused16<T>(nb, lq, Cb, lda, qlen, V, Y, ldp, chunks, g, stride, tri, Tw, credited, s);
+            return;
+        }
+    }
     if constexpr (sizeof(C) == 4) {
         // nb = 128: the kernel built on the 32 x 32 x 2 instruction (SVB_UPDATE_MFMA32=0 keeps this file's)
         static const bool wide = env_int("SVB_UPDATE_MFMA32", 1) != 0;
@@ -398,9 +406,9 @@ void launch_update_fused(int nb, bool lq, T* Cb, int64_t lda, int64_t qlen, cons
 #undef SVB_FUSED_ARGS
 }
 
-template void launch_update_fused<float, float>(int, bool, float*, int64_t, int64_t, const float*, const float*, int64_t, int, int, int64_t, bool, const float*, bool, hipStream_t);
-template void launch_update_fused<__half, float>(int, bool, __half*, int64_t, int64_t, const float*, const float*, int64_t, int, int, int64_t, bool, const float*, bool, hipStream_t);
-template void launch_update_fused<bf16_t, float>(int, bool, bf16_t*, int64_t, int64_t, const float*, const float*, int64_t, int, int, int64_t, bool, const float*, bool, hipStream_t);
-template void launch_update_fused<double, double>(int, bool, double*, int64_t, int64_t, const double*, const double*, int64_t, int, int, int64_t, bool, const double*, bool, hipStream_t);
+template void launch_update_fused<float, float>(int, bool, float*, int64_t, int64_t, const float*, const float*, int64_t, int, int, int64_t, bool, const float*, bool, hipStream_t, bool);
+template void launch_update_fused<__half, float>(int, bool, __half*, int64_t, int64_t, const float*, const float*, int64_t, int, int, int64_t, bool, const float*, bool, hipStream_t, bool);
+template void launch_update_fused<bf16_t, float>(int, bool, bf16_t*, int64_t, int64_t, const float*, const float*, int64_t, int, int, int64_t, bool, const float*, bool, hipStream_t, bool);
+template void launch_update_fused<double, double>(int, bool, double*, int64_t, int64_t, const double*, const double*, int64_t, int, int, int64_t, bool, const double*, bool, hipStream_t, bool);
 
 }  // namespace svb

@@ -147,13 +147,14 @@ bool aligned_for_vectors(const void* A, int64_t lda, svb_dtype dt)
 // Environment switches, read once per process (they select kernel variants kept for testing and
 // measurement; the launch loops consult this copy).
 struct Switches {
-    int domain_chunks, pipeline_layout, tree_spin, ext_events, update_t, event_fence, stage3_host, stage3_relative, no_scale;
+    int domain_chunks, pipeline_layout, tree_spin, update_h16, ext_events, update_t, event_fence, stage3_host, stage3_relative, no_scale;
     bool loaded = false;
     void load()
     {
         domain_chunks = env_int("SVB_DOMAIN_CHUNKS", 0);
         pipeline_layout = env_int("SVB_PIPELINE_LAYOUT", 2);
         tree_spin = env_int("SVB_TREE_SPIN", 1 << 22);
+        update_h16 = env_int("SVB_UPDATE_H16", 1);
         ext_events = env_int("SVB_EXT_EVENTS", 1);
         update_t = env_int("SVB_UPDATE_T", 1);
         event_fence = env_int("SVB_EVENT_FENCE", 0);
@@ -451,7 +452,7 @@ int ge2gb_pipeline(int64_t rows, int64_t cols, T* A, int64_t lda, int nb, C* ban
             auto update = [&](int L, hipStream_t st) {
                 launch_update_fused<T, C>(nb, lq, Cb, lda, qlen, Vb + lv[L].poff, Yb + lv[L].poff, lv[L].ldp,
                                           lv[L].chunks, g, lv[L].stride, L > 0,
-                                          useT ? Tb + toff[L] : (const C*)nullptr, L == 0, st);
+                                          useT ? Tb + toff[L] : (const C*)nullptr, L == 0, st, sw.update_h16 != 0);
             };
             if (layout == 2 && direct && nl > 1 && tsum <= (int64_t)cv.t_elems) {
                 // Tree in two launches that run side by side: the first level on the main stream, every

@@ -146,13 +146,20 @@ void launch_band_clear(C* band, int64_t ldab, int64_t n, hipStream_t s);
 template <typename T, typename C>
 void launch_update_fused(int nb, bool lq, T* Cbase, int64_t lda, int64_t qlen, const C* V, const C* Y,
                          int64_t ldp, int chunks, int g, int64_t stride, bool tri, const C* Tw,
-                         bool credited, hipStream_t s);
+                         bool credited, hipStream_t s, bool half_ops = true);
 template <typename C> int fused_update_rows();
 // the same update for nb = 128 in f32 arithmetic on the 32 x 32 x 2 MFMA (domains of at most 512
 // rows, qlen a multiple of 32)
 template <typename T>
 void launch_update_fused32(bool lq, T* Cbase, int64_t lda, int64_t qlen, const float* V, const float* Y,
                            int64_t ldp, int chunks, int g, int64_t stride, bool tri, bool credited, hipStream_t s);
+
+// the same update for f16 / bf16 storage with both products on the 16-bit matrix instructions (f32
+// accumulate; V, Y and W enter as sums of 16-bit terms), domains of at most 512 rows
+template <typename T>
+void launch_update_fused16(int nb, bool lq, T* Cbase, int64_t lda, int64_t qlen, const float* V, const float* Y,
+                           int64_t ldp, int chunks, int g, int64_t stride, bool tri, const float* Tw, bool credited,
+                           hipStream_t s);
 
 // per-kernel timing hooks (no-ops unless profiling is enabled)
 void prof_begin(int kind, hipStream_t s, double flops, double bytes);

@@ -101,7 +101,7 @@ def _variant_case(name, n, nb):
 
 
 @pytest.mark.parametrize("env", [{"SVB_PIPELINE_LAYOUT": "0"}, {"SVB_PIPELINE_LAYOUT": "1"}, {"SVB_UPDATE_T": "0"},
-                                 {"SVB_EXT_EVENTS": "0"}, {"PROFILE": "1"}])
+                                 {"SVB_UPDATE_H16": "0"}, {"SVB_EXT_EVENTS": "0"}, {"PROFILE": "1"}])
 @pytest.mark.parametrize("name,n,nb", [("c4", 1152, 64), ("c5b", 768, 128), ("c3b", 1024, 32)])
 def test_stage1_driver_variants(monkeypatch, env, name, n, nb):
     # variants of the level pipeline kept beside the default (one launch per tree level with every
@@ -444,6 +444,30 @@ def test_bf16_storage():
     ref = oracle.svdvals(a)
     assert np.abs(s - ref).max() <= 10 * n * 2.0 ** -8 * ref[0]
     assert np.linalg.norm(s - ref) / np.linalg.norm(ref) <= 5e-2
+
+
+@pytest.mark.parametrize("n,nb", [(768, 32), (1152, 64), (1536, 128)])
+@pytest.mark.parametrize("tdt", ["f16", "bf16"])
+def test_half_storage_on_16bit_matrix_instructions(monkeypatch, tdt, n, nb):
+    # f16 / bf16 storage: the trailing update runs on the 16-bit matrix instructions with V, Y and W
+    # split into 16-bit terms.  Several tree levels at every tile size; compared with the oracle on
+    # the rounded matrix, and with the f32-operand kernels, whose error it must not exceed by much.
+    torch_dt, eps, gate = (torch.float16, 2.0 ** -10, 2e-2) if tdt == "f16" else (torch.bfloat16, 2.0 ** -8, 5e-2)
+    a32, info = workloads.make("c3b", n=n, nb=nb)
+    t = torch.from_numpy(np.ascontiguousarray(a32.astype(np.float32).T)).to(torch_dt)
+    a = np.asfortranarray(t.to(torch.float64).numpy().T)          # the rounded matrix, as the library sees it
+    ref = oracle.svdvals(a)
+    rc, s, _ = _svdvals_general(a, nb, dtype=torch_dt)
+    assert rc == 0
+    assert np.abs(s - ref).max() <= 10 * n * eps * ref[0]
+    rel = np.linalg.norm(s - ref) / np.linalg.norm(ref)
+    assert rel <= gate
+    monkeypatch.setenv("SVB_UPDATE_H16", "0")
+    rc, s32, _ = _svdvals_general(a, nb, dtype=torch_dt)
+    assert rc == 0
+    rel32 = np.linalg.norm(s32 - ref) / np.linalg.norm(ref)
+    print(f"[half] {tdt} n={n} nb={nb}: rel. error {rel:.3e} (16-bit operands) {rel32:.3e} (f32 operands)", flush=True)
+    assert rel <= 1.5 * rel32 + 1e-6
 
 
 @pytest.mark.parametrize("dtype,expo", [("f32", 60), ("f32", -60), ("f32", 100), ("f64", 500), ("f64", -500),
