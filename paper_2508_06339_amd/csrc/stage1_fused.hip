@@ -33,7 +33,9 @@ template <typename C, int NB> struct FusedGeom {
     // workgroup per compute unit (f64, nb = 128), so that a SIMD still has two waves to switch between
     static constexpr int NWV = (sizeof(C) == 8 && NB == 128) ? 8 : 4;
     static constexpr int NT = NWV * 64, SW = NWV * 16;   // threads, columns of a strip
-    static constexpr int RC = 32;                         // rows of Y / V per LDS slice
+    // rows of Y / V per LDS slice: every slice costs a fixed amount (its fetch, the wait for it, a
+    // barrier) that at 32 rows exceeds its matrix instructions; 64 rows where registers and LDS allow
+    static constexpr int RC = (sizeof(C) == 4 && NB == 64) ? 64 : 32;
     static constexpr int NV = Frag<C>::NV;
     static constexpr int MT = NB / 16;                    // 16-row tiles of W
     // row lengths chosen so that the operand fetches (16 lanes on 16 different rows) fall on
@@ -245,23 +247,24 @@ __global__ __launch_bounds__((FusedGeom<C, NB>::NT), (sizeof(C) == 8 && NB == 12
                         }
                     }
                 } else {
-                    // C_slice += V_slice (-W)
-                    static_assert(RC / 16 == 2, "two tiles per slice");
-                    const int t0 = ck * 2, t1 = ck * 2 + 1;
-                    const int rb0 = TRI ? (16 * t0 % NB) / 16 : 0, rb1 = TRI ? (16 * t1 % NB) / 16 : 0;
+                    // C_slice += V_slice (-W), two tiles at a time (independent chains of instructions)
+                    static_assert(RC % 32 == 0, "pairs of tiles");
 #pragma unroll
-                    for (int mt = 0; mt < MT; ++mt) {
-                        C a0[4], a1[4];
-                        if (mt >= rb0) F::ld4(&buf[i * LDC + 16 * mt], gq, a0);
-                        if (mt >= rb1) F::ld4(&buf[(16 + i) * LDC + 16 * mt], gq, a1);
+                    for (int tp = 0; tp < RC / 32; ++tp) {
+                        const int t0 = ck * (RC / 16) + 2 * tp, t1 = t0 + 1;
+                        const int rb0 = TRI ? (16 * t0 % NB) / 16 : 0, rb1 = TRI ? (16 * t1 % NB) / 16 : 0;
 #pragma unroll
-                        for (int r = 0; r < 4; ++r) {
-                            if (mt >= rb0) c[t0] = F::mma(a0[r], w[mt][r], c[t0]);
-                            if (mt >= rb1) c[t1] = F::mma(a1[r], w[mt][r], c[t1]);
+                        for (int mt = 0; mt < MT; ++mt) {
+                            C a0[4], a1[4];
+                            if (mt >= rb0) F::ld4(&buf[(32 * tp + i) * LDC + 16 * mt], gq, a0);
+                            if (mt >= rb1) F::ld4(&buf[(32 * tp + 16 + i) * LDC + 16 * mt], gq, a1);
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) {
+                                if (mt >= rb0) c[t0] = F::mma(a0[r], w[mt][r], c[t0]);
+                                if (mt >= rb1) c[t1] = F::mma(a1[r], w[mt][r], c[t1]);
+                            }
                         }
                     }
-                    frag_store<T, C, LQ>(Cb, lda, tile_p(t0), q, gq, c[t0]);
-                    frag_store<T, C, LQ>(Cb, lda, tile_p(t1), q, gq, c[t1]);
                 }
             }
             FT_MARK(isV ? 3 : 2);
@@ -270,6 +273,16 @@ __global__ __launch_bounds__((FusedGeom<C, NB>::NT), (sizeof(C) == 8 && NB == 12
                 if (nextT) tslice_st(nbuf);
                 else if (nextV) slice_st_v(nbuf);
                 else slice_st_y(nbuf);
+            }
+            // The finished tiles go back only now: loads and stores complete out of order with each
+            // other, so a wait for the next slice (above) that found stores in flight would be a
+            // wait for every one of them; issued here they have the whole next stage to complete.
+            if (isV && active) {
+#pragma unroll
+                for (int tt = 0; tt < RC / 16; ++tt) {
+                    const int t = ck * (RC / 16) + tt;
+                    frag_store<T, C, LQ>(Cb, lda, tile_p(t), q, gq, c[t]);
+                }
             }
             FT_MARK(4);
             lds_barrier();
