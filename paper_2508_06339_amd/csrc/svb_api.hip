@@ -467,13 +467,17 @@ int ge2gb_pipeline(int64_t rows, int64_t cols, T* A, int64_t lda, int nb, C* ban
                 const int base = (hs + 1) * 64;
                 (void)hipEventRecord(g_la.lvl[set][0], ms);   // behind the previous half-sweep's last update
                 (void)hipStreamWaitEvent(ss, g_la.lvl[set][0], 0);
+                hipEvent_t first_done = g_la.lvl[set][2];     // the first level's kernel is complete
                 {
                     hipEvent_t ea = nullptr, eb = nullptr;
                     const bool timed = prof_take(SVB_PROF_PANEL, 2.0 * (double)len * nb * nb, 0.0, &ea, &eb);
+                    if (timed) first_done = eb;
                     launch_panel_blk<T, C>(nb, Vb + lv[0].poff, lv[0].ldp, Tb + toff[0], lv[0].chunks, g,
                                            Vb + lv[0].poff + lv[0].ldp * nb, (int64_t)lv[0].domains * nb,
                                            A + row0 + col0 * lda, lda, lq, nullptr, ldab, row0, col0, ms,
-                                           timed ? eb : nullptr, ea, tree_flags + foff[0], base);
+                                           (timed || ext_events) ? first_done : nullptr, ea, tree_flags + foff[0], base,
+                                           tree_err + 1);
+                    if (!timed && !ext_events) (void)hipEventRecord(first_done, ms);
                     if (!useT)
                         launch_panel_y_nb<C>(nb, Vb + lv[0].poff, Yb + lv[0].poff, Tb + toff[0], lv[0].ldp,
                                              (int64_t)lv[0].chunks * nb, g, ms);
@@ -497,12 +501,18 @@ int ge2gb_pipeline(int64_t rows, int64_t cols, T* A, int64_t lda, int nb, C* ban
                 ta.nl = nl - 1; ta.total = first; ta.g = g; ta.lq = lq ? 1 : 0;
                 ta.ticket = tree_tickets + hs; ta.flags = tree_flags; ta.err = tree_err;
                 ta.flag_base = base; ta.spin_limit = sw.tree_spin;
+                ta.started = tree_err + 1; ta.wait_started = 1; ta.start_spin = 64;
                 ta.band = band; ta.ldab = ldab; ta.row0 = row0; ta.col0 = col0;
                 hipEvent_t ea = nullptr, eb = nullptr;
                 const bool timed = prof_take(SVB_PROF_PANEL, 0.0, 0.0, &ea, &eb);
-                const bool tied = useT && (timed || ext_events);   // the tree is the side stream's last kernel
-                hipEvent_t upper_done = timed ? eb : g_la.lvl[set][1];
-                launch_panel_tree<C>(nb, ta, ss, ea, (tied || timed) ? upper_done : nullptr);
+                launch_panel_tree<C>(nb, ta, ss, ea, timed ? eb : nullptr);
+                // second launch, behind the first level in stream order as well: factors what the first
+                // launch left undrawn because the first level's kernel was not running beside it
+                (void)hipStreamWaitEvent(ss, first_done, 0);
+                ta.wait_started = 0;
+                const bool tied = useT && ext_events;   // that launch is the side stream's last kernel
+                hipEvent_t upper_done = g_la.lvl[set][1];
+                launch_panel_tree<C>(nb, ta, ss, nullptr, tied ? upper_done : nullptr);
                 if (!useT)
                     for (int L = 1; L < nl; ++L)
                         launch_panel_y_nb<C>(nb, Vb + lv[L].poff, Yb + lv[L].poff, Tb + toff[L], lv[L].ldp,
