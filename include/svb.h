@@ -24,17 +24,22 @@
  *   - Return value: an svb_status.  On SVB_ERR_ARG / SVB_ERR_UNSUPPORTED /
  *     SVB_ERR_WORKSPACE nothing has been read or written.
  *   - dtype: SVB_F64, SVB_F32, and the storage-only types SVB_F16 / SVB_BF16
- *     (every product and sum is formed in f32, as the paper does for half
- *     precision, Section 4.3; the band, the bidiagonal and the result are f32).
+ *     (every sum is formed in f32, as the paper does for half precision,
+ *     Section 4.3; the trailing update multiplies on the 16-bit matrix
+ *     instructions with its f32 operands split into 16-bit terms, which keeps
+ *     f32 accuracy; the band, the bidiagonal and the result are f32).
  *   - nb (the paper's TILESIZE): 32, 64 or 128; 0 lets the library choose
  *     (svb_choose_nb).
  *   - Magnitudes: entries may be anywhere in the finite range of the storage
  *     type.  svb_svdvals multiplies the matrix by a power of two first when its
  *     largest magnitude lies outside [2^-40, 2^40] (f32 arithmetic) or
  *     [2^-400, 2^400] (f64), because the kernels form sums of squares without
- *     scaling them, and multiplies the bidiagonal back.  The stage-split entry
+ *     scaling them, and multiplies the bidiagonal back.  An SVB_F16 matrix is
+ *     scaled so that max|a| sqrt(m n) is about 2^11: the transformed matrix is
+ *     written back in f16, where an entry can reach a column's norm.  The stage-split entry
  *     points svb_ge2gb / svb_gb2bd do not rescale: their inputs must keep
- *     sums of squares of n entries inside the arithmetic type's range.
+ *     sums of squares of n entries inside the arithmetic type's range (and an
+ *     SVB_F16 matrix its Frobenius norm below 2^13).
  *     A NaN or an infinity in the input gives SVB_ERR_NONFINITE.
  *   - Calls that share a workspace, a matrix or a stream must not overlap, and
  *     calls into the library from different host threads must not overlap at

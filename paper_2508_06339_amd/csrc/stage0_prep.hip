@@ -77,7 +77,7 @@ template <> struct ScaleRange<double> { static constexpr int kExp = 400; };
 template <typename T>
 __global__ __launch_bounds__(256) void scale_kernel(T* __restrict__ A, int64_t lda, int64_t m, int64_t n,
                                                     const double* __restrict__ partial, int nparts,
-                                                    double* __restrict__ factors)
+                                                    double* __restrict__ factors, int lo_exp, int hi_exp, int target_exp)
 {
     __shared__ double red[4];
     __shared__ double sh_f;
@@ -92,7 +92,7 @@ __global__ __launch_bounds__(256) void scale_kernel(T* __restrict__ A, int64_t l
         if (v == v && v > 0.0) {
             int ex;
             (void)frexp(v, &ex);                       // v = frac * 2^ex, frac in [0.5, 1)
-            if (ex > ScaleRange<T>::kExp || ex < -ScaleRange<T>::kExp) f = ldexp(1.0, -ex);
+            if (ex > hi_exp || ex < lo_exp) f = ldexp(1.0, target_exp - ex);
         }
         sh_f = f;
         if (blockIdx.x == 0) {
@@ -137,12 +137,19 @@ void launch_stage_copy(const T* A, int64_t lda, int64_t m, int64_t n, bool trans
 
 // factors: 8 doubles, followed by kScanBlocks partial maxima
 template <typename T>
-void launch_scale_to_range(T* A, int64_t lda, int64_t m, int64_t n, double* factors, hipStream_t s)
+void launch_scale_to_range(T* A, int64_t lda, int64_t m, int64_t n, double* factors, hipStream_t s, int lo_exp,
+                           int hi_exp, int target_exp)
 {
     const int blocks = (int)(n < kScanBlocks ? (n < 1 ? 1 : n) : kScanBlocks);
     double* partial = factors + 8;
     hipLaunchKernelGGL((absmax_kernel<T>), dim3(blocks), dim3(256), 0, s, A, lda, m, n, partial);
-    hipLaunchKernelGGL((scale_kernel<T>), dim3(blocks), dim3(256), 0, s, A, lda, m, n, partial, blocks, factors);
+    hipLaunchKernelGGL((scale_kernel<T>), dim3(blocks), dim3(256), 0, s, A, lda, m, n, partial, blocks, factors, lo_exp,
+                       hi_exp, target_exp);
+}
+template <typename T>
+void launch_scale_to_range(T* A, int64_t lda, int64_t m, int64_t n, double* factors, hipStream_t s)
+{
+    launch_scale_to_range<T>(A, lda, m, n, factors, s, -ScaleRange<T>::kExp, ScaleRange<T>::kExp, 0);
 }
 
 size_t scale_workspace_bytes() { return (size_t)(8 + kScanBlocks) * sizeof(double); }
@@ -159,7 +166,8 @@ void launch_rescale_bidiag(C* d, C* e, int64_t n, const double* factors, hipStre
 #define SVB_PREP_INST(T)                                                                                            \
     template void launch_stage_copy<T>(const T*, int64_t, int64_t, int64_t, bool, T*, int64_t, int64_t, int64_t, \
                                        hipStream_t);                                                                \
-    template void launch_scale_to_range<T>(T*, int64_t, int64_t, int64_t, double*, hipStream_t);
+    template void launch_scale_to_range<T>(T*, int64_t, int64_t, int64_t, double*, hipStream_t);                   \
+    template void launch_scale_to_range<T>(T*, int64_t, int64_t, int64_t, double*, hipStream_t, int, int, int);
 SVB_PREP_INST(double)
 SVB_PREP_INST(float)
 SVB_PREP_INST(__half)

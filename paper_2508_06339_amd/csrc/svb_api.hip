@@ -607,7 +607,18 @@ void scale_dispatch(svb_dtype dt, void* A, int64_t lda, int64_t rows, int64_t co
     case SVB_F64: launch_scale_to_range<double>((double*)A, lda, rows, cols, factors, s); break;
     case SVB_F32: launch_scale_to_range<float>((float*)A, lda, rows, cols, factors, s); break;
     case SVB_BF16: launch_scale_to_range<bf16_t>((bf16_t*)A, lda, rows, cols, factors, s); break;
-    default: break;   // every finite f16 value lies inside the range that needs no scaling
+    default: {
+        // f16 storage: the transformed matrix is written back in f16, and an entry of it can be as
+        // large as a column's norm; the update's products W = Y^T C, bounded by a small multiple of
+        // the Frobenius norm, are split into f16 terms as well.  So max|a| sqrt(rows cols) is
+        // brought to about 2^11 (f16 holds 2^16; entries below 2^-24 of that flush to zero, far
+        // below the storage type's rounding of the entries beside them)
+        int e2 = 0;
+        (void)std::frexp(std::sqrt((double)rows * (double)cols), &e2);   // sqrt(rows cols) <= 2^e2
+        const int hi = 13 - e2;
+        launch_scale_to_range<__half>((__half*)A, lda, rows, cols, factors, s, hi - 8, hi, hi - 2);
+        break;
+    }
     }
 }
 
@@ -779,7 +790,7 @@ int svb_svdvals(svb_dtype dt, int64_t m, int64_t n, void* A_dev, int64_t lda, vo
     const int64_t ldab = 3 * (int64_t)nb;
     const int64_t k = sh.k;
     const svb_dtype bdt = dt == SVB_F64 ? SVB_F64 : SVB_F32;
-    const bool scaled = dt != SVB_F16 && !sw.no_scale;
+    const bool scaled = !sw.no_scale;
 
     hipEvent_t* ev = g_la.stage;
     (void)hipEventRecord(ev[0], s);

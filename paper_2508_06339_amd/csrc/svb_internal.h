@@ -182,6 +182,11 @@ void launch_stage_copy(const T* A, int64_t lda, int64_t m, int64_t n, bool trans
 // matrix is multiplied by factors[0] where that is not 1
 template <typename T>
 void launch_scale_to_range(T* A, int64_t lda, int64_t m, int64_t n, double* factors, hipStream_t s);
+// the same with the window given: scaled when the largest magnitude's binary exponent lies outside
+// [lo_exp, hi_exp], so that it becomes target_exp
+template <typename T>
+void launch_scale_to_range(T* A, int64_t lda, int64_t m, int64_t n, double* factors, hipStream_t s, int lo_exp,
+                           int hi_exp, int target_exp);
 size_t scale_workspace_bytes();   // bytes behind `factors` (the factors and the scan's partial maxima)
 // d, e (n entries each) multiplied by factors[1]
 template <typename C>

@@ -470,6 +470,28 @@ def test_half_storage_on_16bit_matrix_instructions(monkeypatch, tdt, n, nb):
     assert rel <= 1.5 * rel32 + 1e-6
 
 
+@pytest.mark.parametrize("kind", ["large", "small", "tiny"])
+def test_badly_scaled_f16_input(kind):
+    # f16 entries near the ends of the type's range.  The update's f16 operand terms would overflow
+    # (W = Y^T C grows with the norms of the columns: here a rank-one part whose columns have norms
+    # beyond 65504 while every entry is representable) or lose their low parts (entries near the
+    # smallest normal f16 number) without the scaling in front of stage 1.
+    n, nb = 512, 64
+    g = workloads.gaussian_matrix(78, n, n).astype(np.float64)
+    if kind == "large":
+        u, v = g[:, 0], g[0, :]
+        a64 = np.ldexp(np.outer(u, v), 11) + 4.0 * workloads.gaussian_matrix(79, n, n)
+    else:
+        a64 = np.ldexp(g, -9 if kind == "small" else -13)
+    a = np.asfortranarray(a64.astype(np.float16))
+    assert np.all(np.isfinite(a))
+    rc, s, _ = _svdvals_general(a, nb)
+    assert rc == 0, svb.svb_status_string(rc)
+    ref = oracle.svdvals(a.astype(np.float64))
+    assert np.abs(s - ref).max() <= 10 * n * 2.0 ** -10 * ref[0]
+    assert np.linalg.norm(s - ref) / np.linalg.norm(ref) <= 2e-2
+
+
 @pytest.mark.parametrize("dtype,expo", [("f32", 60), ("f32", -60), ("f32", 100), ("f64", 500), ("f64", -500),
                                          ("f32", 0)])
 def test_badly_scaled_input(dtype, expo):
