@@ -558,47 +558,20 @@ template <typename T, typename C, int NB, int HT, bool TRI>
 __global__ __launch_bounds__(NB * 4) void panel_qr_blk_kernel(C* __restrict__ P, int64_t ldp,
                                                               C* __restrict__ Tws, int chunks, int g,
                                                               C* __restrict__ Pnext, int64_t ldnext,
-                                                              PanelEnds<T, C> ends, int* out_flags, int flag_base,
-                                                              int* started)
+                                                              PanelEnds<T, C> ends, int* out_flags, int flag_base)
 {
     const int d = blockIdx.x;
-    // tells the launch of the levels above that this one is on the machine (see panel_tree_kernel)
-    if (started && threadIdx.x == 0) flag_st(started, flag_base);
     const TreeSync sy{nullptr, out_flags ? out_flags + d : nullptr, flag_base, 0, nullptr};
     panel_blk_body<T, C, NB, HT, TRI, false>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, d, sy);
 }
 
-// Every tree level above the first in one launch, running beside the first level's kernel.  A
-// workgroup draws a ticket; tickets are numbered level by level, so the domains a workgroup waits
-// for hold smaller tickets and are already running or done.
-// The launch must not occupy the machine while the first level's kernel cannot run (a tool that
-// lets one kernel execute at a time would otherwise leave these workgroups waiting for flags that
-// never move): with wait_started a workgroup draws a ticket only once the first level's kernel has
-// announced itself, and leaves at once if that does not happen within a few polls.  Whatever is
-// left undrawn is factored by a second launch of this kernel that follows both in stream order
-// (wait_started = 0; normally it finds every ticket drawn and returns).
+// One domain of a tree level above the first: ticket tk of the upper levels' launch (tickets are
+// numbered level by level, so the domains a workgroup waits for hold smaller tickets and are
+// already running or done).
 template <typename C, int NB>
-__global__ __launch_bounds__(NB * 4) void panel_tree_kernel(PanelTreeArgs<C> a)
+__device__ __forceinline__ void panel_tree_item(const PanelTreeArgs<C>& a, const int tk)
 {
     constexpr int HT = panel_blk_tiles<C>();
-    __shared__ int sh_ticket;
-    if (threadIdx.x == 0) {
-        bool go = true;
-        if (a.wait_started) {
-            int spins = 0;
-            while (flag_ld(a.started) < a.flag_base) {
-                if (++spins > a.start_spin) {
-                    go = false;
-                    break;
-                }
-                __builtin_amdgcn_s_sleep(8);
-            }
-        }
-        sh_ticket = go ? atomicAdd(a.ticket, 1) : a.total;
-    }
-    __syncthreads();
-    const int tk = sh_ticket;
-    if (tk >= a.total) return;
     int L = 0;
     while (L + 1 < a.nl && tk >= a.lv[L + 1].first) ++L;
     const PanelTreeLevel<C>& lv = a.lv[L];
@@ -622,6 +595,62 @@ __global__ __launch_bounds__(NB * 4) void panel_tree_kernel(PanelTreeArgs<C> a)
         }
     }
     panel_blk_body<C, C, NB, HT, true, true>(lv.P, lv.ldp, lv.Tws, lv.chunks, a.g, lv.Pnext, lv.ldnext, ends, d, sy);
+}
+
+// Every tree level above the first in one launch, running beside the first level's kernel, one
+// ticket per workgroup.
+// The launch must not occupy the machine while the first level's kernel cannot run (a tool that
+// lets one kernel execute at a time would otherwise leave these workgroups waiting for flags that
+// never move): a workgroup draws its ticket only once the first level's kernel has announced
+// itself, and leaves without one if that does not happen within start_spin polls.  Tickets left
+// undrawn are taken by the workgroups of the first level's kernel when they are done with their
+// own domains (panel_first_kernel), so the tree is complete when that kernel is, whichever of the
+// two launches ran first.
+template <typename C, int NB>
+__global__ __launch_bounds__(NB * 4) void panel_tree_kernel(PanelTreeArgs<C> a)
+{
+    __shared__ int sh_ticket;
+    if (threadIdx.x == 0) {
+        bool go = true;
+        int spins = 0;
+        while (flag_ld(a.started) < a.flag_base) {
+            if (++spins > a.start_spin) {
+                go = false;
+                break;
+            }
+            __builtin_amdgcn_s_sleep(8);
+        }
+        sh_ticket = go ? atomicAdd(a.ticket, 1) : a.total;
+    }
+    __syncthreads();
+    const int tk = sh_ticket;
+    if (tk >= a.total) return;
+    panel_tree_item<C, NB>(a, tk);
+}
+
+// The first tree level of a tree whose upper levels run in panel_tree_kernel beside it: workgroup
+// d announces the kernel, factors domain d of the panel read straight from the matrix, handing
+// its R over block step by block step, and then takes whatever tickets of the upper levels are
+// still undrawn (none, unless the other launch could not run beside this one).
+template <typename T, typename C, int NB>
+__global__ __launch_bounds__(NB * 4) void panel_first_kernel(C* __restrict__ P, int64_t ldp, C* __restrict__ Tws,
+                                                             int chunks, C* __restrict__ Pnext, int64_t ldnext,
+                                                             PanelEnds<T, C> ends, int* out_flags, PanelTreeArgs<C> a)
+{
+    constexpr int HT = panel_blk_tiles<C>();
+    __shared__ int sh_ticket;
+    const int d = blockIdx.x;
+    if (threadIdx.x == 0) flag_st(a.started, a.flag_base);
+    const TreeSync sy{nullptr, out_flags + d, a.flag_base, 0, nullptr};
+    panel_blk_body<T, C, NB, HT, false, false>(P, ldp, Tws, chunks, a.g, Pnext, ldnext, ends, d, sy);
+    for (;;) {
+        __syncthreads();
+        if (threadIdx.x == 0) sh_ticket = flag_ld(a.ticket) < a.total ? atomicAdd(a.ticket, 1) : a.total;
+        __syncthreads();
+        const int tk = sh_ticket;
+        if (tk >= a.total) break;
+        panel_tree_item<C, NB>(a, tk);
+    }
 }
 
 __global__ void fill_int_kernel(int* p, int n, int v)
@@ -677,7 +706,7 @@ template void launch_panel_tree<double>(int, const PanelTreeArgs<double>&, hipSt
 
 template <typename T, typename C, int NB, int HT, bool TRI>
 static void launch_blk_ht(C* P, int64_t ldp, C* Tws, int chunks, int g, C* Pnext, int64_t ldnext,
-                          const PanelEnds<T, C>& ends, int* out_flags, int flag_base, int* started, hipStream_t s,
+                          const PanelEnds<T, C>& ends, int* out_flags, int flag_base, hipStream_t s,
                           hipEvent_t done, hipEvent_t start)
 {
     using G = PanelBlkGeom<C, NB, HT>;
@@ -693,57 +722,77 @@ static void launch_blk_ht(C* P, int64_t ldp, C* Tws, int chunks, int g, C* Pnext
     // marker in the stream between this kernel and the next one
     if (done)
         hipExtLaunchKernelGGL(kern, dim3(domains), dim3(G::NT), (uint32_t)G::kSmemBytes, s, start, done, 0u, P, ldp,
-                              Tws, chunks, g, Pnext, ldnext, ends, out_flags, flag_base, started);
+                              Tws, chunks, g, Pnext, ldnext, ends, out_flags, flag_base);
     else
         hipLaunchKernelGGL(kern, dim3(domains), dim3(G::NT), G::kSmemBytes, s, P, ldp, Tws, chunks, g, Pnext, ldnext,
-                           ends, out_flags, flag_base, started);
+                           ends, out_flags, flag_base);
 }
 
 template <typename T, typename C, int NB>
 static void launch_blk(C* P, int64_t ldp, C* Tws, int chunks, int g, C* Pnext, int64_t ldnext,
-                       const PanelEnds<T, C>& ends, int* out_flags, int flag_base, int* started, hipStream_t s,
-                       hipEvent_t done, hipEvent_t start)
+                       const PanelEnds<T, C>& ends, int* out_flags, int flag_base, const PanelTreeArgs<C>* tree,
+                       hipStream_t s, hipEvent_t done, hipEvent_t start)
 {
     constexpr int HT = panel_blk_tiles<C>();
+    if (ends.Asrc && tree) {
+        // first level of a tree whose upper levels run beside it
+        using G = PanelBlkGeom<C, NB, HT>;
+        auto kern = panel_first_kernel<T, C, NB>;
+        static bool attr_set = false;
+        if (!attr_set) {
+            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                      (int)G::kSmemBytes);
+            attr_set = true;
+        }
+        const int domains = (chunks + g - 1) / g;
+        if (done)
+            hipExtLaunchKernelGGL(kern, dim3(domains), dim3(G::NT), (uint32_t)G::kSmemBytes, s, start, done, 0u, P, ldp,
+                                  Tws, chunks, Pnext, ldnext, ends, out_flags, *tree);
+        else
+            hipLaunchKernelGGL(kern, dim3(domains), dim3(G::NT), G::kSmemBytes, s, P, ldp, Tws, chunks, Pnext, ldnext,
+                               ends, out_flags, *tree);
+        return;
+    }
     // a panel that does not come from the matrix is a stack of triangular factors; near the top of
     // the tree such a stack is short, and a kernel sized for it (fewer rows per thread in the
     // reflector steps, fewer tiles in the block products) is faster than the full-height one
     if (ends.Asrc) {
-        launch_blk_ht<T, C, NB, HT, false>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, out_flags, flag_base, started, s, done, start);
+        launch_blk_ht<T, C, NB, HT, false>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, out_flags, flag_base, s, done, start);
         return;
     }
     const int need = (chunks < g ? chunks : g) * NB / 16;   // tiles of the tallest domain
     if constexpr (HT / 4 * 16 >= NB) {
         if (need <= HT / 4) {
-            launch_blk_ht<T, C, NB, HT / 4, true>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, out_flags, flag_base, started, s, done, start);
+            launch_blk_ht<T, C, NB, HT / 4, true>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, out_flags, flag_base, s, done, start);
             return;
         }
     }
     if constexpr (HT / 2 * 16 >= NB) {
         if (need <= HT / 2) {
-            launch_blk_ht<T, C, NB, HT / 2, true>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, out_flags, flag_base, started, s, done, start);
+            launch_blk_ht<T, C, NB, HT / 2, true>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, out_flags, flag_base, s, done, start);
             return;
         }
     }
-    launch_blk_ht<T, C, NB, HT, true>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, out_flags, flag_base, started, s, done, start);
+    launch_blk_ht<T, C, NB, HT, true>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, out_flags, flag_base, s, done, start);
 }
 
 template <typename T, typename C>
 void launch_panel_blk(int nb, C* P, int64_t ldp, C* Tws, int chunks, int g, C* Pnext, int64_t ldnext,
                       const T* Asrc, int64_t lda, bool lq, C* band, int64_t ldab, int64_t row0, int64_t col0,
-                      hipStream_t s, hipEvent_t done, hipEvent_t start, int* out_flags, int flag_base, int* started)
+                      hipStream_t s, hipEvent_t done, hipEvent_t start, int* out_flags, int flag_base,
+                      const PanelTreeArgs<C>* tree)
 {
     const PanelEnds<T, C> ends{Asrc, lda, lq ? 1 : 0, band, ldab, row0, col0};
     switch (nb) {
-    case 32: launch_blk<T, C, 32>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, out_flags, flag_base, started, s, done, start); break;
-    case 64: launch_blk<T, C, 64>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, out_flags, flag_base, started, s, done, start); break;
-    default: launch_blk<T, C, 128>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, out_flags, flag_base, started, s, done, start); break;
+    case 32: launch_blk<T, C, 32>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, out_flags, flag_base, tree, s, done, start); break;
+    case 64: launch_blk<T, C, 64>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, out_flags, flag_base, tree, s, done, start); break;
+    default: launch_blk<T, C, 128>(P, ldp, Tws, chunks, g, Pnext, ldnext, ends, out_flags, flag_base, tree, s, done, start); break;
     }
 }
 
-template void launch_panel_blk<float, float>(int, float*, int64_t, float*, int, int, float*, int64_t, const float*, int64_t, bool, float*, int64_t, int64_t, int64_t, hipStream_t, hipEvent_t, hipEvent_t, int*, int, int*);
-template void launch_panel_blk<__half, float>(int, float*, int64_t, float*, int, int, float*, int64_t, const __half*, int64_t, bool, float*, int64_t, int64_t, int64_t, hipStream_t, hipEvent_t, hipEvent_t, int*, int, int*);
-template void launch_panel_blk<bf16_t, float>(int, float*, int64_t, float*, int, int, float*, int64_t, const bf16_t*, int64_t, bool, float*, int64_t, int64_t, int64_t, hipStream_t, hipEvent_t, hipEvent_t, int*, int, int*);
-template void launch_panel_blk<double, double>(int, double*, int64_t, double*, int, int, double*, int64_t, const double*, int64_t, bool, double*, int64_t, int64_t, int64_t, hipStream_t, hipEvent_t, hipEvent_t, int*, int, int*);
+template void launch_panel_blk<float, float>(int, float*, int64_t, float*, int, int, float*, int64_t, const float*, int64_t, bool, float*, int64_t, int64_t, int64_t, hipStream_t, hipEvent_t, hipEvent_t, int*, int, const PanelTreeArgs<float>*);
+template void launch_panel_blk<__half, float>(int, float*, int64_t, float*, int, int, float*, int64_t, const __half*, int64_t, bool, float*, int64_t, int64_t, int64_t, hipStream_t, hipEvent_t, hipEvent_t, int*, int, const PanelTreeArgs<float>*);
+template void launch_panel_blk<bf16_t, float>(int, float*, int64_t, float*, int, int, float*, int64_t, const bf16_t*, int64_t, bool, float*, int64_t, int64_t, int64_t, hipStream_t, hipEvent_t, hipEvent_t, int*, int, const PanelTreeArgs<float>*);
+template void launch_panel_blk<double, double>(int, double*, int64_t, double*, int, int, double*, int64_t, const double*, int64_t, bool, double*, int64_t, int64_t, int64_t, hipStream_t, hipEvent_t, hipEvent_t, int*, int, const PanelTreeArgs<double>*);
 
 }  // namespace svb

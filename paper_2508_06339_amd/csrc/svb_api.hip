@@ -467,21 +467,6 @@ int ge2gb_pipeline(int64_t rows, int64_t cols, T* A, int64_t lda, int nb, C* ban
                 const int base = (hs + 1) * 64;
                 (void)hipEventRecord(g_la.lvl[set][0], ms);   // behind the previous half-sweep's last update
                 (void)hipStreamWaitEvent(ss, g_la.lvl[set][0], 0);
-                hipEvent_t first_done = g_la.lvl[set][2];     // the first level's kernel is complete
-                {
-                    hipEvent_t ea = nullptr, eb = nullptr;
-                    const bool timed = prof_take(SVB_PROF_PANEL, 2.0 * (double)len * nb * nb, 0.0, &ea, &eb);
-                    if (timed) first_done = eb;
-                    launch_panel_blk<T, C>(nb, Vb + lv[0].poff, lv[0].ldp, Tb + toff[0], lv[0].chunks, g,
-                                           Vb + lv[0].poff + lv[0].ldp * nb, (int64_t)lv[0].domains * nb,
-                                           A + row0 + col0 * lda, lda, lq, nullptr, ldab, row0, col0, ms,
-                                           (timed || ext_events) ? first_done : nullptr, ea, tree_flags + foff[0], base,
-                                           tree_err + 1);
-                    if (!timed && !ext_events) (void)hipEventRecord(first_done, ms);
-                    if (!useT)
-                        launch_panel_y_nb<C>(nb, Vb + lv[0].poff, Yb + lv[0].poff, Tb + toff[0], lv[0].ldp,
-                                             (int64_t)lv[0].chunks * nb, g, ms);
-                }
                 PanelTreeArgs<C> ta{};
                 int first = 0;
                 for (int L = 1; L < nl; ++L) {
@@ -501,22 +486,38 @@ int ge2gb_pipeline(int64_t rows, int64_t cols, T* A, int64_t lda, int nb, C* ban
                 ta.nl = nl - 1; ta.total = first; ta.g = g; ta.lq = lq ? 1 : 0;
                 ta.ticket = tree_tickets + hs; ta.flags = tree_flags; ta.err = tree_err;
                 ta.flag_base = base; ta.spin_limit = sw.tree_spin;
-                ta.started = tree_err + 1; ta.wait_started = 1; ta.start_spin = 64;
+                // (a few milliseconds of polls before the upper levels' launch leaves its tickets to the
+                // first level's kernel: only a tool that runs one kernel at a time makes it wait that long)
+                ta.started = tree_err + 1; ta.start_spin = 4096;
                 ta.band = band; ta.ldab = ldab; ta.row0 = row0; ta.col0 = col0;
+                // the first level; where Y = V T is wanted its completion is an event (tied to the kernel)
+                // that the side stream's Y products wait for: the tree is complete when this kernel is
+                hipEvent_t first_done = nullptr;
+                {
+                    hipEvent_t ea = nullptr, eb = nullptr;
+                    const bool timed = prof_take(SVB_PROF_PANEL, 2.0 * (double)len * nb * nb, 0.0, &ea, &eb);
+                    if (timed) first_done = eb;
+                    else if (!useT) first_done = g_la.lvl[set][2];
+                    launch_panel_blk<T, C>(nb, Vb + lv[0].poff, lv[0].ldp, Tb + toff[0], lv[0].chunks, g,
+                                           Vb + lv[0].poff + lv[0].ldp * nb, (int64_t)lv[0].domains * nb,
+                                           A + row0 + col0 * lda, lda, lq, nullptr, ldab, row0, col0, ms,
+                                           (timed || ext_events) ? first_done : nullptr, ea, tree_flags + foff[0], base, &ta);
+                    if (first_done && !timed && !ext_events) (void)hipEventRecord(first_done, ms);
+                    if (!useT)
+                        launch_panel_y_nb<C>(nb, Vb + lv[0].poff, Yb + lv[0].poff, Tb + toff[0], lv[0].ldp,
+                                             (int64_t)lv[0].chunks * nb, g, ms);
+                }
                 hipEvent_t ea = nullptr, eb = nullptr;
                 const bool timed = prof_take(SVB_PROF_PANEL, 0.0, 0.0, &ea, &eb);
-                launch_panel_tree<C>(nb, ta, ss, ea, timed ? eb : nullptr);
-                // second launch, behind the first level in stream order as well: factors what the first
-                // launch left undrawn because the first level's kernel was not running beside it
-                (void)hipStreamWaitEvent(ss, first_done, 0);
-                ta.wait_started = 0;
-                const bool tied = useT && ext_events;   // that launch is the side stream's last kernel
-                hipEvent_t upper_done = g_la.lvl[set][1];
-                launch_panel_tree<C>(nb, ta, ss, nullptr, tied ? upper_done : nullptr);
-                if (!useT)
+                const bool tied = useT && (timed || ext_events);   // the tree is the side stream's last kernel
+                hipEvent_t upper_done = timed ? eb : g_la.lvl[set][1];
+                launch_panel_tree<C>(nb, ta, ss, ea, (tied || timed) ? upper_done : nullptr);
+                if (!useT) {
+                    (void)hipStreamWaitEvent(ss, first_done, 0);
                     for (int L = 1; L < nl; ++L)
                         launch_panel_y_nb<C>(nb, Vb + lv[L].poff, Yb + lv[L].poff, Tb + toff[L], lv[L].ldp,
                                              (int64_t)lv[L].chunks * nb, g, ss);
+                }
                 if (!tied) {
                     upper_done = g_la.lvl[set][1];
                     (void)hipEventRecord(upper_done, ss);

@@ -91,11 +91,13 @@ void launch_panel_qr(int nb, C* P, int64_t ldp, C* Y, C* Tws, int chunks, int g,
 // Asrc != nullptr: the panel is read straight from the matrix (Asrc = &A[row0, col0], QR / LQ
 // orientation) instead of the work panel P; band != nullptr: R goes straight into the packed band
 // (the last tree level) instead of Pnext.
+template <typename C> struct PanelTreeArgs;
+// tree (may be null, first level only): the upper levels run in launch_panel_tree beside this launch
 template <typename T, typename C>
 void launch_panel_blk(int nb, C* P, int64_t ldp, C* Tws, int chunks, int g, C* Pnext, int64_t ldnext,
                       const T* Asrc, int64_t lda, bool lq, C* band, int64_t ldab, int64_t row0, int64_t col0,
                       hipStream_t s, hipEvent_t done = nullptr, hipEvent_t start = nullptr,
-                      int* out_flags = nullptr, int flag_base = 0, int* started = nullptr);
+                      int* out_flags = nullptr, int flag_base = 0, const PanelTreeArgs<C>* tree = nullptr);
 template <typename C> int panel_blk_rows();
 // Y = V T for every domain of a level (T: nb x nb per domain)
 template <typename C>
@@ -120,7 +122,7 @@ template <typename C> struct PanelTreeArgs {
     int* err;
     int flag_base, spin_limit;
     int* started;             // set to flag_base by the first level's kernel when it begins
-    int wait_started, start_spin;   // draw tickets only once `started` is set, giving up after start_spin polls
+    int start_spin;           // polls of `started` after which the upper levels' launch leaves its tickets to that kernel
     C* band; int64_t ldab, row0, col0;   // where the last level's R goes
 };
 template <typename C>
