@@ -23,7 +23,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-PEAK_TFLOPS = {"f64": 78.6, "f32": 157.3, "f16": 157.3, "bf16": 157.3}   # MFMA peak of the arithmetic type used
+# dense MFMA peak of the operand type the trailing update multiplies in (f16 / bf16 storage: the
+# 16-bit matrix instructions, f32 accumulate)
+PEAK_TFLOPS = {"f64": 78.6, "f32": 157.3, "f16": 2500.0, "bf16": 2500.0}
 PEAK_HBM_GBS = 8000.0
 
 
@@ -202,7 +204,10 @@ def run_workload(args, svb, torch, workloads, config, steps, warmup):
         # MFMA-bound contraction: credited flops of its first-level launches (both products,
         # 4 rows nb cols per launch; 8/3 n^3 over a run) / their summed duration
         ach = upd["flops"] / upd["seconds"] / 1e12 if upd["seconds"] > 0 else 0.0
-        roofline = dict(kernel="update_fused_kernel (first tree level)", bound="mfma", achieved=ach, peak=peak,
+        kname = ("update_fused16_kernel" if dtype in ("f16", "bf16") else
+                 "update_fused32_kernel" if (dtype == "f32" and nb == 128) else "update_fused_kernel")
+        roofline = dict(kernel=kname + " (first tree level: the launches with TRI = false)", bound="mfma", achieved=ach,
+                        peak=peak,
                         unit="TFLOP/s", frac=ach / peak, traffic=None,
                         launches_per_step=upd["launches"] / steps,
                         avg_launch_ms=upd["seconds"] / max(upd["launches"], 1) * 1e3,
@@ -232,6 +237,10 @@ def run_workload(args, svb, torch, workloads, config, steps, warmup):
     roofline_update = dict(bound="mfma", achieved=upd["flops"] / upd["seconds"] / 1e12 if upd["seconds"] > 0 else 0.0,
                            peak=peak, unit="TFLOP/s")
     roofline_update["frac"] = roofline_update["achieved"] / peak
+    # the same launches against the HBM roofline by their algorithmic bytes (the block read once and
+    # written once): the bound that matters where the operands are 16 bits wide
+    roofline_update["algorithmic_gbs"] = upd["bytes"] / upd["seconds"] / 1e9 if upd["seconds"] > 0 else 0.0
+    roofline_update["hbm_frac"] = roofline_update["algorithmic_gbs"] / PEAK_HBM_GBS
     # stage 2: algorithmic bytes of the two kernels as built (every band block read once and written
     # once per block sweep; the narrow band once per bundle) over the stage's duration.  Both kernels
     # are dependency chains: the HBM roofline is not what limits them.
