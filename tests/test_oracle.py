@@ -1,6 +1,8 @@
 """Pins for the CPU oracle: every check compares it with something the paper
 or the mathematics fixes, never with itself."""
 import math
+import os
+import sys
 
 import numpy as np
 import pytest
@@ -266,3 +268,23 @@ def test_svdvals_config1_matches_library_and_golden():
     s = oracle.svdvals(a)
     ref = np.linalg.svd(np.asarray(a, dtype=np.float64), compute_uv=False)
     assert np.abs(s - ref).max() <= 10 * info["n"] * EPS * ref[0]
+    _against_stored("c1", a, s)
+
+
+def _against_stored(name, a, s):
+    # the stored oracle result of the same workload (tests/golden, written by make_oracle_sigma.py):
+    # the generator still produces the matrix the file was written for, and the oracle the same values
+    sys.path.insert(0, os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden"))
+    import make_oracle_sigma as golden
+    stored = golden.load(name)
+    assert stored is not None
+    sig, meta = stored
+    assert workloads.fingerprint_matches(meta["fingerprint"], workloads.fingerprint(a))
+    assert np.abs(s - sig).max() <= 1e-12 * sig[0]
+
+
+def test_svdvals_config2_matches_prescription_and_golden():
+    a, info = workloads.make("c2")
+    s = oracle.svdvals(a)
+    assert np.abs(s - info["sigma"]).max() <= 10 * info["n"] * 2.0 ** -23 * info["sigma"][0]
+    _against_stored("c2", a, s)
