@@ -55,6 +55,7 @@ def _check(s, ref, n, dtype, extra_fro=None):
     ("c2", 352, 32),
     ("c4", 640, 64),                                         # config 4's recipe, small
     ("c5a", 1152, 128), ("c5b", 1280, 128),                  # configs 5a/5b recipes, small
+    ("c5a", 2688, 128),                                      # three tree levels at nb = 128
     ("c3b", 512, 64),                                        # fp16 storage
 ])
 def test_svdvals_matches_oracle(name, n, nb):
