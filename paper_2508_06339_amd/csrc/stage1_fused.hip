@@ -67,11 +67,13 @@ __device__ unsigned long long svb_fused_timing[8];
 // first), so in every NB-row chunk of V and of Y = V T the 16 x 16 blocks below the block
 // diagonal are exactly zero and their products are skipped.
 // USET: the kernel is given the domains' T factors instead of Y (see the header of this file).
-template <typename T, typename C, int NB, int HT, bool LQ, bool TRI, bool USET>
-__global__ __launch_bounds__((FusedGeom<C, NB>::NT), (sizeof(C) == 8 && NB == 128) ? 1 : 2) void update_fused_kernel(T* __restrict__ Cb, int64_t lda, int64_t qlen,
-                                                           const C* __restrict__ V, const C* __restrict__ Y,
-                                                           int64_t ldp, int chunks, int g, int64_t stride,
-                                                           int strips, int total, const C* __restrict__ Tw)
+// FULL: the domain has all HT tiles and the strip all its columns: every count below is a constant
+// and nothing in the stages is predicated.
+template <typename T, typename C, int NB, int HT, bool LQ, bool TRI, bool USET, bool FULL>
+__device__ __forceinline__ void update_fused_body(T* __restrict__ Cb, int64_t lda, int64_t qlen,
+                                                  const C* __restrict__ V, const C* __restrict__ Y,
+                                                  int64_t ldp, int chunks, int g, int64_t stride,
+                                                  const int d, const int strip, const C* __restrict__ Tw)
 {
     using F = Frag<C>;
     using G = FusedGeom<C, NB>;
@@ -82,21 +84,13 @@ __global__ __launch_bounds__((FusedGeom<C, NB>::NT), (sizeof(C) == 8 && NB == 12
     extern __shared__ __align__(16) unsigned char smem_raw[];
     C* smem = reinterpret_cast<C*>(smem_raw);
 
-    // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2): give every
-    // XCD a contiguous range of tiles, so that the workgroups sharing a domain's V and Y
-    // mostly share an L2 as well.
-    const int per = (total + 7) / 8;
-    const int tile = (int)(blockIdx.x % 8) * per + (int)(blockIdx.x / 8);
-    if (tile >= total) return;
-    const int d = tile / strips, strip = tile % strips;
-
-    const int nch = min(g, chunks - d * g);
-    const int ntile = nch * NB / 16;   // 16-row tiles of this domain
-    const int nck = nch * NB / RC;     // slices of this domain
+    const int nch = FULL ? HT * 16 / NB : min(g, chunks - d * g);
+    const int ntile = FULL ? HT : nch * NB / 16;       // 16-row tiles of this domain
+    const int nck = FULL ? NCK : nch * NB / RC;        // slices of this domain
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int i = lane & 15, gq = lane >> 4;
     const int64_t q = (int64_t)strip * G::SW + wave * 16 + i;
-    const bool active = (int64_t)strip * G::SW + wave * 16 < qlen;   // qlen is a multiple of 16
+    const bool active = FULL || (int64_t)strip * G::SW + wave * 16 < qlen;   // qlen is a multiple of 16
     const int64_t prow0 = (int64_t)d * g * NB;                    // first row of the domain in V / Y
 
     // global p index of tile t: chunk (16t / NB) of the domain, offset (16t % NB) inside it
@@ -325,6 +319,31 @@ __global__ __launch_bounds__((FusedGeom<C, NB>::NT), (sizeof(C) == 8 && NB == 12
     }
 }
 #undef FT_MARK
+
+template <typename T, typename C, int NB, int HT, bool LQ, bool TRI, bool USET>
+__global__ __launch_bounds__((FusedGeom<C, NB>::NT), (sizeof(C) == 8 && NB == 128) ? 1 : 2) void update_fused_kernel(T* __restrict__ Cb, int64_t lda, int64_t qlen,
+                                                           const C* __restrict__ V, const C* __restrict__ Y,
+                                                           int64_t ldp, int chunks, int g, int64_t stride,
+                                                           int strips, int total, const C* __restrict__ Tw)
+{
+    // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2): give every
+    // XCD a contiguous range of tiles, so that the workgroups sharing a domain's V and Y
+    // mostly share an L2 as well.
+    const int per = (total + 7) / 8;
+    const int tile = (int)(blockIdx.x % 8) * per + (int)(blockIdx.x / 8);
+    if (tile >= total) return;
+    const int d = tile / strips, strip = tile % strips;
+    // (the predicate-free body exists for the QR orientation, whose accesses are 16-byte vectors;
+    // in the LQ orientation, element by element, it does not fit the registers)
+    if constexpr (!LQ && sizeof(C) == 4) {
+        const bool full = g * NB == HT * 16 && chunks - d * g >= g && (int64_t)(strip + 1) * FusedGeom<C, NB>::SW <= qlen;
+        if (full) {
+            update_fused_body<T, C, NB, HT, LQ, TRI, USET, true>(Cb, lda, qlen, V, Y, ldp, chunks, g, stride, d, strip, Tw);
+            return;
+        }
+    }
+    update_fused_body<T, C, NB, HT, LQ, TRI, USET, false>(Cb, lda, qlen, V, Y, ldp, chunks, g, stride, d, strip, Tw);
+}
 
 template <typename T, typename C, int NB, int HT, bool LQ, bool TRI, bool USET>
 static void launch_fused(T* Cb, int64_t lda, int64_t qlen, const C* V, const C* Y, int64_t ldp, int chunks,
