@@ -19,8 +19,9 @@
  *   - GPU work is ordered after what the HIP stream passed as `stream` (a
  *     hipStream_t cast to void*, NULL = the default stream) holds at the call,
  *     and that stream waits for it: stage 1 runs on two internal streams that
- *     are forked from and joined back to `stream` with events (the panel tree
- *     on one, the updates it overlaps on the other), the rest on `stream`.
+ *     are forked from and joined back to `stream` with events (the first
+ *     level of every panel tree and the updates on one, the tree's upper
+ *     levels beside them on the other), the rest on `stream`.
  *   - Return value: an svb_status.  On SVB_ERR_ARG / SVB_ERR_UNSUPPORTED /
  *     SVB_ERR_WORKSPACE nothing has been read or written.
  *   - dtype: SVB_F64, SVB_F32, and the storage-only types SVB_F16 / SVB_BF16

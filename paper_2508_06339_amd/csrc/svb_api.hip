@@ -365,14 +365,15 @@ void g_la_release() { g_la.release(); }
 // the last one, an LQ half-sweep (panel = block row k right of the diagonal tile, update = the
 // rows below it).  The matrix is rows x cols, rows >= cols, both whole numbers of tiles.
 //
-// Level pipeline: the tree levels of a panel depend on each other only through the R factors, not
-// through the trailing matrix, so once level L of the panel is factored its update U_L can run
-// while level L+1 is being factored.  Two internal streams:
-//     main: P0 P1 .. Pl Ul P0' ..      side: U0 .. Ul-1
-// The last level's update and the next half-sweep's first panel follow the panel tree on the main
-// stream: a dependency that crosses streams costs two to three times what one inside a stream
-// does (measured), and for all but the largest trailing matrices the panel tree is the longer
-// chain of a half-sweep.  (SVB_PIPELINE_LAYOUT=0: every update on the side stream.)
+// Two internal streams.  The tree levels of a panel depend on each other only through the R
+// factors, not through the trailing matrix.  Default (SVB_PIPELINE_LAYOUT=2): the first level's
+// kernel K_A on the main stream, every level above it in one kernel K_B on the side stream, both
+// started behind the previous half-sweep's last update and running side by side (K_B's levels one
+// block step behind the level below, see stage1_panel_blk.hip); every update on the main stream,
+//     main: K_A U0 [K_B done] U1 .. Ul K_A' ..      side: K_B
+// so that a half-sweep costs K_A, its updates and their launch gaps.  Kept for testing: one launch
+// per level, main: P0 P1 .. Pl Ul P0' .., side: U0 .. Ul-1 (=1), or every update on the side
+// stream (=0).
 template <typename T, typename C>
 int ge2gb_pipeline(int64_t rows, int64_t cols, T* A, int64_t lda, int nb, C* band, int64_t ldab,
                    unsigned char* work, const Carve& cv, int g, const Switches& sw, hipStream_t caller)
