@@ -83,7 +83,7 @@ int svb_workspace_bytes(svb_dtype dt, int64_t m, int64_t n, int nb,
  * The tile size that nb = 0 selects for an m x n matrix of type dt (the paper
  * tunes TILESIZE per matrix size and device, Section 4, Table 3), from timings
  * on MI355X, k = min(m, n): f32 arithmetic (SVB_F32, SVB_F16, SVB_BF16): 32 for
- * k < 1024, 64 up to 20480, 128 beyond; SVB_F64: 32 up to 7168, 64 beyond.
+ * k < 1024, 64 up to 26624, 128 beyond; SVB_F64: 32 up to 2560, 64 beyond.
  * Returns 0 for invalid arguments.
  */
 int svb_choose_nb(svb_dtype dt, int64_t m, int64_t n);

@@ -37,9 +37,9 @@ bool nb_ok(int nb) { return nb == 32 || nb == 64 || nb == 128; }
 int choose_nb(svb_dtype dt, int64_t m, int64_t n)
 {
     const int64_t k = m < n ? m : n;
-    if (dt == SVB_F64) return k <= 7168 ? 32 : 64;
+    if (dt == SVB_F64) return k <= 2560 ? 32 : 64;
     if (k < 1024) return 32;
-    return k <= 20480 ? 64 : 128;
+    return k <= 26624 ? 64 : 128;
 }
 
 inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }

@@ -80,7 +80,9 @@ def test_tile_size_choice():
     assert svb.svb_choose_nb(svb.SVB_F32, 8192, 8192) == 64
     assert svb.svb_choose_nb(svb.SVB_F16, 16384, 16384) == 64
     assert svb.svb_choose_nb(svb.SVB_F32, 32768, 40000) == 128
-    assert svb.svb_choose_nb(svb.SVB_F64, 4096, 4096) == 32
+    assert svb.svb_choose_nb(svb.SVB_F64, 2048, 2048) == 32
+    assert svb.svb_choose_nb(svb.SVB_F64, 4096, 4096) == 64
+    assert svb.svb_choose_nb(svb.SVB_F32, 24576, 24576) == 64
     assert svb.svb_choose_nb(svb.SVB_F64, 32768, 32768) == 64
     assert svb.svb_choose_nb(svb.SVB_F32, 100000, 500) == 32     # the smaller dimension decides
     assert svb.svb_choose_nb(svb.SVB_F32, -1, 5) == 0
